@@ -1,0 +1,398 @@
+"""Pins of the CPU oracle against what the paper and the mathematics fix.
+
+None of these tests compares the oracle with itself: expectations come from the
+collectives' plain definitions (brute force over ranks), the paper's Section 2
+walk-through (tests/golden/), closed forms stated in Section 7.1, exact
+rational arithmetic, and the fp32 summation error bound.
+"""
+import bisect
+import os
+from collections import Counter
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+import oracle
+from oracle import numeric, postcond
+from paper_2201_11840_amd import inputs, programs
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+RING_R = (2, 3, 4, 5, 8)
+GRIDS = ((2, 2), (2, 3), (3, 2), (2, 8), (3, 8))
+
+
+def parse(prog):
+    return oracle.parse_program(prog.to_text())
+
+
+def all_programs():
+    out = []
+    for R in RING_R:
+        out += [programs.ring_allreduce(R), programs.ring_allreduce(R, fuse=False),
+                programs.ring_allreduce(R, use_rrs=True), programs.ring_allreduce(R, instances=3),
+                programs.multichannel_ring_allreduce(R, 2), programs.allpairs_allreduce(R),
+                programs.direct_alltoall(R)]
+    for N, G in GRIDS:
+        out += [programs.hierarchical_allreduce(N, G), programs.hierarchical_allreduce(N, G, fuse=False),
+                programs.alltonext(N, G), programs.twostep_alltoall(N, G)]
+    out += [programs.direct_alltoall(1), programs.alltonext(1, 1), programs.alltonext(1, 4),
+            programs.alltonext(4, 1), programs.twostep_alltoall(1, 4), programs.twostep_alltoall(4, 1)]
+    return out
+
+
+# --------------------------------------------------------------------------
+# 1. symbolic runs against the postconditions (Section 3.2)
+# --------------------------------------------------------------------------
+
+@pytest.mark.parametrize("prog", all_programs(), ids=lambda p: p.name + f"_{p.num_ops()}")
+@pytest.mark.parametrize("slots,order", [(2, "round_robin"), (8, "random"), (None, "random")])
+def test_symbolic_postcondition(prog, slots, order):
+    p = parse(prog)
+    bufs, _ = oracle.run_symbolic(p, slots=slots, order=order, seed=17)
+    postcond.check_symbolic(p.collective, p.ranks, p.in_chunks, p.out_chunks, [b["o"] for b in bufs])
+    if p.collective == "alltonext":
+        assert all(c is None for c in bufs[0]["o"])          # rank 0 receives nothing
+        assert all(b["i"][j] == Counter({(r, j): 1}) for r, b in enumerate(bufs) for j in range(p.in_chunks))
+
+
+def test_postcondition_definitions_by_hand():
+    # tiny cases written out by hand, so the brute-force definitions are themselves pinned
+    e = postcond.symbolic_expected("alltoall", 2, 2, 2)
+    assert e[0] == [Counter({(0, 0): 1}), Counter({(1, 0): 1})]
+    assert e[1] == [Counter({(0, 1): 1}), Counter({(1, 1): 1})]
+    e = postcond.symbolic_expected("allreduce", 2, 1, 1)
+    assert e == [[Counter({(0, 0): 1, (1, 0): 1})]] * 2
+    e = postcond.symbolic_expected("alltonext", 3, 1, 1)
+    assert e == [[None], [Counter({(0, 0): 1})], [Counter({(1, 0): 1})]]
+    a = [np.array([1, 2], np.float32), np.array([3, 4], np.float32)]
+    assert [list(x) for x in postcond.alltoall_expected(a)] == [[1, 3], [2, 4]]
+    o = [np.array([9, 9], np.float32)] * 2
+    assert [list(x) for x in postcond.alltonext_expected(a, o)] == [[9, 9], [1, 2]]
+    assert list(postcond.allreduce_sum_f64(a, "f32")) == [4.0, 6.0]
+
+
+# --------------------------------------------------------------------------
+# 2. the Section 2 walk-through (N=2, G=3)
+# --------------------------------------------------------------------------
+
+def _walkthrough_facts():
+    facts = []
+    with open(os.path.join(GOLDEN, "hier_allreduce_2x3_walkthrough.txt")) as f:
+        for line in f:
+            t = line.split("#", 1)[0].split()
+            if t:
+                facts.append((t[0], [int(x) for x in t[1:]]))
+    return facts
+
+
+def test_hierarchical_walkthrough_states():
+    N, G = 2, 3
+    state = {}
+    for ph in (1, 2, 3, 4):
+        p = parse(programs.hierarchical_allreduce(N, G, phases=ph))
+        bufs, _ = oracle.run_symbolic(p, slots=2)
+        state[ph] = [b["i"] for b in bufs]
+    everything = lambda j: Counter({(r, j): 1 for r in range(N * G)})
+    seen = set()
+    for kind, a in _walkthrough_facts():
+        seen.add(kind)
+        if kind == "message":
+            ph, src, dst, first, count = a
+            p = programs.hierarchical_allreduce(N, G, phases=ph)
+            tbs = [t for t in p.tbs[src] if t.chan == ph - 1 and t.send == dst]
+            assert len(tbs) == 1
+            pushes = [o for o in tbs[0].ops if o.opcode in ("send", "rrcs", "rcs", "rrs")]
+            sent = [(o.srcidx if o.opcode != "rcs" else o.dstidx, o.count, o.opcode) for o in pushes]
+            # GPU 1 forwards its own data (send); GPU 2 adds before sending on (fused rrcs)
+            assert (first, count, "send" if src == 1 else "rrcs") in sent
+        elif kind == "holds":
+            ph, gpu, chunk, *who = a
+            assert state[ph][gpu][chunk] == Counter({(r, chunk): 1 for r in who})
+        elif kind == "pair_covers":
+            ph, ga, gb, c0, c1 = a
+            have = {c for g in (ga, gb) for c in (c0, c1) if state[ph][g][c] == everything(c)}
+            assert have == {c0, c1}
+            for g in (ga, gb):
+                assert sum(state[ph][g][c] == everything(c) for c in (c0, c1)) == 1
+        elif kind == "full_one_each":
+            (ph,) = a
+            for g in range(N * G):
+                assert sum(state[ph][g][c] == everything(c) for c in range(N * G)) == 1
+        elif kind == "all_full":
+            (ph,) = a
+            for g in range(N * G):
+                for c in range(N * G):
+                    assert state[ph][g][c] == everything(c)
+        else:
+            raise AssertionError(f"unknown fact {kind}")
+    assert seen == {"message", "holds", "pair_covers", "full_one_each", "all_full"}
+
+
+# --------------------------------------------------------------------------
+# 3. closed forms (Sections 5.1, 7.1.1, 7.1.2)
+# --------------------------------------------------------------------------
+
+@pytest.mark.parametrize("R", RING_R)
+def test_ring_closed_forms(R):
+    fused = programs.ring_allreduce(R)
+    assert all(len(t.ops) == 2 * R - 1 for r in fused.tbs for t in r)
+    assert fused.in_chunks == R                                     # R ranks -> R chunks
+    unf = programs.ring_allreduce(R, fuse=False)
+    assert all(len(t.ops) == 4 * (R - 1) for r in unf.tbs for t in r)
+    for prog in (fused, unf, programs.multichannel_ring_allreduce(R, 3)):
+        _, st = oracle.run_symbolic(parse(prog), slots=2)
+        assert st["comm_steps"] == 2 * R - 2                        # ring: 2R-2 communication steps
+    _, st = oracle.run_symbolic(parse(programs.allpairs_allreduce(R)), slots=2)
+    assert st["comm_steps"] == 2                                    # all pairs: 2 steps
+    _, st = oracle.run_symbolic(parse(programs.direct_alltoall(R)), slots=2)
+    assert st["comm_steps"] == 1                                    # direct alltoall: one step
+    # ring and all pairs exchange the same volume of data (Section 7.1.2)
+    sent = lambda p: sum(o.count for r in p.tbs for t in r for o in t.ops if o.opcode in ("send", "rcs", "rrcs", "rrs"))
+    assert sent(fused) == sent(programs.allpairs_allreduce(R)) == 2 * R * (R - 1)
+
+
+@pytest.mark.parametrize("R,k", [(4, 2), (8, 8), (3, 5)])
+def test_parallelize_instances(R, k):
+    # k instances, each on 1/k of the data, on disjoint channels (Section 5.1)
+    p = programs.ring_allreduce(R, instances=k)
+    assert p.in_chunks == R * k
+    base = programs.ring_allreduce(R)
+    for r in range(R):
+        assert len(p.tbs[r]) == k
+        assert sorted(t.chan for t in p.tbs[r]) == list(range(k))
+        for t in p.tbs[r]:
+            assert [o.opcode for o in t.ops] == [o.opcode for o in base.tbs[r][0].ops]
+            touched = {o.srcidx for o in t.ops if o.srcbuf != "-"} | {o.dstidx for o in t.ops if o.dstbuf != "-"}
+            assert touched == {q * k + t.chan for q in range(R)}    # its own 1/k of every ring chunk
+
+
+def test_algorithmic_byte_totals():
+    # per-instruction traffic in chunk units: send/recv/copy 2, reduce/rrc/rcs/rrs 3, rrcs 4
+    for R in RING_R:
+        assert programs.ring_allreduce(R).algorithmic_chunks() == R * (2 + 4 * (R - 1) + 3 * (R - 2) + 2)
+    assert programs.ring_allreduce(8, instances=8).algorithmic_chunks() == 50 * 64      # 50 S
+    assert programs.hierarchical_allreduce(2, 8).algorithmic_chunks() == 111 * 16       # 111 S
+    assert programs.alltonext(3, 8).algorithmic_chunks() * 2 == 205 * 8                 # 102.5 S
+    assert programs.direct_alltoall(8).algorithmic_chunks() == 8 * 30                   # 30 chunks per rank
+
+
+# --------------------------------------------------------------------------
+# 4. numeric runs against the plain definitions
+# --------------------------------------------------------------------------
+
+def _allreduce_programs():
+    return [programs.ring_allreduce(4), programs.ring_allreduce(4, fuse=False), programs.ring_allreduce(5, use_rrs=True),
+            programs.ring_allreduce(8, instances=8), programs.multichannel_ring_allreduce(5, 2),
+            programs.allpairs_allreduce(4), programs.hierarchical_allreduce(2, 3),
+            programs.hierarchical_allreduce(2, 8), programs.hierarchical_allreduce(3, 2, fuse=False)]
+
+
+@pytest.mark.parametrize("prog", _allreduce_programs(), ids=lambda p: p.name + f"_{p.num_ops()}")
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
+def test_allreduce_integer_values_exact(prog, dtype):
+    p = parse(prog)
+    elems = p.in_chunks * 24
+    ins = inputs.make_inputs(p.ranks, elems, dtype, "int8", 11840)
+    want = postcond.allreduce_sum_f64(ins[::-1], dtype)     # any order: the sums are exact
+    assert np.abs(want).max() <= 8 * p.ranks
+    oracle.run_program(p, ins, None, dtype, slots=2)
+    for r in range(p.ranks):
+        assert np.array_equal(numeric.to_float64(ins[r], dtype), want)
+
+
+@pytest.mark.parametrize("R", [1, 2, 5, 8])
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
+def test_alltoall_bytewise(R, dtype):
+    for prog in ([programs.direct_alltoall(R)] + ([programs.twostep_alltoall(2, R // 2)] if R % 2 == 0 else [])):
+        p = parse(prog)
+        ins = inputs.make_inputs(R, R * 16, dtype, "normal", 21840)
+        outs = inputs.sentinel_outputs(R, R * 16, dtype)
+        want = postcond.alltoall_expected(ins)
+        keep = [a.copy() for a in ins]
+        oracle.run_program(p, ins, outs, dtype, slots=2)
+        for r in range(R):
+            assert outs[r].tobytes() == want[r].tobytes()
+            assert ins[r].tobytes() == keep[r].tobytes()
+
+
+@pytest.mark.parametrize("N,G", [(1, 1), (1, 4), (4, 1), (2, 2), (3, 8)])
+def test_alltonext_bytewise(N, G):
+    p = parse(programs.alltonext(N, G))
+    R = N * G
+    ins = inputs.make_inputs(R, G * 8, "f16", "normal", 51840)
+    outs = inputs.sentinel_outputs(R, G * 8, "f16")
+    want = postcond.alltonext_expected(ins, outs)
+    oracle.run_program(p, ins, outs, "f16", slots=2)
+    for r in range(R):
+        assert outs[r].tobytes() == want[r].tobytes()
+    assert set(outs[0].view(np.uint16)) == {inputs.SENTINEL16}      # rank 0 untouched
+
+
+@pytest.mark.parametrize("prog", [programs.ring_allreduce(8, instances=2), programs.hierarchical_allreduce(2, 8),
+                                  programs.allpairs_allreduce(8)], ids=lambda p: p.name)
+def test_allreduce_fp32_error_bound_and_rank_agreement(prog):
+    p = parse(prog)
+    ins = inputs.make_inputs(p.ranks, p.in_chunks * 64, "f32", "uniform", 31840)
+    exact = postcond.allreduce_sum_f64(ins, "f32")
+    mag = postcond.allreduce_sum_f64([np.abs(a) for a in ins], "f32")
+    oracle.run_program(p, ins, None, "f32", slots=2)
+    # R-1 correctly rounded adds: |err| <= (R-1) * 2^-24 * sum|x| (to first order; 1.01 covers the rest)
+    bound = 1.01 * (p.ranks - 1) * 2.0 ** -24 * mag
+    assert np.all(np.abs(ins[0].astype(np.float64) - exact) <= bound)
+    assert np.any(ins[0].astype(np.float64) != exact)      # it really is an fp32 computation
+    for r in range(1, p.ranks):
+        assert ins[r].tobytes() == ins[0].tobytes()         # every chunk is reduced once, then copied
+
+
+# --------------------------------------------------------------------------
+# 5. invariance: schedule order, FIFO depth, fusion
+# --------------------------------------------------------------------------
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_result_independent_of_order_slots_and_fusion(dtype):
+    results = []
+    for fuse in (True, False):
+        for slots, order, seed in ((2, "round_robin", 0), (8, "random", 1), (None, "random", 2), (3, "random", 3)):
+            p = parse(programs.hierarchical_allreduce(2, 3, fuse=fuse))
+            ins = inputs.make_inputs(p.ranks, p.in_chunks * 32, dtype, "normal", 41840)
+            oracle.run_program(p, ins, None, dtype, slots=slots, order=order, seed=seed)
+            results.append(b"".join(a.tobytes() for a in ins))
+    assert len(set(results)) == 1
+
+
+def test_rrs_leaves_same_final_result():
+    a = inputs.make_inputs(5, 5 * 16, "f32", "uniform", 7)
+    b = [x.copy() for x in a]
+    oracle.run_program(parse(programs.ring_allreduce(5)), a, None, "f32", slots=2)
+    oracle.run_program(parse(programs.ring_allreduce(5, use_rrs=True)), b, None, "f32", slots=2)
+    assert all(x.tobytes() == y.tobytes() for x, y in zip(a, b))
+
+
+# --------------------------------------------------------------------------
+# 6. the 16-bit adds against exact rational arithmetic
+# --------------------------------------------------------------------------
+
+def _all_finite(dtype):
+    bits = np.arange(65536, dtype=np.uint32).astype(np.uint16)
+    with np.errstate(invalid="ignore"):
+        vals = bits.view(np.float16).astype(np.float64) if dtype == "f16" else numeric.bf16_bits_to_f32(bits).astype(np.float64)
+    keep = np.isfinite(vals)
+    return bits[keep], vals[keep]
+
+
+def _round_exact(x: Fraction, sorted_vals, sorted_bits, maxfinite, ulp_top):
+    """Correctly rounded (nearest, ties to even pattern) value of the rational x."""
+    if abs(x) >= Fraction(maxfinite) + Fraction(ulp_top) / 2:
+        return float("inf") if x > 0 else float("-inf")
+    i = bisect.bisect_left(sorted_vals, float(x))
+    best = None
+    for j in range(max(0, i - 2), min(len(sorted_vals), i + 3)):
+        d = abs(Fraction(sorted_vals[j]) - x)
+        key = (d, int(sorted_bits[j]) & 1)          # tie -> even significand
+        if best is None or key < best[0]:
+            best = (key, sorted_vals[j])
+    return best[1]
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+def test_16bit_add_is_correctly_rounded(dtype):
+    bits, vals = _all_finite(dtype)
+    order = np.argsort(vals, kind="stable")
+    svals, sbits = vals[order], bits[order]
+    # drop -0.0 duplicates for the search table (value 0 appears twice)
+    maxfinite = svals[-1]
+    ulp_top = svals[-1] - svals[-2]
+    rng = np.random.Generator(np.random.PCG64(2201))
+    ia = rng.integers(0, len(bits), 3000)
+    ib = rng.integers(0, len(bits), 3000)
+    # near-magnitude pairs (cancellation, ties, subnormal results) and extremes
+    ia2 = rng.integers(0, len(bits), 3000)
+    ib2 = np.clip(ia2 + rng.integers(-40, 41, 3000), 0, len(bits) - 1)
+    A = np.concatenate([bits[ia], sbits[ia2], sbits[-4:], sbits[:4]])
+    B = np.concatenate([bits[ib], sbits[ib2], sbits[-4:], sbits[:4]])
+    if dtype == "f16":
+        got = numeric.add(A.view(np.float16), B.view(np.float16), dtype).astype(np.float64)
+        fa, fb = A.view(np.float16).astype(np.float64), B.view(np.float16).astype(np.float64)
+    else:
+        got = numeric.bf16_bits_to_f32(numeric.add(A, B, dtype)).astype(np.float64)
+        fa, fb = numeric.bf16_bits_to_f32(A).astype(np.float64), numeric.bf16_bits_to_f32(B).astype(np.float64)
+    n_sub = n_tie = 0
+    for x, y, g in zip(fa, fb, got):
+        exact = Fraction(x) + Fraction(y)
+        want = _round_exact(exact, svals, sbits, maxfinite, ulp_top)
+        assert g == want, (x, y, g, want)
+        n_sub += (want != 0 and abs(want) < svals[svals > 0][0] * 1024)
+        n_tie += (np.isfinite(want) and Fraction(want) != exact)
+    assert n_sub > 0 and n_tie > 0      # the sample did exercise subnormal results and rounding
+
+
+def test_bf16_rounding_special_cases():
+    f = lambda x: numeric.f32_to_bf16_bits(np.array([x], np.float32))[0]
+    assert f(1.0) == 0x3F80
+    assert f(np.float32(1.0) + np.float32(2.0 ** -8)) == 0x3F80        # tie -> even (down)
+    assert f(np.float32(1.0) + np.float32(3 * 2.0 ** -8)) == 0x3F82    # tie -> even (up)
+    assert f(np.float32(1.0) + np.float32(2.0 ** -8) + np.float32(2.0 ** -20)) == 0x3F81
+    assert f(np.float32(3.4e38)) == 0x7F80                             # rounds up to +inf
+    assert f(np.float32(-0.0)) == 0x8000
+    assert f(np.float32(np.inf)) == 0x7F80
+    nan = f(np.float32(np.nan))
+    assert (nan & 0x7F80) == 0x7F80 and (nan & 0x7F) != 0
+
+
+# --------------------------------------------------------------------------
+# 7. error handling: deadlocks and malformed programs are reported, never hang
+# --------------------------------------------------------------------------
+
+def test_fused_ring_needs_two_slots():
+    # every rank has sent once; each rrcs needs a free slot and a message at once (Section 6.1:
+    # a schedule with more than s outstanding sends deadlocks)
+    with pytest.raises(oracle.OracleDeadlock):
+        oracle.run_symbolic(parse(programs.ring_allreduce(4)), slots=1)
+    oracle.run_symbolic(parse(programs.ring_allreduce(4, fuse=False)), slots=1)
+
+
+def _two_rank_prog(ops0, ops1, deps_text=""):
+    def tb(ops, peer):
+        return f"tb 0 send {peer} recv {peer} chan 0 ops {len(ops)}\n" + "".join(o + "\n" for o in ops)
+    return ("gc3ir 1\nname t\ncollective custom\ninplace 0\nprotocol simple\nranks 2\nchunks 2 2\n"
+            f"rank 0 scratch 0 tbs 1\n{tb(ops0, 1)}rank 1 scratch 0 tbs 1\n{tb(ops1, 0)}end\n")
+
+
+def test_bad_programs_are_reported():
+    # both ranks receive first: cyclic wait
+    t = _two_rank_prog(["op recv - 0 o 0 1 0 0", "op send i 0 - 0 1 0 0"],
+                       ["op recv - 0 o 0 1 0 0", "op send i 0 - 0 1 0 0"])
+    with pytest.raises(oracle.OracleDeadlock):
+        oracle.run_symbolic(oracle.parse_program(t))
+    # message count mismatch
+    t = _two_rank_prog(["op send i 0 - 0 2 0 0"], ["op recv - 0 o 0 1 0 0"])
+    with pytest.raises(oracle.OracleError):
+        oracle.run_symbolic(oracle.parse_program(t))
+    # a message nobody receives
+    t = _two_rank_prog(["op send i 0 - 0 1 0 0"], [])
+    with pytest.raises(oracle.OracleError):
+        oracle.run_symbolic(oracle.parse_program(t))
+    # reading an uninitialised chunk (Section 3.3)
+    t = _two_rank_prog(["op send o 0 - 0 1 0 0"], ["op recv - 0 o 0 1 0 0"])
+    with pytest.raises(oracle.OracleError):
+        oracle.run_symbolic(oracle.parse_program(t))
+    # dependency on a step that does not exist
+    t = _two_rank_prog(["op copy i 0 o 0 1 0 1 0 7"], [])
+    with pytest.raises(oracle.OracleError):
+        oracle.run_symbolic(oracle.parse_program(t))
+    with pytest.raises(oracle.IRError):
+        oracle.parse_program("gc3ir 1\nranks 1\n")
+    with pytest.raises(oracle.IRError):
+        oracle.parse_program(t.replace("op copy", "op fly"))
+
+
+def test_wrong_schedule_fails_postcondition():
+    # a plausible generator mistake (ring chunk index off by one) must be caught by the postcondition
+    prog = programs.ring_allreduce(4)
+    prog.tbs[2][0].ops[1].srcidx = (prog.tbs[2][0].ops[1].srcidx + 1) % 4
+    p = parse(prog)
+    bufs, _ = oracle.run_symbolic(p, slots=2)
+    with pytest.raises(AssertionError):
+        postcond.check_symbolic("allreduce", 4, 4, 4, [b["o"] for b in bufs])
