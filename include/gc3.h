@@ -1,0 +1,185 @@
+/*
+ * gc3.h - C ABI of the MI355X (gfx950) runtime that executes GC3-IR collective programs.
+ *
+ * The library implements the runtime of the paper's Section 6: programs in GC3-IR (Section 5,
+ * "GC3-IR": GPU programs -> thread blocks -> sequential instruction lists, one send and one
+ * receive connection per thread block, identified with a channel) are parsed and stored in GPU
+ * memory, their point-to-point connections (Section 6.1: remote buffers of s FIFO slots) are set
+ * up, and a collective is executed by one interpreter kernel (Section 6.2) in which every thread
+ * block walks its own instruction list tile by tile.
+ *
+ * The R ranks of a program are VIRTUAL ranks: disjoint buffers in the memory of one GPU.  A
+ * connection is a FIFO in that GPU's memory guarded by flags; no second GPU and no collective
+ * library is involved.
+ *
+ * Conventions
+ *  - Every function returns a gc3_status (0 = success, negative = error) unless stated
+ *    otherwise; nothing throws across this boundary.  gc3_last_error() gives a message for the
+ *    last failure on the calling thread.
+ *  - "host" / "device" says where a pointer must point.  The library never takes ownership of a
+ *    caller's buffer; objects it returns (gc3_program, gc3_comm) are owned by the library and
+ *    released with the matching free / destroy call.
+ *  - Calls on one gc3_comm must not overlap in time (from several threads or streams): the
+ *    FIFOs, flags and semaphores of a communicator are shared by its runs.
+ */
+#ifndef GC3_H
+#define GC3_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct gc3_program gc3_program;
+typedef struct gc3_comm gc3_comm;
+
+typedef enum gc3_status {
+  GC3_OK = 0,
+  GC3_ERR_PARSE = -1,            /* text is not well-formed GC3-IR */
+  GC3_ERR_INVALID_PROGRAM = -2,  /* structurally invalid (see gc3_program_validate) */
+  GC3_ERR_DEADLOCK = -3,         /* cannot complete with the given number of FIFO slots */
+  GC3_ERR_UNBOUND = -4,          /* a rank has no buffers bound */
+  GC3_ERR_SIZE = -5,             /* element count / chunk size / scratch size not acceptable */
+  GC3_ERR_RESIDENCY = -6,        /* the grid cannot be co-resident on the device */
+  GC3_ERR_TIMEOUT = -7,          /* a wait inside the kernel exceeded the spin limit */
+  GC3_ERR_HIP = -8,              /* a HIP runtime call failed */
+  GC3_ERR_ARG = -9,              /* bad argument (null pointer, out-of-range value) */
+  GC3_ERR_POISONED = -10         /* communicator had a failed run; call gc3_comm_reset */
+} gc3_status;
+
+typedef enum gc3_dtype { GC3_F32 = 0, GC3_F16 = 1, GC3_BF16 = 2 } gc3_dtype;
+
+/* The paper's reduction is a point-wise one, "e.g. addition" (Section 3.1); only the sum is built. */
+typedef enum gc3_redop { GC3_SUM = 0 } gc3_redop;
+
+/* Opcodes of Section 4.2 (instruction generation and fusion). */
+typedef enum gc3_opcode {
+  GC3_OP_SEND = 0, GC3_OP_RECV = 1, GC3_OP_COPY = 2, GC3_OP_REDUCE = 3,
+  GC3_OP_RRC = 4, GC3_OP_RCS = 5, GC3_OP_RRCS = 6, GC3_OP_RRS = 7
+} gc3_opcode;
+
+typedef struct gc3_program_info {
+  int32_t ranks;
+  int32_t in_chunks;          /* chunks per rank in the input buffer */
+  int32_t out_chunks;         /* chunks per rank in the output buffer */
+  int32_t inplace;            /* 1: output aliases input (Section 3.2) */
+  int32_t num_tbs;            /* thread blocks, all ranks */
+  int32_t max_tbs_per_rank;
+  int32_t num_connections;    /* distinct (source rank, destination rank, channel) */
+  int32_t num_instructions;
+  int32_t max_count;          /* largest `count` of any instruction (aggregation, Section 5.1) */
+  int32_t max_scratch_chunks; /* largest scratch chunk count of any rank */
+  uint64_t algorithmic_chunks;/* global-memory traffic of one run in units of one chunk:
+                                 count x (send 2, recv 2, copy 2, reduce 3, rrc 3, rcs 3, rrcs 4, rrs 3) */
+} gc3_program_info;
+
+/* Tunables of a communicator.  Zero in any field selects the default. */
+typedef struct gc3_comm_config {
+  int32_t fifo_slots;      /* s of Section 6.1, 1..8; default 4 */
+  int32_t tile_bytes;      /* bytes of one chunk a workgroup moves per tile (Section 6.2, chunk
+                              tiling); multiple of 16, at most 1 MiB; default 32768.  A FIFO slot
+                              holds max_count x tile_bytes. */
+  int32_t team_width;      /* W: workgroups that execute one IR thread block together, workgroup w
+                              owning the w-th 1/W of every chunk with FIFO slots, flags and
+                              semaphore of its own (the runtime applying Section 5.1's
+                              parallelize(W)); 0 = choose so that the grid fills the device */
+  int32_t wg_size;         /* threads per workgroup: 64, 128, 256 or 512; default 256 */
+  int32_t xcd_placement;   /* 0 default (on), 1 on: place the workgroups of connected thread blocks
+                              on one XCD; 2 off: workgroups in program order */
+  int32_t reserved0;
+  uint64_t spin_limit_us;  /* longest a workgroup waits on one flag before the run is abandoned
+                              with GC3_ERR_TIMEOUT; default 10 s */
+} gc3_comm_config;
+
+typedef struct gc3_comm_info {
+  int32_t team_width;        /* W in use */
+  int32_t wg_size;
+  int32_t grid;              /* workgroups launched per run (including idle padding) */
+  int32_t active_wgs;        /* num_tbs x W */
+  int32_t max_resident_wgs;  /* occupancy x compute units */
+  int32_t fifo_slots;
+  int32_t tile_bytes;
+  int32_t slot_bytes;        /* max_count x tile_bytes */
+  uint64_t fifo_bytes;       /* device memory held by all FIFOs */
+  int32_t compute_units;
+  int32_t reserved0;
+} gc3_comm_info;
+
+/* Message for the most recent error on this thread.  host; owned by the library; never null. */
+const char* gc3_last_error(void);
+
+/* ---- programs (Section 5, GC3-IR; Section 6.2 "Initial Setup": programs are parsed at init) ---- */
+
+/* Parse GC3-IR text (`text`: host, `len` bytes, need not be NUL-terminated).  On success *out is
+ * a new program.  The text format is line oriented:
+ *   gc3ir 1 / name T / collective T / inplace 0|1 / protocol T / ranks R / chunks IN OUT
+ *   rank r scratch N tbs K            (ranks in order)
+ *   tb id send P recv Q chan C ops n  (ids in order; -1 = no peer)
+ *   op OPCODE SRCBUF SRCIDX DSTBUF DSTIDX COUNT HASDEP NDEPS {TB STEP}...
+ *   end
+ * with OPCODE in send recv copy reduce rrc rcs rrcs rrs and buffers i, o, s or - (unused).
+ * Errors: GC3_ERR_PARSE, GC3_ERR_ARG. */
+int gc3_program_load(const char* text, size_t len, gc3_program** out);
+
+void gc3_program_free(gc3_program* prog);
+
+/* Check the constraints the paper's compiler guarantees (Section 5 and 5.2): peers in range,
+ * every send-type instruction in a thread block with a send peer (same for receive), one sending
+ * and one receiving thread block per connection, matching message sizes on both ends of a
+ * connection, chunk indices inside the buffers, dependencies on existing steps of the same rank
+ * whose has-dependent flag is set; then execute the program with `fifo_slots` slots per
+ * connection (Section 6.1) to prove it terminates.  `err`/`errlen`: optional host buffer for a
+ * message.  Errors: GC3_ERR_INVALID_PROGRAM, GC3_ERR_DEADLOCK, GC3_ERR_ARG. */
+int gc3_program_validate(const gc3_program* prog, int fifo_slots, char* err, size_t errlen);
+
+int gc3_program_info_get(const gc3_program* prog, gc3_program_info* out);
+
+/* Scratch chunks rank `rank` needs (Section 3.2: deduced from the highest index used). */
+int gc3_program_scratch_chunks(const gc3_program* prog, int rank, int* out);
+
+/* ---- communicators (Section 6.1 connections, Section 6.2 interpreter) ---- */
+
+/* Validate `prog`, allocate its connections' FIFOs, flags and the thread-block semaphores in
+ * device memory of the current HIP device, upload the instruction tables and check that all
+ * workgroups can be resident at once (Section 6.2: all thread blocks must run concurrently).
+ * `cfg` may be null (defaults).  The program may be freed afterwards.
+ * Errors: validation errors, GC3_ERR_RESIDENCY, GC3_ERR_HIP, GC3_ERR_ARG. */
+int gc3_comm_create(const gc3_program* prog, const gc3_comm_config* cfg, gc3_comm** out);
+
+int gc3_comm_info_get(const gc3_comm* comm, gc3_comm_info* out);
+
+/* Bind the three named buffers of one rank (Section 3.1): device pointers, 16-byte aligned,
+ * owned by the caller and alive for every later run.  For an in-place program `output` must be
+ * null or equal `input`.  `scratch` may be null iff the rank uses no scratch chunk;
+ * `scratch_bytes` is its capacity, checked against the run's chunk size.
+ * Errors: GC3_ERR_ARG. */
+int gc3_comm_bind(gc3_comm* comm, int rank, void* input, void* output, void* scratch, size_t scratch_bytes);
+
+/* Run the collective once, asynchronously on `hip_stream` (a hipStream_t, null = default stream).
+ * `elems_per_rank` is the element count of every rank's INPUT buffer; a chunk is
+ * elems_per_rank / in_chunks elements (Section 3.1: the chunk size is known only at run time),
+ * the output buffer holds out_chunks chunks.  The chunk must be a whole number of elements and
+ * of 16-byte units.  elems_per_rank = 0 is a no-op.  Errors: GC3_ERR_UNBOUND, GC3_ERR_SIZE,
+ * GC3_ERR_POISONED, GC3_ERR_HIP, GC3_ERR_ARG.  A GC3_ERR_TIMEOUT inside the kernel is reported by
+ * gc3_comm_status. */
+int gc3_comm_run(gc3_comm* comm, size_t elems_per_rank, gc3_dtype dtype, gc3_redop op, void* hip_stream);
+
+/* Bytes the method loads and stores through global memory in one run of this size:
+ * algorithmic_chunks x chunk bytes. */
+int gc3_comm_algorithmic_bytes(const gc3_comm* comm, size_t elems_per_rank, gc3_dtype dtype, uint64_t* out);
+
+/* Wait for the device and report whether any run since the last reset failed
+ * (GC3_ERR_TIMEOUT; the communicator is then poisoned) or GC3_OK. */
+int gc3_comm_status(gc3_comm* comm);
+
+/* Clear all flags, semaphores and the error state (synchronises the device). */
+int gc3_comm_reset(gc3_comm* comm);
+
+void gc3_comm_destroy(gc3_comm* comm);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GC3_H */

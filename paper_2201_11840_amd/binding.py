@@ -1,0 +1,170 @@
+"""ctypes binding of libgc3.so: the same entry points as include/gc3.h, argument marshalling only.
+
+Every step of the collective runs inside the library's kernels.  There is no fallback: if the
+library has not been built, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "lib", "libgc3.so")
+
+GC3_OK = 0
+GC3_ERR_PARSE = -1
+GC3_ERR_INVALID_PROGRAM = -2
+GC3_ERR_DEADLOCK = -3
+GC3_ERR_UNBOUND = -4
+GC3_ERR_SIZE = -5
+GC3_ERR_RESIDENCY = -6
+GC3_ERR_TIMEOUT = -7
+GC3_ERR_HIP = -8
+GC3_ERR_ARG = -9
+GC3_ERR_POISONED = -10
+
+GC3_F32, GC3_F16, GC3_BF16 = 0, 1, 2
+GC3_SUM = 0
+DTYPE_CODE = {"f32": GC3_F32, "f16": GC3_F16, "bf16": GC3_BF16}
+
+EXPORTS = ("gc3_last_error", "gc3_program_load", "gc3_program_free", "gc3_program_validate",
+           "gc3_program_info_get", "gc3_program_scratch_chunks", "gc3_comm_create", "gc3_comm_info_get",
+           "gc3_comm_bind", "gc3_comm_run", "gc3_comm_algorithmic_bytes", "gc3_comm_status",
+           "gc3_comm_reset", "gc3_comm_destroy")
+
+
+class ProgramInfo(C.Structure):
+    _fields_ = [("ranks", C.c_int32), ("in_chunks", C.c_int32), ("out_chunks", C.c_int32),
+                ("inplace", C.c_int32), ("num_tbs", C.c_int32), ("max_tbs_per_rank", C.c_int32),
+                ("num_connections", C.c_int32), ("num_instructions", C.c_int32), ("max_count", C.c_int32),
+                ("max_scratch_chunks", C.c_int32), ("algorithmic_chunks", C.c_uint64)]
+
+
+class CommConfig(C.Structure):
+    _fields_ = [("fifo_slots", C.c_int32), ("tile_bytes", C.c_int32), ("team_width", C.c_int32),
+                ("wg_size", C.c_int32), ("xcd_placement", C.c_int32), ("reserved0", C.c_int32),
+                ("spin_limit_us", C.c_uint64)]
+
+
+class CommInfo(C.Structure):
+    _fields_ = [("team_width", C.c_int32), ("wg_size", C.c_int32), ("grid", C.c_int32),
+                ("active_wgs", C.c_int32), ("max_resident_wgs", C.c_int32), ("fifo_slots", C.c_int32),
+                ("tile_bytes", C.c_int32), ("slot_bytes", C.c_int32), ("fifo_bytes", C.c_uint64),
+                ("compute_units", C.c_int32), ("reserved0", C.c_int32)]
+
+
+class Gc3Error(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"gc3 status {status}: {message}")
+        self.status = status
+        self.message = message
+
+
+_lib: Optional[C.CDLL] = None
+
+
+def lib() -> C.CDLL:
+    """The loaded library; raises if it has not been built (no fallback path exists)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: run `python __graft_entry__.py build` "
+                               "(or paper_2201_11840_amd.build.build()) first")
+        L = C.CDLL(LIB_PATH)
+        L.gc3_last_error.restype = C.c_char_p
+        L.gc3_last_error.argtypes = []
+        L.gc3_program_load.argtypes = [C.c_char_p, C.c_size_t, C.POINTER(C.c_void_p)]
+        L.gc3_program_free.argtypes = [C.c_void_p]
+        L.gc3_program_free.restype = None
+        L.gc3_program_validate.argtypes = [C.c_void_p, C.c_int, C.c_char_p, C.c_size_t]
+        L.gc3_program_info_get.argtypes = [C.c_void_p, C.POINTER(ProgramInfo)]
+        L.gc3_program_scratch_chunks.argtypes = [C.c_void_p, C.c_int, C.POINTER(C.c_int)]
+        L.gc3_comm_create.argtypes = [C.c_void_p, C.POINTER(CommConfig), C.POINTER(C.c_void_p)]
+        L.gc3_comm_info_get.argtypes = [C.c_void_p, C.POINTER(CommInfo)]
+        L.gc3_comm_bind.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t]
+        L.gc3_comm_run.argtypes = [C.c_void_p, C.c_size_t, C.c_int, C.c_int, C.c_void_p]
+        L.gc3_comm_algorithmic_bytes.argtypes = [C.c_void_p, C.c_size_t, C.c_int, C.POINTER(C.c_uint64)]
+        L.gc3_comm_status.argtypes = [C.c_void_p]
+        L.gc3_comm_reset.argtypes = [C.c_void_p]
+        L.gc3_comm_destroy.argtypes = [C.c_void_p]
+        L.gc3_comm_destroy.restype = None
+        _lib = L
+    return _lib
+
+
+def _check(status: int) -> None:
+    if status != GC3_OK:
+        raise Gc3Error(status, gc3_last_error())
+
+
+def gc3_last_error() -> str:
+    return lib().gc3_last_error().decode()
+
+
+def gc3_program_load(text: str) -> C.c_void_p:
+    raw = text.encode()
+    h = C.c_void_p()
+    _check(lib().gc3_program_load(raw, len(raw), C.byref(h)))
+    return h
+
+
+def gc3_program_free(prog: C.c_void_p) -> None:
+    lib().gc3_program_free(prog)
+
+
+def gc3_program_validate(prog: C.c_void_p, fifo_slots: int) -> None:
+    buf = C.create_string_buffer(512)
+    _check(lib().gc3_program_validate(prog, fifo_slots, buf, len(buf)))
+
+
+def gc3_program_info_get(prog: C.c_void_p) -> ProgramInfo:
+    info = ProgramInfo()
+    _check(lib().gc3_program_info_get(prog, C.byref(info)))
+    return info
+
+
+def gc3_program_scratch_chunks(prog: C.c_void_p, rank: int) -> int:
+    n = C.c_int()
+    _check(lib().gc3_program_scratch_chunks(prog, rank, C.byref(n)))
+    return n.value
+
+
+def gc3_comm_create(prog: C.c_void_p, cfg: Optional[CommConfig] = None) -> C.c_void_p:
+    h = C.c_void_p()
+    _check(lib().gc3_comm_create(prog, C.byref(cfg) if cfg is not None else None, C.byref(h)))
+    return h
+
+
+def gc3_comm_info_get(comm: C.c_void_p) -> CommInfo:
+    info = CommInfo()
+    _check(lib().gc3_comm_info_get(comm, C.byref(info)))
+    return info
+
+
+def gc3_comm_bind(comm: C.c_void_p, rank: int, input_ptr: int, output_ptr: Optional[int],
+                  scratch_ptr: Optional[int], scratch_bytes: int) -> None:
+    _check(lib().gc3_comm_bind(comm, rank, C.c_void_p(input_ptr), C.c_void_p(output_ptr or 0),
+                               C.c_void_p(scratch_ptr or 0), scratch_bytes))
+
+
+def gc3_comm_run(comm: C.c_void_p, elems_per_rank: int, dtype: int, op: int = GC3_SUM, stream: int = 0) -> None:
+    _check(lib().gc3_comm_run(comm, elems_per_rank, dtype, op, C.c_void_p(stream)))
+
+
+def gc3_comm_algorithmic_bytes(comm: C.c_void_p, elems_per_rank: int, dtype: int) -> int:
+    n = C.c_uint64()
+    _check(lib().gc3_comm_algorithmic_bytes(comm, elems_per_rank, dtype, C.byref(n)))
+    return n.value
+
+
+def gc3_comm_status(comm: C.c_void_p) -> None:
+    _check(lib().gc3_comm_status(comm))
+
+
+def gc3_comm_reset(comm: C.c_void_p) -> None:
+    _check(lib().gc3_comm_reset(comm))
+
+
+def gc3_comm_destroy(comm: C.c_void_p) -> None:
+    lib().gc3_comm_destroy(comm)

@@ -1,0 +1,51 @@
+// Device-resident tables of a communicator: the parsed program flattened for the interpreter
+// kernel (Section 6.2, "Instruction Data Structure": step, opcode, source/destination buffer and
+// chunk offset, count, dependency lists, has-dependent flag).
+#pragma once
+#include <cstdint>
+
+namespace gc3 {
+
+constexpr uint32_t kIdleWg = 0xffffffffu;
+constexpr int kFlagStrideWords = 16;  // one 64-bit flag per 128-byte line
+
+struct DInstr {            // 32 bytes
+  uint32_t op;             // gc3_opcode
+  uint32_t srcbuf, dstbuf; // 0 input, 1 output, 2 scratch (3 unused)
+  uint32_t srcidx, dstidx; // chunk index inside the buffer
+  uint32_t count;          // consecutive chunks
+  uint32_t dep_begin;      // first entry in the dependency table
+  uint32_t ndeps_hasdep;   // (number of dependencies << 1) | has-dependent flag
+};
+
+struct DDep {              // 16 bytes
+  uint32_t tb;             // global thread-block index of the dependee
+  uint32_t step;           // its step
+  uint32_t ninstr;         // instruction count of the dependee (semaphore values advance by this per tile)
+  uint32_t pad;
+};
+
+struct DTb {               // 32 bytes
+  uint32_t rank;
+  uint32_t instr_begin, ninstr;
+  int32_t send_conn, recv_conn;  // connection index or -1
+  uint32_t pad[3];
+};
+
+struct KParams {
+  const DTb* tbs;
+  const DInstr* instrs;
+  const DDep* deps;
+  const uint32_t* wgmap;   // per workgroup: global thread-block index * W + lane, or kIdleWg
+  void* const* bufs;       // [rank*3 + buffer] user buffers
+  unsigned char* fifo;     // [(conn*W + lane) * slots + slot] * slot_bytes
+  uint64_t* flags;         // [((conn*W + lane)*2 + {0 tail, 1 head}) * kFlagStrideWords]
+  uint64_t* sems;          // [(tb*W + lane) * kFlagStrideWords]
+  uint32_t* error;         // 0 = fine, else a gc3_status (negated) set by the first failing workgroup
+  uint64_t run_base;       // run number << 32; all flag values of this run lie above it
+  uint64_t chunk_bytes;
+  uint64_t spin_limit_ticks;  // of the 100 MHz wall clock
+  uint32_t W, slots, tile_bytes, slot_bytes;
+};
+
+}  // namespace gc3

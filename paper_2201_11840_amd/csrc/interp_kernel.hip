@@ -1,0 +1,284 @@
+// The GC3-IR interpreter kernel for gfx950 (Section 6.2 of the paper, figure "GC3 interpreter").
+//
+// One workgroup executes one lane of one IR thread block: it walks that thread block's
+// instruction list once per tile (outer loop = chunk tiling, inner loop = instructions), waits
+// for the instruction's cross-thread-block dependencies and FIFO slots, moves one tile of each of
+// the instruction's chunks with 128-bit accesses, then publishes FIFO flags and its semaphore.
+//
+// A thread block is run by a team of W workgroups; lane w owns the w-th 1/W of every chunk and
+// has FIFO slots, flags and a semaphore of its own, so lanes never synchronise with each other.
+// All instructions are element-wise, hence this is Section 5.1's parallelize(W) applied by the
+// runtime: values and reduction order are those of the program.
+//
+// Flag protocol (Section 6.1, remote buffers with s slots).  All flags are 64-bit and only grow:
+// value = run_base + n, where run_base = run number << 32.
+//   tail[conn, lane]  written by the sender:   messages published in this run
+//   head[conn, lane]  written by the receiver: messages consumed in this run
+//   sem[tb, lane]     written by the thread block: tile * ninstr + step + 1 of the latest
+//                     instruction with dependents that it finished (the listing in the paper
+//                     stores the bare step; the tile term and the +1 make the value monotone and
+//                     distinguish "step 0 done" from the initial 0)
+// A sender waits for head >= run_base + k + 1 - s before its k-th push (k >= s), a receiver for
+// tail >= run_base + k + 1 before its k-th pop.  Publishing is: workgroup barrier, then one
+// thread issues an agent-scope release fence and relaxed stores; waiting is relaxed agent-scope
+// loads by the first wavefront, an agent-scope acquire fence, then a workgroup barrier.
+#include <hip/hip_runtime.h>
+
+#include "device_tables.h"
+#include "gc3.h"
+
+namespace gc3 {
+
+namespace {
+
+constexpr int kUnroll = 4;
+
+typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float float2_t __attribute__((ext_vector_type(2)));
+
+template <int DT>
+__device__ __forceinline__ uint32_t add_word(uint32_t a, uint32_t b);
+
+template <>
+__device__ __forceinline__ uint32_t add_word<GC3_F32>(uint32_t a, uint32_t b) {
+  return __float_as_uint(__uint_as_float(a) + __uint_as_float(b));
+}
+// two fp16 values per word: one correctly rounded add each (round to nearest even, subnormals kept)
+template <>
+__device__ __forceinline__ uint32_t add_word<GC3_F16>(uint32_t a, uint32_t b) {
+  half2_t x = __builtin_bit_cast(half2_t, a), y = __builtin_bit_cast(half2_t, b);
+  return __builtin_bit_cast(uint32_t, (half2_t)(x + y));
+}
+// two bf16 values per word: widen to fp32 (exact), add, round to nearest even back to bf16
+template <>
+__device__ __forceinline__ uint32_t add_word<GC3_BF16>(uint32_t a, uint32_t b) {
+  float2_t x, y;
+  x.x = __uint_as_float(a << 16);
+  x.y = __uint_as_float(a & 0xffff0000u);
+  y.x = __uint_as_float(b << 16);
+  y.y = __uint_as_float(b & 0xffff0000u);
+  float2_t s = x + y;
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(s, bf16x2_t));
+}
+
+template <int DT>
+__device__ __forceinline__ uint4 add_vec(uint4 a, uint4 b) {
+  uint4 r;
+  r.x = add_word<DT>(a.x, b.x);
+  r.y = add_word<DT>(a.y, b.y);
+  r.z = add_word<DT>(a.z, b.z);
+  r.w = add_word<DT>(a.w, b.w);
+  return r;
+}
+
+// out0[i] (and out1[i]) = in0[i] (+ in1[i]) for i in [0, nvec), 16 bytes per element.  Element i is
+// always handled by thread i mod nthreads, so a location is touched by the same thread in every
+// instruction of a thread block.
+template <bool IN1, bool OUT0, bool OUT1, int DT>
+__device__ __forceinline__ void move_tile(const uint4* in0, const uint4* in1, uint4* out0, uint4* out1,
+                                          uint32_t nvec, uint32_t tid, uint32_t nthreads) {
+  const uint32_t step = nthreads * kUnroll;
+  const uint32_t full = nvec - nvec % step;
+  for (uint32_t base = tid; base < full; base += step) {
+    uint4 a[kUnroll], b[kUnroll];
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) a[u] = in0[base + u * nthreads];
+    if (IN1) {
+#pragma unroll
+      for (int u = 0; u < kUnroll; ++u) b[u] = in1[base + u * nthreads];
+#pragma unroll
+      for (int u = 0; u < kUnroll; ++u) a[u] = add_vec<DT>(a[u], b[u]);
+    }
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+      if (OUT0) out0[base + u * nthreads] = a[u];
+      if (OUT1) out1[base + u * nthreads] = a[u];
+    }
+  }
+  if (full < nvec) {
+    uint4 a[kUnroll], b[kUnroll];
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+      uint32_t i = full + tid + u * nthreads;
+      if (i < nvec) {
+        a[u] = in0[i];
+        if (IN1) b[u] = in1[i];
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+      uint32_t i = full + tid + u * nthreads;
+      if (i < nvec) {
+        uint4 v = IN1 ? add_vec<DT>(a[u], b[u]) : a[u];
+        if (OUT0) out0[i] = v;
+        if (OUT1) out1[i] = v;
+      }
+    }
+  }
+}
+
+__device__ __forceinline__ uint64_t load_flag(const uint64_t* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void store_flag(uint64_t* p, uint64_t v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// First byte of lane w's share of a chunk of U 16-byte units split over W lanes.  Shares are cut at
+// 256-byte boundaries when every lane can get at least that much.
+__device__ __forceinline__ uint64_t lane_begin(uint64_t U, uint32_t w, uint32_t W) {
+  if (w >= W) return U << 4;
+  if (U >= 16ull * W) return (((U >> 4) * w) / W) << 8;
+  return ((U * w) / W) << 4;
+}
+
+}  // namespace
+
+template <int DT>
+__global__ void __launch_bounds__(512) gc3_interpreter(KParams p) {
+  __shared__ int s_ok[2];
+  const uint32_t tid = threadIdx.x, nthreads = blockDim.x;
+  const uint32_t m = p.wgmap[blockIdx.x];
+  if (m == kIdleWg) return;
+  const uint32_t W = p.W;
+  const uint32_t tbi = m / W, lane = m % W;
+  const DTb tb = p.tbs[tbi];
+
+  const uint64_t U = p.chunk_bytes >> 4;
+  const uint64_t off0 = lane_begin(U, lane, W);
+  const uint64_t share = lane_begin(U, lane + 1, W) - off0;
+  const uint32_t tile = p.tile_bytes;
+  const uint32_t ntiles = (uint32_t)((share + tile - 1) / tile);
+
+  uint64_t* const tail_send = tb.send_conn >= 0 ? p.flags + ((uint64_t)(tb.send_conn * W + lane) * 2 + 0) * kFlagStrideWords : nullptr;
+  uint64_t* const head_send = tb.send_conn >= 0 ? p.flags + ((uint64_t)(tb.send_conn * W + lane) * 2 + 1) * kFlagStrideWords : nullptr;
+  uint64_t* const tail_recv = tb.recv_conn >= 0 ? p.flags + ((uint64_t)(tb.recv_conn * W + lane) * 2 + 0) * kFlagStrideWords : nullptr;
+  uint64_t* const head_recv = tb.recv_conn >= 0 ? p.flags + ((uint64_t)(tb.recv_conn * W + lane) * 2 + 1) * kFlagStrideWords : nullptr;
+  unsigned char* const fifo_send = tb.send_conn >= 0 ? p.fifo + (uint64_t)(tb.send_conn * W + lane) * p.slots * p.slot_bytes : nullptr;
+  unsigned char* const fifo_recv = tb.recv_conn >= 0 ? p.fifo + (uint64_t)(tb.recv_conn * W + lane) * p.slots * p.slot_bytes : nullptr;
+  uint64_t* const my_sem = p.sems + (uint64_t)(tbi * W + lane) * kFlagStrideWords;
+
+  uint32_t send_seq = 0, recv_seq = 0, phase = 0;
+
+  for (uint32_t t = 0; t < ntiles; ++t) {                      // chunk tiling (outermost loop)
+    const uint64_t toff = (uint64_t)t * tile;
+    const uint32_t len = (uint32_t)(share - toff < tile ? share - toff : tile);   // bytes of this tile, per chunk
+    const uint32_t nvec = len >> 4;
+    for (uint32_t s = 0; s < tb.ninstr; ++s) {                 // instruction loop
+      const DInstr ins = p.instrs[tb.instr_begin + s];
+      const uint32_t op = ins.op;
+      const bool pops = op == GC3_OP_RECV || op == GC3_OP_RRC || op == GC3_OP_RCS || op == GC3_OP_RRCS || op == GC3_OP_RRS;
+      const bool pushes = op == GC3_OP_SEND || op == GC3_OP_RCS || op == GC3_OP_RRCS || op == GC3_OP_RRS;
+      const uint32_t ndeps = ins.ndeps_hasdep >> 1;
+      const bool hasdep = ins.ndeps_hasdep & 1;
+      const bool wait_slot = pushes && send_seq >= p.slots;
+
+      // ---- wait for dependencies, for a message, for a free slot -------------------------------
+      if (pops || wait_slot || ndeps) {
+        if (tid < 64) {
+          bool ok = true;
+          const uint32_t total = 2 + ndeps;
+          for (uint32_t it0 = 0; it0 < total && ok; it0 += 64) {
+            const uint32_t it = it0 + tid;
+            const uint64_t* ptr = nullptr;
+            uint64_t want = 0;
+            if (it == 0) {
+              if (pops) { ptr = tail_recv; want = p.run_base + recv_seq + 1; }
+            } else if (it == 1) {
+              if (wait_slot) { ptr = head_send; want = p.run_base + send_seq + 1 - p.slots; }
+            } else if (it < total) {
+              const DDep d = p.deps[ins.dep_begin + it - 2];
+              ptr = p.sems + (uint64_t)(d.tb * W + lane) * kFlagStrideWords;
+              want = p.run_base + (uint64_t)t * d.ninstr + d.step + 1;
+            }
+            bool pending = ptr != nullptr;
+            const uint64_t start = wall_clock64();
+            uint32_t spins = 0;
+            for (;;) {
+              if (pending && load_flag(ptr) >= want) pending = false;
+              if (!__any(pending)) break;
+              __builtin_amdgcn_s_sleep(1);
+              if ((++spins & 255u) == 0) {
+                if (__hip_atomic_load(p.error, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) { ok = false; break; }
+                if (wall_clock64() - start > p.spin_limit_ticks) {
+                  atomicCAS(p.error, 0u, (uint32_t)(-GC3_ERR_TIMEOUT));
+                  ok = false;
+                  break;
+                }
+              }
+            }
+          }
+          __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+          if (tid == 0) s_ok[phase & 1] = ok ? 1 : 0;
+        }
+        __syncthreads();
+        const int ok_all = s_ok[phase & 1];
+        ++phase;
+        if (!ok_all) return;     // the run is abandoned; every workgroup leaves the same way
+      }
+
+      // ---- move the tile ----------------------------------------------------------------------
+      const uint64_t coff = off0 + toff;   // byte offset inside each chunk
+      unsigned char* const srcb = ins.srcbuf < 3 ? (unsigned char*)p.bufs[tb.rank * 3 + ins.srcbuf] + (uint64_t)ins.srcidx * p.chunk_bytes + coff : nullptr;
+      unsigned char* const dstb = ins.dstbuf < 3 ? (unsigned char*)p.bufs[tb.rank * 3 + ins.dstbuf] + (uint64_t)ins.dstidx * p.chunk_bytes + coff : nullptr;
+      unsigned char* const rslot = pops ? fifo_recv + (uint64_t)(recv_seq % p.slots) * p.slot_bytes : nullptr;
+      unsigned char* const sslot = pushes ? fifo_send + (uint64_t)(send_seq % p.slots) * p.slot_bytes : nullptr;
+      for (uint32_t j = 0; j < ins.count; ++j) {
+        const uint4* src = (const uint4*)(srcb + (uint64_t)j * p.chunk_bytes);
+        uint4* dst = (uint4*)(dstb + (uint64_t)j * p.chunk_bytes);
+        const uint4* rs = (const uint4*)(rslot + (uint64_t)j * len);
+        uint4* ss = (uint4*)(sslot + (uint64_t)j * len);
+        switch (op) {
+          case GC3_OP_SEND:   move_tile<false, true, false, DT>(src, nullptr, ss, nullptr, nvec, tid, nthreads); break;
+          case GC3_OP_RECV:   move_tile<false, true, false, DT>(rs, nullptr, dst, nullptr, nvec, tid, nthreads); break;
+          case GC3_OP_COPY:   move_tile<false, true, false, DT>(src, nullptr, dst, nullptr, nvec, tid, nthreads); break;
+          case GC3_OP_REDUCE: move_tile<true, true, false, DT>(dst, src, dst, nullptr, nvec, tid, nthreads); break;
+          case GC3_OP_RRC:    move_tile<true, true, false, DT>(rs, src, dst, nullptr, nvec, tid, nthreads); break;
+          case GC3_OP_RCS:    move_tile<false, true, true, DT>(rs, nullptr, dst, ss, nvec, tid, nthreads); break;
+          case GC3_OP_RRCS:   move_tile<true, true, true, DT>(rs, src, dst, ss, nvec, tid, nthreads); break;
+          case GC3_OP_RRS:    move_tile<true, true, false, DT>(rs, src, ss, nullptr, nvec, tid, nthreads); break;
+          default: break;
+        }
+      }
+
+      // ---- publish: slot filled, slot freed, semaphore ------------------------------------------
+      if (pushes) ++send_seq;
+      if (pops) ++recv_seq;
+      if (pushes || pops || hasdep) {
+        __syncthreads();
+        if (tid == 0) {
+          __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+          if (pushes) store_flag(tail_send, p.run_base + send_seq);
+          if (pops) store_flag(head_recv, p.run_base + recv_seq);
+          if (hasdep) store_flag(my_sem, p.run_base + (uint64_t)t * tb.ninstr + s + 1);
+        }
+      }
+    }
+  }
+}
+
+// Host-callable launcher; returns the hipError_t of the launch.
+int launch_interpreter(int dtype, unsigned grid, unsigned block, void* stream, const KParams& p) {
+  hipStream_t st = (hipStream_t)stream;
+  switch (dtype) {
+    case GC3_F32: hipLaunchKernelGGL(gc3_interpreter<GC3_F32>, dim3(grid), dim3(block), 0, st, p); break;
+    case GC3_F16: hipLaunchKernelGGL(gc3_interpreter<GC3_F16>, dim3(grid), dim3(block), 0, st, p); break;
+    case GC3_BF16: hipLaunchKernelGGL(gc3_interpreter<GC3_BF16>, dim3(grid), dim3(block), 0, st, p); break;
+    default: return (int)hipErrorInvalidValue;
+  }
+  return (int)hipGetLastError();
+}
+
+// Occupancy of the interpreter (workgroups of `block` threads per compute unit), minimum over dtypes.
+int interpreter_occupancy(unsigned block, int* out) {
+  int a = 0, b = 0, c = 0;
+  hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&a, gc3_interpreter<GC3_F32>, (int)block, 0);
+  if (e == hipSuccess) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&b, gc3_interpreter<GC3_F16>, (int)block, 0);
+  if (e == hipSuccess) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&c, gc3_interpreter<GC3_BF16>, (int)block, 0);
+  if (e != hipSuccess) return (int)e;
+  *out = a < b ? (a < c ? a : c) : (b < c ? b : c);
+  return 0;
+}
+
+}  // namespace gc3

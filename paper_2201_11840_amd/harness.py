@@ -1,0 +1,117 @@
+"""Device-memory plumbing around the C-ABI: PyTorch supplies buffers and streams, nothing else.
+
+`Collective` owns one communicator and the per-rank device buffers (raw byte tensors) of one
+workload; `run()` is a single gc3_comm_run on torch's current stream.
+"""
+from __future__ import annotations
+
+from typing import List, Optional, Sequence
+
+import numpy as np
+import torch
+
+from . import binding as B
+from .inputs import ITEMSIZE, SENTINEL16, STORAGE
+
+
+def make_config(fifo_slots: int = 0, tile_bytes: int = 0, team_width: int = 0, wg_size: int = 0,
+                xcd_placement: int = 0, spin_limit_us: int = 0) -> B.CommConfig:
+    return B.CommConfig(fifo_slots, tile_bytes, team_width, wg_size, xcd_placement, 0, spin_limit_us)
+
+
+class Collective:
+    def __init__(self, ir_text: str, dtype: str, elems_per_rank: int, cfg: Optional[B.CommConfig] = None,
+                 device: str = "cuda:0"):
+        if not torch.cuda.is_available():
+            raise RuntimeError("no GPU: the GC3 runtime has no CPU path")
+        self.device = torch.device(device)
+        torch.cuda.set_device(self.device)
+        self.dtype = dtype
+        self.code = B.DTYPE_CODE[dtype]
+        self.elems = elems_per_rank
+        prog = B.gc3_program_load(ir_text)
+        try:
+            self.pinfo = B.gc3_program_info_get(prog)
+            self.scratch_chunks = [B.gc3_program_scratch_chunks(prog, r) for r in range(self.pinfo.ranks)]
+            self.comm = B.gc3_comm_create(prog, cfg)
+        finally:
+            B.gc3_program_free(prog)
+        self.info = B.gc3_comm_info_get(self.comm)
+        self.ranks = self.pinfo.ranks
+        self.inplace = bool(self.pinfo.inplace)
+        es = ITEMSIZE[dtype]
+        if elems_per_rank % self.pinfo.in_chunks:
+            raise ValueError("elems_per_rank must be a multiple of the program's chunk count")
+        self.chunk_bytes = elems_per_rank // self.pinfo.in_chunks * es
+        in_bytes = elems_per_rank * es
+        out_bytes = self.chunk_bytes * self.pinfo.out_chunks
+        alloc = lambda n: torch.empty(max(n, 16), dtype=torch.uint8, device=self.device)
+        self.inputs = [alloc(in_bytes) for _ in range(self.ranks)]
+        self.outputs = self.inputs if self.inplace else [alloc(out_bytes) for _ in range(self.ranks)]
+        self.scratch = [alloc(self.scratch_chunks[r] * self.chunk_bytes) if self.scratch_chunks[r] else None
+                        for r in range(self.ranks)]
+        self.in_bytes, self.out_bytes = in_bytes, out_bytes
+        for r in range(self.ranks):
+            s = self.scratch[r]
+            B.gc3_comm_bind(self.comm, r, self.inputs[r].data_ptr(),
+                            None if self.inplace else self.outputs[r].data_ptr(),
+                            s.data_ptr() if s is not None else None,
+                            self.scratch_chunks[r] * self.chunk_bytes)
+        self.algorithmic_bytes = (B.gc3_comm_algorithmic_bytes(self.comm, elems_per_rank, self.code)
+                                  if elems_per_rank else 0)
+
+    def resize(self, elems_per_rank: int) -> None:
+        """Use a smaller element count on the same communicator and buffers."""
+        es = ITEMSIZE[self.dtype]
+        if elems_per_rank % self.pinfo.in_chunks:
+            raise ValueError("elems_per_rank must be a multiple of the program's chunk count")
+        cb = elems_per_rank // self.pinfo.in_chunks * es
+        if elems_per_rank * es > self.inputs[0].numel() or cb * self.pinfo.out_chunks > self.outputs[0].numel():
+            raise ValueError("larger than the buffers this object allocated")
+        self.elems, self.chunk_bytes = elems_per_rank, cb
+        self.in_bytes, self.out_bytes = elems_per_rank * es, cb * self.pinfo.out_chunks
+        self.algorithmic_bytes = (B.gc3_comm_algorithmic_bytes(self.comm, elems_per_rank, self.code)
+                                  if elems_per_rank else 0)
+
+    # -- data movement between host arrays and the device buffers (not part of the collective) --
+    def upload(self, inputs: Sequence[np.ndarray], outputs: Optional[Sequence[np.ndarray]] = None) -> None:
+        for r in range(self.ranks):
+            if self.in_bytes:
+                self.inputs[r][:self.in_bytes].copy_(torch.from_numpy(inputs[r].view(np.uint8)))
+            if outputs is not None and not self.inplace and self.out_bytes:
+                self.outputs[r][:self.out_bytes].copy_(torch.from_numpy(outputs[r].view(np.uint8)))
+        torch.cuda.synchronize()
+
+    def fill_outputs_with_sentinel(self) -> None:
+        if self.inplace:
+            return
+        for r in range(self.ranks):
+            self.outputs[r].view(torch.int16).fill_(SENTINEL16)
+        torch.cuda.synchronize()
+
+    def download(self, which: str = "out") -> List[np.ndarray]:
+        torch.cuda.synchronize()
+        bufs, n = (self.outputs, self.out_bytes) if which == "out" else (self.inputs, self.in_bytes)
+        st = STORAGE[self.dtype]
+        return [b[:n].cpu().numpy().view(st).copy() for b in bufs]
+
+    def run(self) -> None:
+        """One collective, asynchronous on torch's current stream."""
+        B.gc3_comm_run(self.comm, self.elems, self.code, B.GC3_SUM, torch.cuda.current_stream().cuda_stream)
+
+    def status(self) -> None:
+        B.gc3_comm_status(self.comm)
+
+    def reset(self) -> None:
+        B.gc3_comm_reset(self.comm)
+
+    def close(self) -> None:
+        if getattr(self, "comm", None) is not None:
+            B.gc3_comm_destroy(self.comm)
+            self.comm = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

@@ -1,0 +1,283 @@
+"""GPU parity: the HIP interpreter (through the C ABI) against the CPU oracle, element by element.
+
+Tolerances: copy-only and integer-valued data bit-exact; fp32 bit-exact (the reduction order is the
+program's); fp16 / bf16 within 1e-3 relative (+1e-5 of the largest magnitude as an absolute floor for
+sums near zero) - and, because both sides perform one correctly rounded add per hop in the same
+order, they are additionally expected to agree bitwise, which is asserted too.
+"""
+import numpy as np
+import pytest
+
+import oracle
+from oracle import numeric, postcond
+from paper_2201_11840_amd import inputs, programs, workloads
+
+pytestmark = pytest.mark.gpu
+
+
+def _harness():
+    from paper_2201_11840_amd import harness
+    return harness
+
+
+def compare(got, want, dtype, exact_only=False):
+    g64, w64 = numeric.to_float64(got, dtype), numeric.to_float64(want, dtype)
+    if dtype == "f32" or exact_only:
+        assert got.tobytes() == want.tobytes(), f"{np.count_nonzero(got != want)} of {got.size} elements differ"
+        return
+    tol = 1e-3 * np.abs(w64) + 1e-5 * (np.abs(w64).max() if w64.size else 0.0)
+    assert np.all(np.abs(g64 - w64) <= tol), f"max err {np.abs(g64 - w64).max()}"
+    assert got.tobytes() == want.tobytes(), f"within tolerance but {np.count_nonzero(got != want)} elements not bitwise equal"
+
+
+def run_case(prog, dtype, elems, dist="normal", seed=1234, cfg=None, repeats=1, exact_only=False):
+    """Run `prog` on the GPU and in the oracle on the same seeded inputs; compare every output element
+    of every rank (and the inputs of out-of-place programs, which must be untouched)."""
+    H = _harness()
+    text = prog.to_text()
+    p = oracle.parse_program(text)
+    ins = inputs.make_inputs(p.ranks, elems, dtype, dist, seed)
+    out_elems = elems // p.in_chunks * p.out_chunks
+    outs = None if p.inplace else inputs.sentinel_outputs(p.ranks, out_elems, dtype)
+    coll = H.Collective(text, dtype, elems, cfg)
+    try:
+        want_in = [a.copy() for a in ins]
+        want_out = None if p.inplace else [a.copy() for a in outs]
+        oracle.run_program(p, want_in, want_out, dtype, slots=coll.info.fifo_slots)
+        for _ in range(repeats):
+            coll.upload(ins, outs)
+            coll.run()
+            coll.status()
+            got_out = coll.download("out")
+            for r in range(p.ranks):
+                compare(got_out[r], (want_in if p.inplace else want_out)[r], dtype, exact_only)
+            if not p.inplace:
+                got_in = coll.download("in")
+                for r in range(p.ranks):
+                    assert got_in[r].tobytes() == ins[r].tobytes()
+    finally:
+        coll.close()
+
+
+def small_cfg(**kw):
+    H = _harness()
+    base = dict(fifo_slots=2, tile_bytes=1024, team_width=3)
+    base.update(kw)
+    return H.make_config(**base)
+
+
+# ---- the tiny-R grid, small tiles so that every run spans several tiles and a ragged tail ----------
+
+@pytest.mark.parametrize("R", [2, 3, 4, 5, 8])
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
+def test_ring_allreduce_grid(R, dtype):
+    elems = R * 2500 * (1 if dtype == "f32" else 2)       # chunk = 10000 bytes: 3 lanes, ragged tiles
+    run_case(programs.ring_allreduce(R), dtype, elems, "normal", 100 + R, small_cfg())
+    run_case(programs.ring_allreduce(R, fuse=False), dtype, elems, "uniform", 200 + R, small_cfg(fifo_slots=1))
+    run_case(programs.ring_allreduce(R, use_rrs=True), dtype, elems, "normal", 300 + R, small_cfg(team_width=1))
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_allreduce_variants(dtype):
+    m = 1 if dtype == "f32" else 2
+    run_case(programs.ring_allreduce(4, instances=3), dtype, 12 * 1000 * m, "normal", 1, small_cfg())
+    run_case(programs.multichannel_ring_allreduce(5, 3), dtype, 5 * 1000 * m, "normal", 2, small_cfg())
+    run_case(programs.allpairs_allreduce(4), dtype, 4 * 1000 * m, "normal", 3, small_cfg())
+    run_case(programs.allpairs_allreduce(8), dtype, 8 * 1000 * m, "uniform", 4, small_cfg(team_width=2))
+
+
+@pytest.mark.parametrize("N,G", [(2, 2), (2, 3), (3, 2), (2, 8), (3, 8)])
+def test_hierarchical_allreduce_grid(N, G):
+    # cross-thread-block semaphores, count = N aggregated chunks
+    run_case(programs.hierarchical_allreduce(N, G), "bf16", N * G * 2000, "normal", 41, small_cfg())
+    run_case(programs.hierarchical_allreduce(N, G, fuse=False), "f32", N * G * 1000, "uniform", 42, small_cfg(team_width=2))
+
+
+@pytest.mark.parametrize("R", [1, 2, 3, 8])
+def test_direct_alltoall_grid(R):
+    run_case(programs.direct_alltoall(R), "f16", R * 5000, "normal", 21, small_cfg(), exact_only=True)
+
+
+@pytest.mark.parametrize("N,G", [(1, 4), (4, 1), (2, 3), (3, 8)])
+def test_twostep_alltoall_and_alltonext_grid(N, G):
+    # 3 x 8 has 216 / 396 thread blocks: keep the grid within what the device holds at once
+    wide = 1 if N * G > 8 else 3
+    run_case(programs.twostep_alltoall(N, G), "f16", N * G * 1000, "normal", 22, small_cfg(team_width=wide), exact_only=True)
+    run_case(programs.alltonext(N, G), "f16", G * 5000, "normal", 51, small_cfg(team_width=min(wide, 2)), exact_only=True)
+
+
+# ---- edge cases ------------------------------------------------------------------------------------
+
+def test_smallest_chunk_and_more_lanes_than_units():
+    # chunk = 16 bytes (one unit): lanes beyond the first own nothing and must stay consistent
+    run_case(programs.ring_allreduce(4), "f32", 16, "int8", 5, small_cfg(team_width=4))
+    run_case(programs.hierarchical_allreduce(2, 2), "f16", 4 * 8, "int8", 6, small_cfg(team_width=5))
+    run_case(programs.direct_alltoall(3), "bf16", 3 * 8 * 3, "normal", 7, small_cfg(team_width=2), exact_only=True)
+
+
+def test_empty_input_is_a_noop():
+    H = _harness()
+    coll = H.Collective(programs.ring_allreduce(4).to_text(), "f32", 0)
+    coll.run()
+    coll.status()
+    coll.close()
+
+
+def test_largest_tile_and_slot_settings():
+    # tile_bytes at its maximum (1 MiB), 8 slots, 512-thread workgroups, placement off
+    cfg = _harness().make_config(fifo_slots=8, tile_bytes=1 << 20, team_width=1, wg_size=512, xcd_placement=2)
+    run_case(programs.ring_allreduce(3), "f32", 3 * (3 << 18) + 3 * 4, "uniform", 8, cfg)   # chunk = 3 MiB + 16 B
+    cfg = _harness().make_config(fifo_slots=8, tile_bytes=16, team_width=1, wg_size=64)
+    run_case(programs.ring_allreduce(3), "f32", 3 * 100, "uniform", 9, cfg)                 # 25 tiles of one unit
+
+
+def test_repeated_runs_and_changing_sizes_on_one_communicator():
+    # flags and semaphores only grow: a second and third run reuse them without clearing
+    H = _harness()
+    prog = programs.hierarchical_allreduce(2, 3)
+    text = prog.to_text()
+    p = oracle.parse_program(text)
+    coll = H.Collective(text, "f32", 6 * 12000, small_cfg())
+    for elems in (6 * 4000, 6 * 40, 6 * 12000, 6 * 4):
+        coll.resize(elems)
+        ins = inputs.make_inputs(6, elems, "f32", "uniform", elems)
+        want = [a.copy() for a in ins]
+        oracle.run_program(p, want, None, "f32", slots=2)
+        for _ in range(3):
+            coll.upload(ins)
+            coll.run()
+            coll.status()
+            for g, w in zip(coll.download(), want):
+                assert g.tobytes() == w.tobytes()
+    coll.close()
+    run_case(prog, "f32", 6 * 4000, "uniform", 77, small_cfg(), repeats=4)
+
+
+def test_api_errors_without_launch():
+    H = _harness()
+    from paper_2201_11840_amd import binding as B
+    coll = H.Collective(programs.ring_allreduce(4).to_text(), "f32", 64)
+    with pytest.raises(B.Gc3Error) as e:
+        B.gc3_comm_run(coll.comm, 66, B.GC3_F32)          # not a multiple of the chunk count
+    assert e.value.status == B.GC3_ERR_SIZE
+    with pytest.raises(B.Gc3Error) as e:
+        B.gc3_comm_run(coll.comm, 4 * 2, B.GC3_F32)       # chunk of 8 bytes: not a 16-byte unit
+    assert e.value.status == B.GC3_ERR_SIZE
+    with pytest.raises(B.Gc3Error) as e:
+        B.gc3_comm_bind(coll.comm, 0, coll.inputs[0].data_ptr(), coll.inputs[1].data_ptr(), None, 0)
+    assert e.value.status == B.GC3_ERR_ARG                # in-place program with a different output
+    coll.close()
+    prog = B.gc3_program_load(programs.direct_alltoall(2).to_text())
+    comm = B.gc3_comm_create(prog)
+    B.gc3_program_free(prog)
+    with pytest.raises(B.Gc3Error) as e:
+        B.gc3_comm_run(comm, 64, B.GC3_F16)
+    assert e.value.status == B.GC3_ERR_UNBOUND
+    B.gc3_comm_destroy(comm)
+    # a program that cannot be resident: 396 thread blocks x 64 lanes
+    prog = B.gc3_program_load(programs.alltonext(3, 8).to_text())
+    with pytest.raises(B.Gc3Error) as e:
+        B.gc3_comm_create(prog, H.make_config(team_width=64, wg_size=512))
+    assert e.value.status == B.GC3_ERR_RESIDENCY
+    with pytest.raises(B.Gc3Error) as e:
+        B.gc3_comm_create(prog, H.make_config(fifo_slots=9))
+    assert e.value.status == B.GC3_ERR_ARG
+    B.gc3_program_free(prog)
+    prog = B.gc3_program_load(programs.ring_allreduce(4).to_text())
+    with pytest.raises(B.Gc3Error) as e:
+        B.gc3_comm_create(prog, H.make_config(fifo_slots=1))     # fused ring needs two slots
+    assert e.value.status == B.GC3_ERR_DEADLOCK
+    B.gc3_program_free(prog)
+
+
+# ---- the benchmark configurations, default launch configuration -------------------------------------
+
+def _sampled_case(w, n_samples, seed):
+    """Full-size GPU run checked on sampled element positions.  Every instruction is element-wise and
+    treats all chunks alike, so element e of every chunk depends only on element e of other chunks:
+    the oracle run on the gathered positions gives exactly the values the full run must hold there."""
+    H = _harness()
+    prog = w.build()
+    text = prog.to_text()
+    p = oracle.parse_program(text)
+    elems = w.elems_per_rank
+    ce = elems // p.in_chunks
+    ins = inputs.make_inputs(p.ranks, elems, w.dtype, w.dist, w.seed)
+    coll = H.Collective(text, w.dtype, elems)
+    try:
+        coll.upload(ins)
+        coll.run()
+        coll.status()
+        got = coll.download("out")
+    finally:
+        coll.close()
+    rng = np.random.Generator(np.random.PCG64(seed))
+    lane = ce // max(coll.info.team_width, 1)
+    edges = [0, 1, ce - 1, ce - 2, lane - 1, lane, lane + 1, 2 * lane - 1, 2 * lane, ce // 2]
+    pos = np.unique(np.clip(np.concatenate([rng.integers(0, ce, n_samples), np.array(edges)]), 0, ce - 1))
+    gather = lambda a, nchunks: a.reshape(nchunks, ce)[:, pos].reshape(-1).copy()
+    small_in = [gather(a, p.in_chunks) for a in ins]
+    oracle.run_program(p, small_in, None, w.dtype, slots=coll.info.fifo_slots)
+    for r in range(p.ranks):
+        compare(gather(got[r], p.out_chunks), small_in[r], w.dtype)
+    # and a property that holds at any size: all ranks of an AllReduce agree bitwise
+    for r in range(1, p.ranks):
+        assert got[r].tobytes() == got[0].tobytes()
+
+
+def test_config1_ring_allreduce_r4():
+    w = workloads.ring_ar_r4()
+    run_case(w.build(), w.dtype, w.elems_per_rank, w.dist, w.seed, exact_only=True)
+    run_case(programs.ring_allreduce(4, fuse=False), w.dtype, w.elems_per_rank, w.dist, w.seed, exact_only=True)
+    # integer-valued data: also equal to the plain sum over ranks
+    ins = inputs.make_inputs(4, w.elems_per_rank, "f32", "int8", w.seed)
+    H = _harness()
+    coll = H.Collective(w.build().to_text(), "f32", w.elems_per_rank)
+    coll.upload(ins)
+    coll.run()
+    coll.status()
+    want = postcond.allreduce_sum_f64(ins, "f32")
+    for g in coll.download():
+        assert np.array_equal(g.astype(np.float64), want)
+    coll.close()
+
+
+def test_config2_direct_alltoall_r8():
+    w = workloads.direct_a2a_r8()
+    run_case(w.build(), w.dtype, w.elems_per_rank, w.dist, w.seed, exact_only=True)
+
+
+@pytest.mark.parametrize("mib", [1, 16, 64])
+def test_config3_ring_allreduce_r8_x8(mib):
+    w = workloads.ring_ar_r8x8(mib)
+    run_case(w.build(), w.dtype, w.elems_per_rank, w.dist, w.seed)
+
+
+def test_config3_ring_allreduce_r8_x8_256MiB_sampled():
+    _sampled_case(workloads.ring_ar_r8x8(256), 20000, 3)
+
+
+def test_config4_hierarchical_allreduce_2x8():
+    run_case(workloads.hier_ar_2x8(4).build(), "bf16", workloads.hier_ar_2x8(4).elems_per_rank, "normal", 41840)
+    _sampled_case(workloads.hier_ar_2x8(64), 20000, 4)
+
+
+def test_config5_alltonext_3x8():
+    w = workloads.alltonext_3x8()
+    H = _harness()
+    prog = w.build()
+    ins = inputs.make_inputs(24, w.elems_per_rank, w.dtype, w.dist, w.seed)
+    coll = H.Collective(prog.to_text(), w.dtype, w.elems_per_rank)
+    try:
+        coll.fill_outputs_with_sentinel()
+        coll.upload(ins)
+        coll.run()
+        coll.status()
+        got = coll.download("out")
+    finally:
+        coll.close()
+    assert set(np.unique(got[0].view(np.uint16))) == {inputs.SENTINEL16}       # rank 0 receives nothing
+    for r in range(1, 24):
+        assert got[r].tobytes() == ins[r - 1].tobytes()                      # out[i+1] == in[i], bytewise
+    # the oracle on a smaller buffer of the same program, element by element
+    run_case(prog, w.dtype, 8 * 65536, w.dist, w.seed, exact_only=True)
