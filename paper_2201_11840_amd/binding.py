@@ -10,7 +10,8 @@ import os
 from typing import Optional
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "lib", "libgc3.so")
+# GC3_LIB_PATH selects another build of the same library (a tuning variant); there is no other path.
+LIB_PATH = os.environ.get("GC3_LIB_PATH") or os.path.join(_HERE, "lib", "libgc3.so")
 
 GC3_OK = 0
 GC3_ERR_PARSE = -1

@@ -3,6 +3,7 @@ from __future__ import annotations
 
 import os
 import subprocess
+from typing import Optional, Sequence
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
@@ -12,15 +13,17 @@ LIB_PATH = os.path.join(LIB_DIR, "libgc3.so")
 SOURCES = ["program.cpp", "comm.cpp", "interp_kernel.hip"]
 
 
-def build(verbose: bool = False) -> str:
-    """Compile every source for gfx950 and link libgc3.so; returns its path."""
+def build(verbose: bool = False, defines: Sequence[str] = (), out: Optional[str] = None) -> str:
+    """Compile every source for gfx950 and link libgc3.so; returns its path.
+    `defines` (e.g. ["GC3_FENCE_MODE=0"]) and `out` build a tuning variant elsewhere."""
     os.makedirs(LIB_DIR, exist_ok=True)
+    out = out or LIB_PATH
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     cmd = [hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
            "-Wall", "-Wno-unused-command-line-argument",
            "-I", os.path.join(ROOT, "include"), "-I", CSRC,
-           "-o", LIB_PATH] + [os.path.join(CSRC, s) for s in SOURCES]
+           "-o", out] + [f"-D{d}" for d in defines] + [os.path.join(CSRC, s) for s in SOURCES]
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, capture_output=True, text=True)
@@ -28,7 +31,7 @@ def build(verbose: bool = False) -> str:
         raise RuntimeError("hipcc failed:\n" + res.stdout + res.stderr)
     if verbose and res.stderr:
         print(res.stderr)
-    return LIB_PATH
+    return out
 
 
 if __name__ == "__main__":

@@ -62,9 +62,11 @@ __device__ __forceinline__ uint32_t add_word<GC3_BF16>(uint32_t a, uint32_t b) {
   return __builtin_bit_cast(uint32_t, __builtin_convertvector(s, bf16x2_t));
 }
 
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
 template <int DT>
-__device__ __forceinline__ uint4 add_vec(uint4 a, uint4 b) {
-  uint4 r;
+__device__ __forceinline__ u32x4 add_vec(u32x4 a, u32x4 b) {
+  u32x4 r;
   r.x = add_word<DT>(a.x, b.x);
   r.y = add_word<DT>(a.y, b.y);
   r.z = add_word<DT>(a.z, b.z);
@@ -72,48 +74,60 @@ __device__ __forceinline__ uint4 add_vec(uint4 a, uint4 b) {
   return r;
 }
 
+// Cache policy of a 128-bit access (the sc0 / nt / sc1 bits of gfx950 buffer instructions).
+// Payload that another workgroup, possibly on another die with its own L2, reads or wrote goes
+// through device-scope accesses (sc1): stores are written through, loads do not hit stale lines.
+constexpr int kPolPlain = 0, kPolSc0 = 1, kPolNt = 2, kPolSc1 = 16;
+#ifndef GC3_POL_SLOT_LD
+#define GC3_POL_SLOT_LD (kPolSc1)
+#endif
+#ifndef GC3_POL_SLOT_ST
+#define GC3_POL_SLOT_ST (kPolSc1)
+#endif
+#ifndef GC3_POL_USER_LD
+#define GC3_POL_USER_LD (kPolPlain)
+#endif
+#ifndef GC3_POL_USER_ST
+#define GC3_POL_USER_ST (kPolPlain)
+#endif
+// 0: every wait ends with a device-scope acquire fence and every publish starts with a device-scope
+//    release fence (L2 write-back / invalidate).  1: FIFO payload relies on its per-access policy;
+//    the fences are issued only around semaphores, which order plain user-buffer accesses.
+#ifndef GC3_FENCE_MODE
+#define GC3_FENCE_MODE 1
+#endif
+
+typedef __amdgpu_buffer_rsrc_t rsrc_t;
+
+// Buffer descriptor over [base, base + bytes): accesses beyond it are dropped by the hardware
+// (loads return 0), which also makes the ragged last sweep of a tile safe without predicates.
+__device__ __forceinline__ rsrc_t make_rsrc(const void* base, uint32_t bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)bytes, 0x00020000);
+}
+
 // out0[i] (and out1[i]) = in0[i] (+ in1[i]) for i in [0, nvec), 16 bytes per element.  Element i is
 // always handled by thread i mod nthreads, so a location is touched by the same thread in every
 // instruction of a thread block.
-template <bool IN1, bool OUT0, bool OUT1, int DT>
-__device__ __forceinline__ void move_tile(const uint4* in0, const uint4* in1, uint4* out0, uint4* out1,
+template <bool IN1, bool OUT1, int DT, int P_IN0, int P_IN1, int P_OUT0, int P_OUT1>
+__device__ __forceinline__ void move_tile(rsrc_t in0, rsrc_t in1, rsrc_t out0, rsrc_t out1,
                                           uint32_t nvec, uint32_t tid, uint32_t nthreads) {
   const uint32_t step = nthreads * kUnroll;
-  const uint32_t full = nvec - nvec % step;
-  for (uint32_t base = tid; base < full; base += step) {
-    uint4 a[kUnroll], b[kUnroll];
+  for (uint32_t base = tid; base < nvec; base += step) {
+    u32x4 a[kUnroll], b[kUnroll];
 #pragma unroll
-    for (int u = 0; u < kUnroll; ++u) a[u] = in0[base + u * nthreads];
+    for (int u = 0; u < kUnroll; ++u)
+      a[u] = __builtin_amdgcn_raw_buffer_load_b128(in0, (base + u * nthreads) << 4, 0, P_IN0);
     if (IN1) {
 #pragma unroll
-      for (int u = 0; u < kUnroll; ++u) b[u] = in1[base + u * nthreads];
+      for (int u = 0; u < kUnroll; ++u)
+        b[u] = __builtin_amdgcn_raw_buffer_load_b128(in1, (base + u * nthreads) << 4, 0, P_IN1);
 #pragma unroll
       for (int u = 0; u < kUnroll; ++u) a[u] = add_vec<DT>(a[u], b[u]);
     }
 #pragma unroll
     for (int u = 0; u < kUnroll; ++u) {
-      if (OUT0) out0[base + u * nthreads] = a[u];
-      if (OUT1) out1[base + u * nthreads] = a[u];
-    }
-  }
-  if (full < nvec) {
-    uint4 a[kUnroll], b[kUnroll];
-#pragma unroll
-    for (int u = 0; u < kUnroll; ++u) {
-      uint32_t i = full + tid + u * nthreads;
-      if (i < nvec) {
-        a[u] = in0[i];
-        if (IN1) b[u] = in1[i];
-      }
-    }
-#pragma unroll
-    for (int u = 0; u < kUnroll; ++u) {
-      uint32_t i = full + tid + u * nthreads;
-      if (i < nvec) {
-        uint4 v = IN1 ? add_vec<DT>(a[u], b[u]) : a[u];
-        if (OUT0) out0[i] = v;
-        if (OUT1) out1[i] = v;
-      }
+      __builtin_amdgcn_raw_buffer_store_b128(a[u], out0, (base + u * nthreads) << 4, 0, P_OUT0);
+      if (OUT1) __builtin_amdgcn_raw_buffer_store_b128(a[u], out1, (base + u * nthreads) << 4, 0, P_OUT1);
     }
   }
 }
@@ -209,7 +223,7 @@ __global__ void __launch_bounds__(512) gc3_interpreter(KParams p) {
               }
             }
           }
-          __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+          if (GC3_FENCE_MODE == 0 || ndeps) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
           if (tid == 0) s_ok[phase & 1] = ok ? 1 : 0;
         }
         __syncthreads();
@@ -224,20 +238,21 @@ __global__ void __launch_bounds__(512) gc3_interpreter(KParams p) {
       unsigned char* const dstb = ins.dstbuf < 3 ? (unsigned char*)p.bufs[tb.rank * 3 + ins.dstbuf] + (uint64_t)ins.dstidx * p.chunk_bytes + coff : nullptr;
       unsigned char* const rslot = pops ? fifo_recv + (uint64_t)(recv_seq % p.slots) * p.slot_bytes : nullptr;
       unsigned char* const sslot = pushes ? fifo_send + (uint64_t)(send_seq % p.slots) * p.slot_bytes : nullptr;
+      constexpr int UL = GC3_POL_USER_LD, US = GC3_POL_USER_ST, SL = GC3_POL_SLOT_LD, SS = GC3_POL_SLOT_ST;
       for (uint32_t j = 0; j < ins.count; ++j) {
-        const uint4* src = (const uint4*)(srcb + (uint64_t)j * p.chunk_bytes);
-        uint4* dst = (uint4*)(dstb + (uint64_t)j * p.chunk_bytes);
-        const uint4* rs = (const uint4*)(rslot + (uint64_t)j * len);
-        uint4* ss = (uint4*)(sslot + (uint64_t)j * len);
+        const rsrc_t src = make_rsrc(srcb + (uint64_t)j * p.chunk_bytes, srcb ? len : 0);
+        const rsrc_t dst = make_rsrc(dstb + (uint64_t)j * p.chunk_bytes, dstb ? len : 0);
+        const rsrc_t rs = make_rsrc(rslot + (uint64_t)j * len, rslot ? len : 0);
+        const rsrc_t ss = make_rsrc(sslot + (uint64_t)j * len, sslot ? len : 0);
         switch (op) {
-          case GC3_OP_SEND:   move_tile<false, true, false, DT>(src, nullptr, ss, nullptr, nvec, tid, nthreads); break;
-          case GC3_OP_RECV:   move_tile<false, true, false, DT>(rs, nullptr, dst, nullptr, nvec, tid, nthreads); break;
-          case GC3_OP_COPY:   move_tile<false, true, false, DT>(src, nullptr, dst, nullptr, nvec, tid, nthreads); break;
-          case GC3_OP_REDUCE: move_tile<true, true, false, DT>(dst, src, dst, nullptr, nvec, tid, nthreads); break;
-          case GC3_OP_RRC:    move_tile<true, true, false, DT>(rs, src, dst, nullptr, nvec, tid, nthreads); break;
-          case GC3_OP_RCS:    move_tile<false, true, true, DT>(rs, nullptr, dst, ss, nvec, tid, nthreads); break;
-          case GC3_OP_RRCS:   move_tile<true, true, true, DT>(rs, src, dst, ss, nvec, tid, nthreads); break;
-          case GC3_OP_RRS:    move_tile<true, true, false, DT>(rs, src, ss, nullptr, nvec, tid, nthreads); break;
+          case GC3_OP_SEND:   move_tile<false, false, DT, UL, 0, SS, 0>(src, src, ss, ss, nvec, tid, nthreads); break;
+          case GC3_OP_RECV:   move_tile<false, false, DT, SL, 0, US, 0>(rs, rs, dst, dst, nvec, tid, nthreads); break;
+          case GC3_OP_COPY:   move_tile<false, false, DT, UL, 0, US, 0>(src, src, dst, dst, nvec, tid, nthreads); break;
+          case GC3_OP_REDUCE: move_tile<true, false, DT, UL, UL, US, 0>(dst, src, dst, dst, nvec, tid, nthreads); break;
+          case GC3_OP_RRC:    move_tile<true, false, DT, SL, UL, US, 0>(rs, src, dst, dst, nvec, tid, nthreads); break;
+          case GC3_OP_RCS:    move_tile<false, true, DT, SL, 0, US, SS>(rs, rs, dst, ss, nvec, tid, nthreads); break;
+          case GC3_OP_RRCS:   move_tile<true, true, DT, SL, UL, US, SS>(rs, src, dst, ss, nvec, tid, nthreads); break;
+          case GC3_OP_RRS:    move_tile<true, false, DT, SL, UL, SS, 0>(rs, src, ss, ss, nvec, tid, nthreads); break;
           default: break;
         }
       }
@@ -248,7 +263,7 @@ __global__ void __launch_bounds__(512) gc3_interpreter(KParams p) {
       if (pushes || pops || hasdep) {
         __syncthreads();
         if (tid == 0) {
-          __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+          if (GC3_FENCE_MODE == 0 || hasdep) __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
           if (pushes) store_flag(tail_send, p.run_base + send_seq);
           if (pops) store_flag(head_recv, p.run_base + recv_seq);
           if (hasdep) store_flag(my_sem, p.run_base + (uint64_t)t * tb.ninstr + s + 1);

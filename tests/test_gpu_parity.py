@@ -153,6 +153,32 @@ def test_repeated_runs_and_changing_sizes_on_one_communicator():
     run_case(prog, "f32", 6 * 4000, "uniform", 77, small_cfg(), repeats=4)
 
 
+@pytest.mark.parametrize("prog", [programs.ring_allreduce(8, instances=8), programs.hierarchical_allreduce(2, 8),
+                                  programs.alltonext(3, 8)], ids=lambda p: p.name)
+def test_fresh_data_every_run_on_one_communicator(prog):
+    # FIFO slots are reused run after run: a receiver that saw an old copy of a slot would return
+    # the previous run's data, so every run gets different inputs
+    H = _harness()
+    text = prog.to_text()
+    p = oracle.parse_program(text)
+    elems = p.in_chunks * 8192
+    coll = H.Collective(text, "f32", elems)
+    try:
+        for it in range(6):
+            ins = inputs.make_inputs(p.ranks, elems, "f32", "uniform", 9000 + 100 * it)
+            outs = None if p.inplace else inputs.sentinel_outputs(p.ranks, elems // p.in_chunks * p.out_chunks, "f32")
+            want_in = [a.copy() for a in ins]
+            want_out = None if p.inplace else [a.copy() for a in outs]
+            oracle.run_program(p, want_in, want_out, "f32", slots=coll.info.fifo_slots)
+            coll.upload(ins, outs)
+            coll.run()
+            coll.status()
+            for g, w in zip(coll.download("out"), want_in if p.inplace else want_out):
+                assert g.tobytes() == w.tobytes(), f"run {it}"
+    finally:
+        coll.close()
+
+
 def test_api_errors_without_launch():
     H = _harness()
     from paper_2201_11840_amd import binding as B
