@@ -15,7 +15,7 @@
 #include "program.h"
 
 namespace gc3 {
-int launch_interpreter(int dtype, unsigned grid, unsigned block, void* stream, const KParams& p);
+int launch_interpreter(int dtype, bool coherent_user, unsigned grid, unsigned block, void* stream, const KParams& p);
 int interpreter_occupancy(unsigned block, int* out);
 }  // namespace gc3
 
@@ -41,6 +41,7 @@ struct gc3_comm {
   int device = 0;
   int32_t ranks = 0, in_chunks = 0, out_chunks = 0;
   bool inplace = false;
+  bool has_deps = false;  // some instruction waits on another thread block's semaphore
   uint64_t algorithmic_chunks = 0;
   std::vector<int32_t> scratch_chunks;
   gc3_comm_info info{};
@@ -202,8 +203,9 @@ int gc3_comm_create(const gc3_program* prog, const gc3_comm_config* cfg_in, gc3_
   const long resident = (long)occ * cus;
   int W = cfg.team_width;
   if (W == 0) {
-    // fill the device with about two workgroups per compute unit, but never beyond residency
-    long target = std::min<long>(2L * cus, resident);
+    // about four workgroups per compute unit (enough bytes in flight to cover memory latency),
+    // never beyond residency
+    long target = std::min<long>(4L * cus, resident);
     W = (int)std::max<long>(1, std::min<long>(64, target / ntb));
   }
   const long active = (long)ntb * W;
@@ -276,6 +278,7 @@ int gc3_comm_create(const gc3_program* prog, const gc3_comm_config* cfg_in, gc3_
   c->out_chunks = prog->inplace ? prog->in_chunks : prog->out_chunks;
   c->inplace = prog->inplace;
   c->algorithmic_chunks = alg_chunks;
+  c->has_deps = !deps.empty();
   for (int r = 0; r < R; ++r) c->scratch_chunks.push_back(prog->rank[r].scratch_chunks);
   c->bufs.assign((size_t)R * 3, nullptr);
   c->scratch_bytes.assign(R, 0);
@@ -386,7 +389,7 @@ int gc3_comm_run(gc3_comm* comm, size_t elems_per_rank, gc3_dtype dtype, gc3_red
   p.slots = (uint32_t)comm->info.fifo_slots;
   p.tile_bytes = (uint32_t)comm->info.tile_bytes;
   p.slot_bytes = (uint32_t)comm->info.slot_bytes;
-  int e = launch_interpreter((int)dtype, (unsigned)comm->info.grid, (unsigned)comm->info.wg_size, hip_stream, p);
+  int e = launch_interpreter((int)dtype, comm->has_deps, (unsigned)comm->info.grid, (unsigned)comm->info.wg_size, hip_stream, p);
   if (e != 0) return hip_fail((hipError_t)e, "interpreter launch");
   return GC3_OK;
 }

@@ -19,9 +19,10 @@
 //                     stores the bare step; the tile term and the +1 make the value monotone and
 //                     distinguish "step 0 done" from the initial 0)
 // A sender waits for head >= run_base + k + 1 - s before its k-th push (k >= s), a receiver for
-// tail >= run_base + k + 1 before its k-th pop.  Publishing is: workgroup barrier, then one
-// thread issues an agent-scope release fence and relaxed stores; waiting is relaxed agent-scope
-// loads by the first wavefront, an agent-scope acquire fence, then a workgroup barrier.
+// tail >= run_base + k + 1 before its k-th pop.  Publishing is: workgroup barrier (every wavefront
+// first waits until its device-scope stores have completed), then one thread stores the flags with
+// relaxed agent-scope atomics; waiting is relaxed agent-scope loads by the first wavefront, then a
+// workgroup barrier, then device-scope loads of the payload.
 #include <hip/hip_runtime.h>
 
 #include "device_tables.h"
@@ -31,7 +32,7 @@ namespace gc3 {
 
 namespace {
 
-constexpr int kUnroll = 4;
+
 
 typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
@@ -74,9 +75,15 @@ __device__ __forceinline__ u32x4 add_vec(u32x4 a, u32x4 b) {
   return r;
 }
 
-// Cache policy of a 128-bit access (the sc0 / nt / sc1 bits of gfx950 buffer instructions).
-// Payload that another workgroup, possibly on another die with its own L2, reads or wrote goes
-// through device-scope accesses (sc1): stores are written through, loads do not hit stale lines.
+// Cache policy of a 128-bit access: the sc0 / nt / sc1 bits of gfx950 buffer instructions.
+// MI355X has one L2 per die (XCD) and these L2s are not kept coherent with each other, so data that a
+// workgroup on another die wrote, or will read, must not be served from / parked in the local L2:
+//   sc1 (device scope) store: written through, complete at device scope when its counter retires;
+//   sc1 load: never served from a stale line.
+// FIFO payload always moves with sc1.  User buffers are streamed once (nt = non-temporal); they need
+// device scope only in programs with cross-thread-block dependencies, where one workgroup reads
+// chunks another one wrote in the same run (template parameter COH).  With these policies no bulk L2
+// write-back / invalidate (agent-scope fence) is needed anywhere in the kernel.
 constexpr int kPolPlain = 0, kPolSc0 = 1, kPolNt = 2, kPolSc1 = 16;
 #ifndef GC3_POL_SLOT_LD
 #define GC3_POL_SLOT_LD (kPolSc1)
@@ -85,16 +92,24 @@ constexpr int kPolPlain = 0, kPolSc0 = 1, kPolNt = 2, kPolSc1 = 16;
 #define GC3_POL_SLOT_ST (kPolSc1)
 #endif
 #ifndef GC3_POL_USER_LD
-#define GC3_POL_USER_LD (kPolPlain)
+#define GC3_POL_USER_LD (kPolNt)
 #endif
 #ifndef GC3_POL_USER_ST
-#define GC3_POL_USER_ST (kPolPlain)
+#define GC3_POL_USER_ST (kPolSc1)
 #endif
-// 0: every wait ends with a device-scope acquire fence and every publish starts with a device-scope
-//    release fence (L2 write-back / invalidate).  1: FIFO payload relies on its per-access policy;
-//    the fences are issued only around semaphores, which order plain user-buffer accesses.
-#ifndef GC3_FENCE_MODE
-#define GC3_FENCE_MODE 1
+#ifndef GC3_POL_USER_LD_COH
+#define GC3_POL_USER_LD_COH (kPolSc1 | kPolNt)
+#endif
+#ifndef GC3_POL_USER_ST_COH
+#define GC3_POL_USER_ST_COH (kPolSc1 | kPolNt)
+#endif
+// 1 = conservative build for A/B measurements: every wait ends with an agent-scope acquire fence and
+// every publish starts with an agent-scope release fence (bulk L2 invalidate / write-back).
+#ifndef GC3_CONSERVATIVE_FENCES
+#define GC3_CONSERVATIVE_FENCES 0
+#endif
+#ifndef GC3_UNROLL
+#define GC3_UNROLL 4
 #endif
 
 typedef __amdgpu_buffer_rsrc_t rsrc_t;
@@ -111,21 +126,21 @@ __device__ __forceinline__ rsrc_t make_rsrc(const void* base, uint32_t bytes) {
 template <bool IN1, bool OUT1, int DT, int P_IN0, int P_IN1, int P_OUT0, int P_OUT1>
 __device__ __forceinline__ void move_tile(rsrc_t in0, rsrc_t in1, rsrc_t out0, rsrc_t out1,
                                           uint32_t nvec, uint32_t tid, uint32_t nthreads) {
-  const uint32_t step = nthreads * kUnroll;
+  const uint32_t step = nthreads * GC3_UNROLL;
   for (uint32_t base = tid; base < nvec; base += step) {
-    u32x4 a[kUnroll], b[kUnroll];
+    u32x4 a[GC3_UNROLL], b[GC3_UNROLL];
 #pragma unroll
-    for (int u = 0; u < kUnroll; ++u)
+    for (int u = 0; u < GC3_UNROLL; ++u)
       a[u] = __builtin_amdgcn_raw_buffer_load_b128(in0, (base + u * nthreads) << 4, 0, P_IN0);
     if (IN1) {
 #pragma unroll
-      for (int u = 0; u < kUnroll; ++u)
+      for (int u = 0; u < GC3_UNROLL; ++u)
         b[u] = __builtin_amdgcn_raw_buffer_load_b128(in1, (base + u * nthreads) << 4, 0, P_IN1);
 #pragma unroll
-      for (int u = 0; u < kUnroll; ++u) a[u] = add_vec<DT>(a[u], b[u]);
+      for (int u = 0; u < GC3_UNROLL; ++u) a[u] = add_vec<DT>(a[u], b[u]);
     }
 #pragma unroll
-    for (int u = 0; u < kUnroll; ++u) {
+    for (int u = 0; u < GC3_UNROLL; ++u) {
       __builtin_amdgcn_raw_buffer_store_b128(a[u], out0, (base + u * nthreads) << 4, 0, P_OUT0);
       if (OUT1) __builtin_amdgcn_raw_buffer_store_b128(a[u], out1, (base + u * nthreads) << 4, 0, P_OUT1);
     }
@@ -149,7 +164,7 @@ __device__ __forceinline__ uint64_t lane_begin(uint64_t U, uint32_t w, uint32_t 
 
 }  // namespace
 
-template <int DT>
+template <int DT, bool COH>
 __global__ void __launch_bounds__(512) gc3_interpreter(KParams p) {
   __shared__ int s_ok[2];
   const uint32_t tid = threadIdx.x, nthreads = blockDim.x;
@@ -223,7 +238,7 @@ __global__ void __launch_bounds__(512) gc3_interpreter(KParams p) {
               }
             }
           }
-          if (GC3_FENCE_MODE == 0 || ndeps) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+          if (GC3_CONSERVATIVE_FENCES) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
           if (tid == 0) s_ok[phase & 1] = ok ? 1 : 0;
         }
         __syncthreads();
@@ -238,7 +253,8 @@ __global__ void __launch_bounds__(512) gc3_interpreter(KParams p) {
       unsigned char* const dstb = ins.dstbuf < 3 ? (unsigned char*)p.bufs[tb.rank * 3 + ins.dstbuf] + (uint64_t)ins.dstidx * p.chunk_bytes + coff : nullptr;
       unsigned char* const rslot = pops ? fifo_recv + (uint64_t)(recv_seq % p.slots) * p.slot_bytes : nullptr;
       unsigned char* const sslot = pushes ? fifo_send + (uint64_t)(send_seq % p.slots) * p.slot_bytes : nullptr;
-      constexpr int UL = GC3_POL_USER_LD, US = GC3_POL_USER_ST, SL = GC3_POL_SLOT_LD, SS = GC3_POL_SLOT_ST;
+      constexpr int UL = COH ? GC3_POL_USER_LD_COH : GC3_POL_USER_LD, US = COH ? GC3_POL_USER_ST_COH : GC3_POL_USER_ST;
+      constexpr int SL = GC3_POL_SLOT_LD, SS = GC3_POL_SLOT_ST;
       for (uint32_t j = 0; j < ins.count; ++j) {
         const rsrc_t src = make_rsrc(srcb + (uint64_t)j * p.chunk_bytes, srcb ? len : 0);
         const rsrc_t dst = make_rsrc(dstb + (uint64_t)j * p.chunk_bytes, dstb ? len : 0);
@@ -263,7 +279,7 @@ __global__ void __launch_bounds__(512) gc3_interpreter(KParams p) {
       if (pushes || pops || hasdep) {
         __syncthreads();
         if (tid == 0) {
-          if (GC3_FENCE_MODE == 0 || hasdep) __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+          if (GC3_CONSERVATIVE_FENCES) __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
           if (pushes) store_flag(tail_send, p.run_base + send_seq);
           if (pops) store_flag(head_recv, p.run_base + recv_seq);
           if (hasdep) store_flag(my_sem, p.run_base + (uint64_t)t * tb.ninstr + s + 1);
@@ -273,26 +289,39 @@ __global__ void __launch_bounds__(512) gc3_interpreter(KParams p) {
   }
 }
 
-// Host-callable launcher; returns the hipError_t of the launch.
-int launch_interpreter(int dtype, unsigned grid, unsigned block, void* stream, const KParams& p) {
-  hipStream_t st = (hipStream_t)stream;
-  switch (dtype) {
-    case GC3_F32: hipLaunchKernelGGL(gc3_interpreter<GC3_F32>, dim3(grid), dim3(block), 0, st, p); break;
-    case GC3_F16: hipLaunchKernelGGL(gc3_interpreter<GC3_F16>, dim3(grid), dim3(block), 0, st, p); break;
-    case GC3_BF16: hipLaunchKernelGGL(gc3_interpreter<GC3_BF16>, dim3(grid), dim3(block), 0, st, p); break;
-    default: return (int)hipErrorInvalidValue;
-  }
+// Host-callable launcher; returns the hipError_t of the launch.  `coherent_user` selects the
+// instantiation for programs with cross-thread-block dependencies.
+template <int DT>
+static int launch_dt(bool coh, unsigned grid, unsigned block, hipStream_t st, const KParams& p) {
+  if (coh) hipLaunchKernelGGL((gc3_interpreter<DT, true>), dim3(grid), dim3(block), 0, st, p);
+  else hipLaunchKernelGGL((gc3_interpreter<DT, false>), dim3(grid), dim3(block), 0, st, p);
   return (int)hipGetLastError();
 }
 
-// Occupancy of the interpreter (workgroups of `block` threads per compute unit), minimum over dtypes.
+int launch_interpreter(int dtype, bool coherent_user, unsigned grid, unsigned block, void* stream, const KParams& p) {
+  hipStream_t st = (hipStream_t)stream;
+  switch (dtype) {
+    case GC3_F32: return launch_dt<GC3_F32>(coherent_user, grid, block, st, p);
+    case GC3_F16: return launch_dt<GC3_F16>(coherent_user, grid, block, st, p);
+    case GC3_BF16: return launch_dt<GC3_BF16>(coherent_user, grid, block, st, p);
+    default: return (int)hipErrorInvalidValue;
+  }
+}
+
+// Occupancy of the interpreter (workgroups of `block` threads per compute unit), minimum over the
+// instantiations.
 int interpreter_occupancy(unsigned block, int* out) {
-  int a = 0, b = 0, c = 0;
-  hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&a, gc3_interpreter<GC3_F32>, (int)block, 0);
-  if (e == hipSuccess) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&b, gc3_interpreter<GC3_F16>, (int)block, 0);
-  if (e == hipSuccess) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&c, gc3_interpreter<GC3_BF16>, (int)block, 0);
-  if (e != hipSuccess) return (int)e;
-  *out = a < b ? (a < c ? a : c) : (b < c ? b : c);
+  int best = 1 << 30;
+  const void* fns[] = {(const void*)gc3_interpreter<GC3_F32, false>, (const void*)gc3_interpreter<GC3_F32, true>,
+                       (const void*)gc3_interpreter<GC3_F16, false>, (const void*)gc3_interpreter<GC3_F16, true>,
+                       (const void*)gc3_interpreter<GC3_BF16, false>, (const void*)gc3_interpreter<GC3_BF16, true>};
+  for (const void* f : fns) {
+    int n = 0;
+    hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, f, (int)block, 0);
+    if (e != hipSuccess) return (int)e;
+    if (n < best) best = n;
+  }
+  *out = best;
   return 0;
 }
 
