@@ -77,18 +77,21 @@ typedef struct gc3_program_info {
 
 /* Tunables of a communicator.  Zero in any field selects the default. */
 typedef struct gc3_comm_config {
-  int32_t fifo_slots;      /* s of Section 6.1, 1..8; default 4 */
+  int32_t fifo_slots;      /* s of Section 6.1, 1..8; default 2 */
   int32_t tile_bytes;      /* bytes of one chunk a workgroup moves per tile (Section 6.2, chunk
-                              tiling); multiple of 16, at most 1 MiB; default 32768.  A FIFO slot
+                              tiling); multiple of 16, at most 1 MiB; default 32768, halved (not
+                              below 16384) while all FIFOs together exceed 256 MiB.  A FIFO slot
                               holds max_count x tile_bytes. */
-  int32_t team_width;      /* W: workgroups that execute one IR thread block together, workgroup w
-                              owning the w-th 1/W of every chunk with FIFO slots, flags and
-                              semaphore of its own (the runtime applying Section 5.1's
-                              parallelize(W)); 0 = choose so that the grid fills the device */
+  int32_t team_width;      /* W: lanes per IR thread block; lane w owns the w-th 1/W of every chunk and
+                              has FIFO slots, flags and a semaphore of its own (the runtime applying
+                              Section 5.1's parallelize(W)).  Lightly loaded thread blocks of one
+                              rank may share a workgroup.  0 = choose W and the sharing so that the
+                              heaviest workgroup is lightest */
   int32_t wg_size;         /* threads per workgroup: 64, 128, 256 or 512; default 256 */
   int32_t xcd_placement;   /* 0 default (on), 1 on: place the workgroups of connected thread blocks
                               on one XCD; 2 off: workgroups in program order */
-  int32_t reserved0;
+  int32_t target_wgs;      /* workgroups the schedule aims at (never more than can be resident);
+                              0 = four per compute unit */
   uint64_t spin_limit_us;  /* longest a workgroup waits on one flag before the run is abandoned
                               with GC3_ERR_TIMEOUT; default 10 s */
 } gc3_comm_config;
@@ -97,14 +100,14 @@ typedef struct gc3_comm_info {
   int32_t team_width;        /* W in use */
   int32_t wg_size;
   int32_t grid;              /* workgroups launched per run (including idle padding) */
-  int32_t active_wgs;        /* num_tbs x W */
+  int32_t active_wgs;        /* workgroups that execute at least one thread-block lane */
   int32_t max_resident_wgs;  /* occupancy x compute units */
   int32_t fifo_slots;
   int32_t tile_bytes;
   int32_t slot_bytes;        /* max_count x tile_bytes */
   uint64_t fifo_bytes;       /* device memory held by all FIFOs */
   int32_t compute_units;
-  int32_t reserved0;
+  int32_t max_fibers_per_wg; /* most thread-block lanes multiplexed by one workgroup (1 = none shared) */
 } gc3_comm_info;
 
 /* Message for the most recent error on this thread.  host; owned by the library; never null. */
@@ -149,6 +152,13 @@ int gc3_program_scratch_chunks(const gc3_program* prog, int rank, int* out);
 int gc3_comm_create(const gc3_program* prog, const gc3_comm_config* cfg, gc3_comm** out);
 
 int gc3_comm_info_get(const gc3_comm* comm, gc3_comm_info* out);
+
+/* The plan gc3_comm_create would make for `prog` on a device with `compute_units` compute units that
+ * holds `max_resident_wgs` workgroups of cfg->wg_size threads at once, without touching any device
+ * (host only): team width, grid, sharing of workgroups, FIFO memory (Section 6.2, "Initial Setup":
+ * an IR must fit the device).  Errors: as gc3_comm_create, except GC3_ERR_HIP. */
+int gc3_program_plan(const gc3_program* prog, const gc3_comm_config* cfg, int compute_units,
+                     int max_resident_wgs, gc3_comm_info* out);
 
 /* Bind the three named buffers of one rank (Section 3.1): device pointers, 16-byte aligned,
  * owned by the caller and alive for every later run.  For an in-place program `output` must be

@@ -30,7 +30,7 @@ GC3_SUM = 0
 DTYPE_CODE = {"f32": GC3_F32, "f16": GC3_F16, "bf16": GC3_BF16}
 
 EXPORTS = ("gc3_last_error", "gc3_program_load", "gc3_program_free", "gc3_program_validate",
-           "gc3_program_info_get", "gc3_program_scratch_chunks", "gc3_comm_create", "gc3_comm_info_get",
+           "gc3_program_info_get", "gc3_program_scratch_chunks", "gc3_program_plan", "gc3_comm_create", "gc3_comm_info_get",
            "gc3_comm_bind", "gc3_comm_run", "gc3_comm_algorithmic_bytes", "gc3_comm_status",
            "gc3_comm_reset", "gc3_comm_destroy")
 
@@ -44,15 +44,21 @@ class ProgramInfo(C.Structure):
 
 class CommConfig(C.Structure):
     _fields_ = [("fifo_slots", C.c_int32), ("tile_bytes", C.c_int32), ("team_width", C.c_int32),
-                ("wg_size", C.c_int32), ("xcd_placement", C.c_int32), ("reserved0", C.c_int32),
+                ("wg_size", C.c_int32), ("xcd_placement", C.c_int32), ("target_wgs", C.c_int32),
                 ("spin_limit_us", C.c_uint64)]
+
+
+def make_config(fifo_slots: int = 0, tile_bytes: int = 0, team_width: int = 0, wg_size: int = 0,
+                xcd_placement: int = 0, spin_limit_us: int = 0, target_wgs: int = 0) -> CommConfig:
+    """A gc3_comm_config; zero fields select the library's defaults."""
+    return CommConfig(fifo_slots, tile_bytes, team_width, wg_size, xcd_placement, target_wgs, spin_limit_us)
 
 
 class CommInfo(C.Structure):
     _fields_ = [("team_width", C.c_int32), ("wg_size", C.c_int32), ("grid", C.c_int32),
                 ("active_wgs", C.c_int32), ("max_resident_wgs", C.c_int32), ("fifo_slots", C.c_int32),
                 ("tile_bytes", C.c_int32), ("slot_bytes", C.c_int32), ("fifo_bytes", C.c_uint64),
-                ("compute_units", C.c_int32), ("reserved0", C.c_int32)]
+                ("compute_units", C.c_int32), ("max_fibers_per_wg", C.c_int32)]
 
 
 class Gc3Error(RuntimeError):
@@ -81,6 +87,7 @@ def lib() -> C.CDLL:
         L.gc3_program_validate.argtypes = [C.c_void_p, C.c_int, C.c_char_p, C.c_size_t]
         L.gc3_program_info_get.argtypes = [C.c_void_p, C.POINTER(ProgramInfo)]
         L.gc3_program_scratch_chunks.argtypes = [C.c_void_p, C.c_int, C.POINTER(C.c_int)]
+        L.gc3_program_plan.argtypes = [C.c_void_p, C.POINTER(CommConfig), C.c_int, C.c_int, C.POINTER(CommInfo)]
         L.gc3_comm_create.argtypes = [C.c_void_p, C.POINTER(CommConfig), C.POINTER(C.c_void_p)]
         L.gc3_comm_info_get.argtypes = [C.c_void_p, C.POINTER(CommInfo)]
         L.gc3_comm_bind.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t]
@@ -129,6 +136,13 @@ def gc3_program_scratch_chunks(prog: C.c_void_p, rank: int) -> int:
     n = C.c_int()
     _check(lib().gc3_program_scratch_chunks(prog, rank, C.byref(n)))
     return n.value
+
+
+def gc3_program_plan(prog: C.c_void_p, cfg: Optional[CommConfig], compute_units: int, max_resident_wgs: int) -> CommInfo:
+    info = CommInfo()
+    _check(lib().gc3_program_plan(prog, C.byref(cfg) if cfg is not None else None, compute_units,
+                                  max_resident_wgs, C.byref(info)))
+    return info
 
 
 def gc3_comm_create(prog: C.c_void_p, cfg: Optional[CommConfig] = None) -> C.c_void_p:

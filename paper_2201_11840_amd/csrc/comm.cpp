@@ -4,6 +4,7 @@
 #include <hip/hip_runtime_api.h>
 
 #include <algorithm>
+#include <cmath>
 #include <cstring>
 #include <map>
 #include <numeric>
@@ -12,6 +13,7 @@
 #include <vector>
 
 #include "device_tables.h"
+#include "plan.h"
 #include "program.h"
 
 namespace gc3 {
@@ -22,8 +24,6 @@ int interpreter_occupancy(unsigned block, int* out);
 using namespace gc3;
 
 namespace {
-constexpr int kXcds = 8;  // MI355X: 8 accelerator dies, workgroup i is dispatched to die i mod 8
-
 int dtype_size(int dt) { return dt == GC3_F32 ? 4 : (dt == GC3_F16 || dt == GC3_BF16) ? 2 : 0; }
 
 int hip_fail(hipError_t e, const char* what) {
@@ -51,7 +51,8 @@ struct gc3_comm {
   DTb* d_tbs = nullptr;
   DInstr* d_instrs = nullptr;
   DDep* d_deps = nullptr;
-  uint32_t* d_wgmap = nullptr;
+  uint32_t* d_wg_begin = nullptr;
+  uint32_t* d_wg_fibers = nullptr;
   void** d_bufs = nullptr;
   unsigned char* d_fifo = nullptr;
   uint64_t* d_flags = nullptr;
@@ -69,7 +70,7 @@ struct gc3_comm {
 
   ~gc3_comm() {
     // best effort; errors on teardown are ignored
-    for (void* q : {(void*)d_tbs, (void*)d_instrs, (void*)d_deps, (void*)d_wgmap, (void*)d_bufs,
+    for (void* q : {(void*)d_tbs, (void*)d_instrs, (void*)d_deps, (void*)d_wg_begin, (void*)d_wg_fibers, (void*)d_bufs,
                     (void*)d_fifo, (void*)d_flags, (void*)d_sems, (void*)d_error})
       if (q) (void)hipFree(q);
   }
@@ -85,14 +86,6 @@ int upload(T** dptr, const std::vector<T>& host) {
   return GC3_OK;
 }
 
-// Union-find over thread blocks: blocks joined by a connection or a dependency form one group.
-struct Dsu {
-  std::vector<int> p;
-  explicit Dsu(int n) : p(n) { std::iota(p.begin(), p.end(), 0); }
-  int find(int x) { while (p[x] != x) x = p[x] = p[p[x]]; return x; }
-  void join(int a, int b) { p[find(a)] = find(b); }
-};
-
 }  // namespace
 
 extern "C" {
@@ -101,170 +94,36 @@ int gc3_comm_create(const gc3_program* prog, const gc3_comm_config* cfg_in, gc3_
   if (!prog || !out) { set_error("null argument"); return GC3_ERR_ARG; }
   *out = nullptr;
   gc3_comm_config cfg{};
-  if (cfg_in) cfg = *cfg_in;
-  if (cfg.fifo_slots == 0) cfg.fifo_slots = 4;
-  if (cfg.tile_bytes == 0) cfg.tile_bytes = 32768;
-  if (cfg.wg_size == 0) cfg.wg_size = 256;
-  if (cfg.spin_limit_us == 0) cfg.spin_limit_us = 10ull * 1000 * 1000;
-  if (cfg.fifo_slots < 1 || cfg.fifo_slots > 8) { set_error("fifo_slots must be 1..8"); return GC3_ERR_ARG; }
-  if (cfg.tile_bytes < 16 || cfg.tile_bytes % 16 || cfg.tile_bytes > (1 << 20)) {
-    set_error("tile_bytes must be a multiple of 16 in [16, 1 MiB]");
-    return GC3_ERR_ARG;
-  }
-  if (cfg.wg_size != 64 && cfg.wg_size != 128 && cfg.wg_size != 256 && cfg.wg_size != 512) {
-    set_error("wg_size must be 64, 128, 256 or 512");
-    return GC3_ERR_ARG;
-  }
-  if (cfg.team_width < 0 || cfg.team_width > 256) { set_error("team_width must be 0..256"); return GC3_ERR_ARG; }
-  if (cfg.xcd_placement < 0 || cfg.xcd_placement > 2) { set_error("xcd_placement must be 0, 1 or 2"); return GC3_ERR_ARG; }
-
   std::string msg;
-  int rc = validate(*prog, cfg.fifo_slots, msg);
+  int rc = resolve_config(cfg_in, cfg, msg);
   if (rc != GC3_OK) { set_error(msg); return rc; }
 
-  // ---- flatten the program -------------------------------------------------------------------
-  const int R = prog->ranks;
-  std::vector<int> tb_base(R + 1, 0);
-  for (int r = 0; r < R; ++r) tb_base[r + 1] = tb_base[r] + (int)prog->rank[r].tbs.size();
-  const int ntb = tb_base[R];
-  if (ntb == 0) { set_error("program has no thread blocks"); return GC3_ERR_INVALID_PROGRAM; }
-  std::map<std::tuple<int, int, int>, int> conn_id;
-  auto conn_of = [&](int src, int dst, int ch) {
-    auto key = std::make_tuple(src, dst, ch);
-    auto it = conn_id.find(key);
-    if (it != conn_id.end()) return it->second;
-    int id = (int)conn_id.size();
-    conn_id[key] = id;
-    return id;
-  };
-  std::vector<DTb> tbs(ntb);
-  std::vector<DInstr> instrs;
-  std::vector<DDep> deps;
-  Dsu groups(ntb);
-  std::map<int, int> conn_first_tb;
-  int max_count = 1;
-  uint64_t alg_chunks = 0;
-  for (int r = 0; r < R; ++r) {
-    for (size_t b = 0; b < prog->rank[r].tbs.size(); ++b) {
-      const ThreadBlock& tb = prog->rank[r].tbs[b];
-      const int g = tb_base[r] + (int)b;
-      DTb& d = tbs[g];
-      d = DTb{};
-      d.rank = (uint32_t)r;
-      d.instr_begin = (uint32_t)instrs.size();
-      d.ninstr = (uint32_t)tb.instrs.size();
-      d.send_conn = d.recv_conn = -1;
-      for (const Instr& in : tb.instrs) {
-        if (op_pushes(in.op)) d.send_conn = conn_of(r, tb.send, tb.chan);
-        if (op_pops(in.op)) d.recv_conn = conn_of(tb.recv, r, tb.chan);
-        DInstr di{};
-        di.op = in.op;
-        di.srcbuf = (in.srcbuf == BUF_OUT && prog->inplace) ? (uint32_t)BUF_IN : in.srcbuf;
-        di.dstbuf = (in.dstbuf == BUF_OUT && prog->inplace) ? (uint32_t)BUF_IN : in.dstbuf;
-        di.srcidx = (uint32_t)in.srcidx;
-        di.dstidx = (uint32_t)in.dstidx;
-        di.count = (uint32_t)in.count;
-        di.dep_begin = (uint32_t)deps.size();
-        di.ndeps_hasdep = ((uint32_t)in.deps.size() << 1) | (in.hasdep ? 1u : 0u);
-        for (auto& dp : in.deps) {
-          DDep dd{};
-          dd.tb = (uint32_t)(tb_base[r] + dp.first);
-          dd.step = (uint32_t)dp.second;
-          dd.ninstr = (uint32_t)prog->rank[r].tbs[dp.first].instrs.size();
-          deps.push_back(dd);
-          groups.join(g, (int)dd.tb);
-        }
-        instrs.push_back(di);
-        max_count = std::max(max_count, in.count);
-        alg_chunks += (uint64_t)op_traffic(in.op) * (uint64_t)in.count;
-      }
-      for (int c : {d.send_conn, d.recv_conn}) {
-        if (c < 0) continue;
-        auto it = conn_first_tb.find(c);
-        if (it == conn_first_tb.end()) conn_first_tb[c] = g;
-        else groups.join(g, it->second);
-      }
-    }
-  }
-  const int nconn = (int)conn_id.size();
-
-  // ---- device, team width, residency -----------------------------------------------------------
   gc3_comm* c = new gc3_comm();
   struct Guard { gc3_comm* c; ~Guard() { delete c; } } guard{c};
   HIP_TRY(hipGetDevice(&c->device));
   hipDeviceProp_t prop;
   HIP_TRY(hipGetDeviceProperties(&prop, c->device));
-  const int cus = prop.multiProcessorCount;
   int occ = 0;
   {
     int e = interpreter_occupancy((unsigned)cfg.wg_size, &occ);
     if (e != 0) return hip_fail((hipError_t)e, "hipOccupancyMaxActiveBlocksPerMultiprocessor");
   }
-  const long resident = (long)occ * cus;
-  int W = cfg.team_width;
-  if (W == 0) {
-    // about four workgroups per compute unit (enough bytes in flight to cover memory latency),
-    // never beyond residency
-    long target = std::min<long>(4L * cus, resident);
-    W = (int)std::max<long>(1, std::min<long>(64, target / ntb));
-  }
-  const long active = (long)ntb * W;
+  // all workgroups wait on each other, so the whole grid has to be resident at once (Section 6.2)
+  Plan plan;
+  rc = make_plan(*prog, cfg, prop.multiProcessorCount, (long)occ * prop.multiProcessorCount, plan, msg);
+  if (rc != GC3_OK) { set_error(msg); return rc; }
 
-  // ---- placement: workgroup index -> (thread block, lane) ------------------------------------------
-  std::vector<uint32_t> wgmap;
-  if (cfg.xcd_placement == 2) {
-    wgmap.resize(active);
-    for (long i = 0; i < active; ++i) wgmap[i] = (uint32_t)i;
-  } else {
-    // groups of thread blocks that talk to each other, one copy per lane, spread over the dies
-    std::map<int, std::vector<int>> members;
-    for (int g = 0; g < ntb; ++g) members[groups.find(g)].push_back(g);
-    std::vector<std::vector<uint32_t>> per_xcd(kXcds);
-    std::vector<std::pair<size_t, int>> order;  // (size, root), large groups first
-    for (auto& kv : members) order.emplace_back(kv.second.size(), kv.first);
-    std::stable_sort(order.begin(), order.end(), [](auto& a, auto& b) { return a.first > b.first; });
-    // no die takes more than its fair share, so a group larger than that spills onto the next die
-    const size_t fair = (size_t)((active + kXcds - 1) / kXcds);
-    auto least_loaded = [&]() {
-      int best = 0;
-      for (int x = 1; x < kXcds; ++x)
-        if (per_xcd[x].size() < per_xcd[best].size()) best = x;
-      return best;
-    };
-    for (auto& o : order) {
-      for (int w = 0; w < W; ++w) {
-        int cur = least_loaded();
-        for (int g : members[o.second]) {
-          if (per_xcd[cur].size() >= fair) cur = least_loaded();
-          per_xcd[cur].push_back((uint32_t)(g * W + w));
-        }
-      }
-    }
-    size_t longest = 0;
-    for (auto& v : per_xcd) longest = std::max(longest, v.size());
-    wgmap.assign(longest * kXcds, kIdleWg);
-    for (int x = 0; x < kXcds; ++x)
-      for (size_t k = 0; k < per_xcd[x].size(); ++k) wgmap[k * kXcds + x] = per_xcd[x][k];
-  }
-  const long grid = (long)wgmap.size();
-  if (grid > resident) {
-    set_error("program needs " + std::to_string(grid) + " resident workgroups of " + std::to_string(cfg.wg_size) +
-              " threads, the device holds " + std::to_string(resident));
-    return GC3_ERR_RESIDENCY;
-  }
-
-  // ---- allocate ---------------------------------------------------------------------------------
-  const uint64_t slot_bytes = (uint64_t)max_count * (uint64_t)cfg.tile_bytes;
-  const uint64_t fifo_bytes = std::max<uint64_t>(16, (uint64_t)nconn * W * cfg.fifo_slots * slot_bytes);
-  if (slot_bytes > (1ull << 30) || fifo_bytes > (64ull << 30)) { set_error("FIFO memory too large"); return GC3_ERR_SIZE; }
-  c->flags_bytes = std::max<size_t>(1, (size_t)nconn * W * 2) * kFlagStrideWords * sizeof(uint64_t);
-  c->sems_bytes = (size_t)ntb * W * kFlagStrideWords * sizeof(uint64_t);
-  if ((rc = upload(&c->d_tbs, tbs)) != GC3_OK) return rc;
-  if ((rc = upload(&c->d_instrs, instrs)) != GC3_OK) return rc;
-  if ((rc = upload(&c->d_deps, deps)) != GC3_OK) return rc;
-  if ((rc = upload(&c->d_wgmap, wgmap)) != GC3_OK) return rc;
+  const int R = prog->ranks;
+  const int W = plan.info.team_width;
+  c->flags_bytes = std::max<size_t>(1, (size_t)plan.nconn * W * 2) * kFlagStrideWords * sizeof(uint64_t);
+  c->sems_bytes = std::max<size_t>(1, (size_t)plan.ntb * W) * kFlagStrideWords * sizeof(uint64_t);
+  if ((rc = upload(&c->d_tbs, plan.tbs)) != GC3_OK) return rc;
+  if ((rc = upload(&c->d_instrs, plan.instrs)) != GC3_OK) return rc;
+  if ((rc = upload(&c->d_deps, plan.deps)) != GC3_OK) return rc;
+  if ((rc = upload(&c->d_wg_begin, plan.wg_begin)) != GC3_OK) return rc;
+  if ((rc = upload(&c->d_wg_fibers, plan.wg_fibers)) != GC3_OK) return rc;
   HIP_TRY(hipMalloc((void**)&c->d_bufs, (size_t)R * 3 * sizeof(void*)));
-  HIP_TRY(hipMalloc((void**)&c->d_fifo, fifo_bytes));
+  HIP_TRY(hipMalloc((void**)&c->d_fifo, plan.info.fifo_bytes));
   HIP_TRY(hipMalloc((void**)&c->d_flags, c->flags_bytes));
   HIP_TRY(hipMalloc((void**)&c->d_sems, c->sems_bytes));
   HIP_TRY(hipMalloc((void**)&c->d_error, 256));
@@ -277,23 +136,14 @@ int gc3_comm_create(const gc3_program* prog, const gc3_comm_config* cfg_in, gc3_
   c->in_chunks = prog->in_chunks;
   c->out_chunks = prog->inplace ? prog->in_chunks : prog->out_chunks;
   c->inplace = prog->inplace;
-  c->algorithmic_chunks = alg_chunks;
-  c->has_deps = !deps.empty();
+  c->algorithmic_chunks = plan.algorithmic_chunks;
+  c->has_deps = !plan.deps.empty();
   for (int r = 0; r < R; ++r) c->scratch_chunks.push_back(prog->rank[r].scratch_chunks);
   c->bufs.assign((size_t)R * 3, nullptr);
   c->scratch_bytes.assign(R, 0);
   c->bound.assign(R, 0);
   c->spin_limit_ticks = cfg.spin_limit_us * 100ull;  // wall clock runs at 100 MHz
-  c->info.team_width = W;
-  c->info.wg_size = cfg.wg_size;
-  c->info.grid = (int32_t)grid;
-  c->info.active_wgs = (int32_t)active;
-  c->info.max_resident_wgs = (int32_t)std::min<long>(resident, INT32_MAX);
-  c->info.fifo_slots = cfg.fifo_slots;
-  c->info.tile_bytes = cfg.tile_bytes;
-  c->info.slot_bytes = (int32_t)slot_bytes;
-  c->info.fifo_bytes = fifo_bytes;
-  c->info.compute_units = cus;
+  c->info = plan.info;
   guard.c = nullptr;
   *out = c;
   return GC3_OK;
@@ -361,7 +211,7 @@ int gc3_comm_run(gc3_comm* comm, size_t elems_per_rank, gc3_dtype dtype, gc3_red
       return GC3_ERR_SIZE;
     }
   }
-  if (elems_per_rank == 0) return GC3_OK;
+  if (elems_per_rank == 0 || comm->info.grid == 0) return GC3_OK;
   int dev = -1;
   HIP_TRY(hipGetDevice(&dev));
   if (dev != comm->device) { set_error("communicator belongs to another device"); return GC3_ERR_ARG; }
@@ -376,7 +226,8 @@ int gc3_comm_run(gc3_comm* comm, size_t elems_per_rank, gc3_dtype dtype, gc3_red
   p.tbs = comm->d_tbs;
   p.instrs = comm->d_instrs;
   p.deps = comm->d_deps;
-  p.wgmap = comm->d_wgmap;
+  p.wg_begin = comm->d_wg_begin;
+  p.wg_fibers = comm->d_wg_fibers;
   p.bufs = comm->d_bufs;
   p.fifo = comm->d_fifo;
   p.flags = comm->d_flags;

@@ -6,7 +6,7 @@
 
 namespace gc3 {
 
-constexpr uint32_t kIdleWg = 0xffffffffu;
+constexpr int kMaxFibersPerWg = 32;  // lanes of IR thread blocks one workgroup may multiplex
 constexpr int kFlagStrideWords = 16;  // one 64-bit flag per 128-byte line
 
 struct DInstr {            // 32 bytes
@@ -36,7 +36,8 @@ struct KParams {
   const DTb* tbs;
   const DInstr* instrs;
   const DDep* deps;
-  const uint32_t* wgmap;   // per workgroup: global thread-block index * W + lane, or kIdleWg
+  const uint32_t* wg_begin;   // [grid + 1] range of each workgroup in wg_fibers (empty = idle workgroup)
+  const uint32_t* wg_fibers;  // fiber = global thread-block index * W + lane
   void* const* bufs;       // [rank*3 + buffer] user buffers
   unsigned char* fifo;     // [(conn*W + lane) * slots + slot] * slot_bytes
   uint64_t* flags;         // [((conn*W + lane)*2 + {0 tail, 1 head}) * kFlagStrideWords]

@@ -84,7 +84,7 @@ __device__ __forceinline__ u32x4 add_vec(u32x4 a, u32x4 b) {
 // device scope only in programs with cross-thread-block dependencies, where one workgroup reads
 // chunks another one wrote in the same run (template parameter COH).  With these policies no bulk L2
 // write-back / invalidate (agent-scope fence) is needed anywhere in the kernel.
-constexpr int kPolPlain = 0, kPolSc0 = 1, kPolNt = 2, kPolSc1 = 16;
+constexpr int kPolNt = 2, kPolSc1 = 16;   // (bit 0 would be sc0)
 #ifndef GC3_POL_SLOT_LD
 #define GC3_POL_SLOT_LD (kPolSc1)
 #endif
@@ -164,127 +164,199 @@ __device__ __forceinline__ uint64_t lane_begin(uint64_t U, uint32_t w, uint32_t 
 
 }  // namespace
 
+constexpr uint32_t kFiberDone = 0xffffffffu;
+
+__device__ __forceinline__ uint32_t uni(uint32_t v) { return __builtin_amdgcn_readfirstlane(v); }
+
+// A workgroup runs a short list of FIBERS.  A fiber is one lane of one IR thread block: its own
+// tile counter, step counter and FIFO sequence numbers.  The workgroup visits its unfinished
+// fibers round-robin and advances each as far as its waits allow; while more than one fiber is
+// unfinished a wait is a single poll (a fiber that is not ready yields to the next one, so thread
+// blocks sharing a workgroup can never block each other), and the last unfinished fiber waits by
+// spinning.  One fiber per workgroup is the paper's one-thread-block-per-block execution.
 template <int DT, bool COH>
 __global__ void __launch_bounds__(512) gc3_interpreter(KParams p) {
-  __shared__ int s_ok[2];
+  __shared__ uint32_t f_id[kMaxFibersPerWg], f_t[kMaxFibersPerWg], f_s[kMaxFibersPerWg];
+  __shared__ uint32_t f_send[kMaxFibersPerWg], f_recv[kMaxFibersPerWg];
+  __shared__ uint64_t f_off0[kMaxFibersPerWg], f_share[kMaxFibersPerWg];
+  __shared__ int s_res[2];
   const uint32_t tid = threadIdx.x, nthreads = blockDim.x;
-  const uint32_t m = p.wgmap[blockIdx.x];
-  if (m == kIdleWg) return;
+  const uint32_t fbeg = p.wg_begin[blockIdx.x];
+  const uint32_t nf = p.wg_begin[blockIdx.x + 1] - fbeg;
+  if (nf == 0) return;
   const uint32_t W = p.W;
-  const uint32_t tbi = m / W, lane = m % W;
-  const DTb tb = p.tbs[tbi];
-
-  const uint64_t U = p.chunk_bytes >> 4;
-  const uint64_t off0 = lane_begin(U, lane, W);
-  const uint64_t share = lane_begin(U, lane + 1, W) - off0;
   const uint32_t tile = p.tile_bytes;
-  const uint32_t ntiles = (uint32_t)((share + tile - 1) / tile);
+  if (tid < nf) {
+    const uint32_t fid = p.wg_fibers[fbeg + tid];
+    const uint64_t U = p.chunk_bytes >> 4;
+    const uint64_t o = lane_begin(U, fid % W, W);
+    f_id[tid] = fid;
+    f_t[tid] = 0;
+    f_s[tid] = 0;
+    f_send[tid] = 0;
+    f_recv[tid] = 0;
+    f_off0[tid] = o;
+    f_share[tid] = lane_begin(U, fid % W + 1, W) - o;
+  }
+  uint32_t live = nf, phase = 0;
+  uint64_t last_progress = wall_clock64();
 
-  uint64_t* const tail_send = tb.send_conn >= 0 ? p.flags + ((uint64_t)(tb.send_conn * W + lane) * 2 + 0) * kFlagStrideWords : nullptr;
-  uint64_t* const head_send = tb.send_conn >= 0 ? p.flags + ((uint64_t)(tb.send_conn * W + lane) * 2 + 1) * kFlagStrideWords : nullptr;
-  uint64_t* const tail_recv = tb.recv_conn >= 0 ? p.flags + ((uint64_t)(tb.recv_conn * W + lane) * 2 + 0) * kFlagStrideWords : nullptr;
-  uint64_t* const head_recv = tb.recv_conn >= 0 ? p.flags + ((uint64_t)(tb.recv_conn * W + lane) * 2 + 1) * kFlagStrideWords : nullptr;
-  unsigned char* const fifo_send = tb.send_conn >= 0 ? p.fifo + (uint64_t)(tb.send_conn * W + lane) * p.slots * p.slot_bytes : nullptr;
-  unsigned char* const fifo_recv = tb.recv_conn >= 0 ? p.fifo + (uint64_t)(tb.recv_conn * W + lane) * p.slots * p.slot_bytes : nullptr;
-  uint64_t* const my_sem = p.sems + (uint64_t)(tbi * W + lane) * kFlagStrideWords;
+  while (live) {
+    bool any_progress = false;
+    for (uint32_t fi = 0; fi < nf; ++fi) {
+      __syncthreads();                                   // state written in the previous visit is visible
+      uint32_t t = uni(f_t[fi]);
+      if (t == kFiberDone) continue;
+      const uint32_t fid = uni(f_id[fi]);
+      const uint32_t tbi = fid / W, lane = fid % W;
+      const DTb tb = p.tbs[tbi];
+      const uint64_t off0 = ((uint64_t)uni((uint32_t)(f_off0[fi] >> 32)) << 32) | uni((uint32_t)f_off0[fi]);
+      const uint64_t share = ((uint64_t)uni((uint32_t)(f_share[fi] >> 32)) << 32) | uni((uint32_t)f_share[fi]);
+      const uint32_t ntiles = (uint32_t)((share + tile - 1) / tile);
+      uint32_t s = uni(f_s[fi]), send_seq = uni(f_send[fi]), recv_seq = uni(f_recv[fi]);
 
-  uint32_t send_seq = 0, recv_seq = 0, phase = 0;
+      uint64_t* const tail_send = tb.send_conn >= 0 ? p.flags + ((uint64_t)(tb.send_conn * W + lane) * 2 + 0) * kFlagStrideWords : nullptr;
+      uint64_t* const head_send = tb.send_conn >= 0 ? p.flags + ((uint64_t)(tb.send_conn * W + lane) * 2 + 1) * kFlagStrideWords : nullptr;
+      uint64_t* const tail_recv = tb.recv_conn >= 0 ? p.flags + ((uint64_t)(tb.recv_conn * W + lane) * 2 + 0) * kFlagStrideWords : nullptr;
+      uint64_t* const head_recv = tb.recv_conn >= 0 ? p.flags + ((uint64_t)(tb.recv_conn * W + lane) * 2 + 1) * kFlagStrideWords : nullptr;
+      unsigned char* const fifo_send = tb.send_conn >= 0 ? p.fifo + (uint64_t)(tb.send_conn * W + lane) * p.slots * p.slot_bytes : nullptr;
+      unsigned char* const fifo_recv = tb.recv_conn >= 0 ? p.fifo + (uint64_t)(tb.recv_conn * W + lane) * p.slots * p.slot_bytes : nullptr;
+      uint64_t* const my_sem = p.sems + (uint64_t)(tbi * W + lane) * kFlagStrideWords;
 
-  for (uint32_t t = 0; t < ntiles; ++t) {                      // chunk tiling (outermost loop)
-    const uint64_t toff = (uint64_t)t * tile;
-    const uint32_t len = (uint32_t)(share - toff < tile ? share - toff : tile);   // bytes of this tile, per chunk
-    const uint32_t nvec = len >> 4;
-    for (uint32_t s = 0; s < tb.ninstr; ++s) {                 // instruction loop
-      const DInstr ins = p.instrs[tb.instr_begin + s];
-      const uint32_t op = ins.op;
-      const bool pops = op == GC3_OP_RECV || op == GC3_OP_RRC || op == GC3_OP_RCS || op == GC3_OP_RRCS || op == GC3_OP_RRS;
-      const bool pushes = op == GC3_OP_SEND || op == GC3_OP_RCS || op == GC3_OP_RRCS || op == GC3_OP_RRS;
-      const uint32_t ndeps = ins.ndeps_hasdep >> 1;
-      const bool hasdep = ins.ndeps_hasdep & 1;
-      const bool wait_slot = pushes && send_seq >= p.slots;
+      bool progressed = false;
+      while (t < ntiles && s < tb.ninstr) {              // tile loop outside, instruction loop inside
+        const uint64_t toff = (uint64_t)t * tile;
+        const uint32_t len = (uint32_t)(share - toff < tile ? share - toff : tile);   // bytes of this tile, per chunk
+        const uint32_t nvec = len >> 4;
+        const DInstr ins = p.instrs[tb.instr_begin + s];
+        const uint32_t op = ins.op;
+        const bool pops = op == GC3_OP_RECV || op == GC3_OP_RRC || op == GC3_OP_RCS || op == GC3_OP_RRCS || op == GC3_OP_RRS;
+        const bool pushes = op == GC3_OP_SEND || op == GC3_OP_RCS || op == GC3_OP_RRCS || op == GC3_OP_RRS;
+        const uint32_t ndeps = ins.ndeps_hasdep >> 1;
+        const bool hasdep = ins.ndeps_hasdep & 1;
+        const bool wait_slot = pushes && send_seq >= p.slots;
 
-      // ---- wait for dependencies, for a message, for a free slot -------------------------------
-      if (pops || wait_slot || ndeps) {
-        if (tid < 64) {
-          bool ok = true;
-          const uint32_t total = 2 + ndeps;
-          for (uint32_t it0 = 0; it0 < total && ok; it0 += 64) {
-            const uint32_t it = it0 + tid;
-            const uint64_t* ptr = nullptr;
-            uint64_t want = 0;
-            if (it == 0) {
-              if (pops) { ptr = tail_recv; want = p.run_base + recv_seq + 1; }
-            } else if (it == 1) {
-              if (wait_slot) { ptr = head_send; want = p.run_base + send_seq + 1 - p.slots; }
-            } else if (it < total) {
-              const DDep d = p.deps[ins.dep_begin + it - 2];
-              ptr = p.sems + (uint64_t)(d.tb * W + lane) * kFlagStrideWords;
-              want = p.run_base + (uint64_t)t * d.ninstr + d.step + 1;
-            }
-            bool pending = ptr != nullptr;
-            const uint64_t start = wall_clock64();
-            uint32_t spins = 0;
-            for (;;) {
-              if (pending && load_flag(ptr) >= want) pending = false;
-              if (!__any(pending)) break;
-              __builtin_amdgcn_s_sleep(1);
-              if ((++spins & 255u) == 0) {
-                if (__hip_atomic_load(p.error, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) { ok = false; break; }
-                if (wall_clock64() - start > p.spin_limit_ticks) {
-                  atomicCAS(p.error, 0u, (uint32_t)(-GC3_ERR_TIMEOUT));
-                  ok = false;
-                  break;
+        // ---- wait for dependencies, for a message, for a free slot -----------------------------
+        if (pops || wait_slot || ndeps) {
+          const bool block = live == 1;
+          if (tid < 64) {
+            int res = 1;                                   // 1 ready, 0 not ready, -1 run abandoned
+            const uint32_t total = 2 + ndeps;
+            for (uint32_t it0 = 0; it0 < total && res == 1; it0 += 64) {
+              const uint32_t it = it0 + tid;
+              const uint64_t* ptr = nullptr;
+              uint64_t want = 0;
+              if (it == 0) {
+                if (pops) { ptr = tail_recv; want = p.run_base + recv_seq + 1; }
+              } else if (it == 1) {
+                if (wait_slot) { ptr = head_send; want = p.run_base + send_seq + 1 - p.slots; }
+              } else if (it < total) {
+                const DDep d = p.deps[ins.dep_begin + it - 2];
+                ptr = p.sems + (uint64_t)(d.tb * W + lane) * kFlagStrideWords;
+                want = p.run_base + (uint64_t)t * d.ninstr + d.step + 1;
+              }
+              bool pending = ptr != nullptr;
+              const uint64_t start = wall_clock64();
+              uint32_t spins = 0;
+              for (;;) {
+                if (pending && load_flag(ptr) >= want) pending = false;
+                if (!__any(pending)) break;
+                if (!block) { res = 0; break; }
+                __builtin_amdgcn_s_sleep(1);
+                if ((++spins & 255u) == 0) {
+                  if (__hip_atomic_load(p.error, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) { res = -1; break; }
+                  if (wall_clock64() - start > p.spin_limit_ticks) {
+                    atomicCAS(p.error, 0u, (uint32_t)(-GC3_ERR_TIMEOUT));
+                    res = -1;
+                    break;
+                  }
                 }
               }
             }
+            if (GC3_CONSERVATIVE_FENCES) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+            if (tid == 0) s_res[phase & 1] = res;
           }
-          if (GC3_CONSERVATIVE_FENCES) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-          if (tid == 0) s_ok[phase & 1] = ok ? 1 : 0;
+          __syncthreads();
+          const int res_all = s_res[phase & 1];
+          ++phase;
+          if (res_all < 0) return;     // the run is abandoned; every workgroup leaves the same way
+          if (res_all == 0) break;     // not ready: yield to the next fiber
         }
-        __syncthreads();
-        const int ok_all = s_ok[phase & 1];
-        ++phase;
-        if (!ok_all) return;     // the run is abandoned; every workgroup leaves the same way
+
+        // ---- move the tile --------------------------------------------------------------------
+        const uint64_t coff = off0 + toff;   // byte offset inside each chunk
+        unsigned char* const srcb = ins.srcbuf < 3 ? (unsigned char*)p.bufs[tb.rank * 3 + ins.srcbuf] + (uint64_t)ins.srcidx * p.chunk_bytes + coff : nullptr;
+        unsigned char* const dstb = ins.dstbuf < 3 ? (unsigned char*)p.bufs[tb.rank * 3 + ins.dstbuf] + (uint64_t)ins.dstidx * p.chunk_bytes + coff : nullptr;
+        unsigned char* const rslot = pops ? fifo_recv + (uint64_t)(recv_seq % p.slots) * p.slot_bytes : nullptr;
+        unsigned char* const sslot = pushes ? fifo_send + (uint64_t)(send_seq % p.slots) * p.slot_bytes : nullptr;
+        constexpr int UL = COH ? GC3_POL_USER_LD_COH : GC3_POL_USER_LD, US = COH ? GC3_POL_USER_ST_COH : GC3_POL_USER_ST;
+        constexpr int SL = GC3_POL_SLOT_LD, SS = GC3_POL_SLOT_ST;
+        for (uint32_t j = 0; j < ins.count; ++j) {
+          const rsrc_t src = make_rsrc(srcb + (uint64_t)j * p.chunk_bytes, srcb ? len : 0);
+          const rsrc_t dst = make_rsrc(dstb + (uint64_t)j * p.chunk_bytes, dstb ? len : 0);
+          const rsrc_t rs = make_rsrc(rslot + (uint64_t)j * len, rslot ? len : 0);
+          const rsrc_t ss = make_rsrc(sslot + (uint64_t)j * len, sslot ? len : 0);
+          switch (op) {
+            case GC3_OP_SEND:   move_tile<false, false, DT, UL, 0, SS, 0>(src, src, ss, ss, nvec, tid, nthreads); break;
+            case GC3_OP_RECV:   move_tile<false, false, DT, SL, 0, US, 0>(rs, rs, dst, dst, nvec, tid, nthreads); break;
+            case GC3_OP_COPY:   move_tile<false, false, DT, UL, 0, US, 0>(src, src, dst, dst, nvec, tid, nthreads); break;
+            case GC3_OP_REDUCE: move_tile<true, false, DT, UL, UL, US, 0>(dst, src, dst, dst, nvec, tid, nthreads); break;
+            case GC3_OP_RRC:    move_tile<true, false, DT, SL, UL, US, 0>(rs, src, dst, dst, nvec, tid, nthreads); break;
+            case GC3_OP_RCS:    move_tile<false, true, DT, SL, 0, US, SS>(rs, rs, dst, ss, nvec, tid, nthreads); break;
+            case GC3_OP_RRCS:   move_tile<true, true, DT, SL, UL, US, SS>(rs, src, dst, ss, nvec, tid, nthreads); break;
+            case GC3_OP_RRS:    move_tile<true, false, DT, SL, UL, SS, 0>(rs, src, ss, ss, nvec, tid, nthreads); break;
+            default: break;
+          }
+        }
+
+        // ---- publish: slot filled, slot freed, semaphore ----------------------------------------
+        if (pushes) ++send_seq;
+        if (pops) ++recv_seq;
+        if (pushes || pops || hasdep) {
+          __syncthreads();
+          if (tid == 0) {
+            if (GC3_CONSERVATIVE_FENCES) __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+            if (pushes) store_flag(tail_send, p.run_base + send_seq);
+            if (pops) store_flag(head_recv, p.run_base + recv_seq);
+            if (hasdep) store_flag(my_sem, p.run_base + (uint64_t)t * tb.ninstr + s + 1);
+          }
+        }
+        progressed = true;
+        if (++s == tb.ninstr) { s = 0; ++t; }
       }
 
-      // ---- move the tile ----------------------------------------------------------------------
-      const uint64_t coff = off0 + toff;   // byte offset inside each chunk
-      unsigned char* const srcb = ins.srcbuf < 3 ? (unsigned char*)p.bufs[tb.rank * 3 + ins.srcbuf] + (uint64_t)ins.srcidx * p.chunk_bytes + coff : nullptr;
-      unsigned char* const dstb = ins.dstbuf < 3 ? (unsigned char*)p.bufs[tb.rank * 3 + ins.dstbuf] + (uint64_t)ins.dstidx * p.chunk_bytes + coff : nullptr;
-      unsigned char* const rslot = pops ? fifo_recv + (uint64_t)(recv_seq % p.slots) * p.slot_bytes : nullptr;
-      unsigned char* const sslot = pushes ? fifo_send + (uint64_t)(send_seq % p.slots) * p.slot_bytes : nullptr;
-      constexpr int UL = COH ? GC3_POL_USER_LD_COH : GC3_POL_USER_LD, US = COH ? GC3_POL_USER_ST_COH : GC3_POL_USER_ST;
-      constexpr int SL = GC3_POL_SLOT_LD, SS = GC3_POL_SLOT_ST;
-      for (uint32_t j = 0; j < ins.count; ++j) {
-        const rsrc_t src = make_rsrc(srcb + (uint64_t)j * p.chunk_bytes, srcb ? len : 0);
-        const rsrc_t dst = make_rsrc(dstb + (uint64_t)j * p.chunk_bytes, dstb ? len : 0);
-        const rsrc_t rs = make_rsrc(rslot + (uint64_t)j * len, rslot ? len : 0);
-        const rsrc_t ss = make_rsrc(sslot + (uint64_t)j * len, sslot ? len : 0);
-        switch (op) {
-          case GC3_OP_SEND:   move_tile<false, false, DT, UL, 0, SS, 0>(src, src, ss, ss, nvec, tid, nthreads); break;
-          case GC3_OP_RECV:   move_tile<false, false, DT, SL, 0, US, 0>(rs, rs, dst, dst, nvec, tid, nthreads); break;
-          case GC3_OP_COPY:   move_tile<false, false, DT, UL, 0, US, 0>(src, src, dst, dst, nvec, tid, nthreads); break;
-          case GC3_OP_REDUCE: move_tile<true, false, DT, UL, UL, US, 0>(dst, src, dst, dst, nvec, tid, nthreads); break;
-          case GC3_OP_RRC:    move_tile<true, false, DT, SL, UL, US, 0>(rs, src, dst, dst, nvec, tid, nthreads); break;
-          case GC3_OP_RCS:    move_tile<false, true, DT, SL, 0, US, SS>(rs, rs, dst, ss, nvec, tid, nthreads); break;
-          case GC3_OP_RRCS:   move_tile<true, true, DT, SL, UL, US, SS>(rs, src, dst, ss, nvec, tid, nthreads); break;
-          case GC3_OP_RRS:    move_tile<true, false, DT, SL, UL, SS, 0>(rs, src, ss, ss, nvec, tid, nthreads); break;
-          default: break;
-        }
-      }
-
-      // ---- publish: slot filled, slot freed, semaphore ------------------------------------------
-      if (pushes) ++send_seq;
-      if (pops) ++recv_seq;
-      if (pushes || pops || hasdep) {
-        __syncthreads();
+      const bool finished = t >= ntiles || tb.ninstr == 0;   // also true for a lane that owns no bytes
+      if (progressed || finished) {
+        any_progress = true;
+        __syncthreads();                                 // every wavefront has read this fiber's old state
         if (tid == 0) {
-          if (GC3_CONSERVATIVE_FENCES) __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
-          if (pushes) store_flag(tail_send, p.run_base + send_seq);
-          if (pops) store_flag(head_recv, p.run_base + recv_seq);
-          if (hasdep) store_flag(my_sem, p.run_base + (uint64_t)t * tb.ninstr + s + 1);
+          f_t[fi] = finished ? kFiberDone : t;
+          f_s[fi] = s;
+          f_send[fi] = send_seq;
+          f_recv[fi] = recv_seq;
         }
       }
+      if (finished) --live;
+    }
+    if (live && !any_progress) {
+      // a whole sweep without progress: back off, and give up when nothing moved for the spin limit
+      if (tid == 0) {
+        int res = 1;
+        if (__hip_atomic_load(p.error, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) {
+          res = -1;
+        } else if (wall_clock64() - last_progress > p.spin_limit_ticks) {
+          atomicCAS(p.error, 0u, (uint32_t)(-GC3_ERR_TIMEOUT));
+          res = -1;
+        }
+        s_res[phase & 1] = res;
+      }
+      __syncthreads();
+      const int res_all = s_res[phase & 1];
+      ++phase;
+      if (res_all < 0) return;
+      __builtin_amdgcn_s_sleep(2);
+    } else {
+      last_progress = wall_clock64();
     }
   }
 }

@@ -1,0 +1,320 @@
+// Planning of a GC3-IR program for the interpreter kernel (host only, no device calls).
+//
+// The paper's runtime launches one thread block per IR thread block (Section 6.2) and relies on the
+// user's parallelize(N) directive for parallelism (Section 5.1).  Here the runtime itself splits
+// every IR thread block into W lanes (each lane = the program applied to 1/W of every chunk) and
+// lets lightly loaded thread blocks of one rank share a workgroup, so that the number of busy
+// workgroups matches the device whatever the program's thread-block count is.
+#include "plan.h"
+
+#include <algorithm>
+#include <cmath>
+#include <map>
+#include <numeric>
+#include <tuple>
+
+namespace gc3 {
+
+namespace {
+constexpr int kXcds = 8;  // MI355X: 8 accelerator dies (XCDs), workgroup i is dispatched to die i mod 8
+
+// Union-find: thread blocks joined by a connection or a dependency form one group.
+struct Dsu {
+  std::vector<int> p;
+  explicit Dsu(int n) : p(n) { std::iota(p.begin(), p.end(), 0); }
+  int find(int x) { while (p[x] != x) x = p[x] = p[p[x]]; return x; }
+  void join(int a, int b) { p[find(a)] = find(b); }
+};
+}  // namespace
+
+int resolve_config(const gc3_comm_config* cfg_in, gc3_comm_config& cfg, std::string& msg) {
+  cfg = gc3_comm_config{};
+  if (cfg_in) cfg = *cfg_in;
+  if (cfg.fifo_slots == 0) cfg.fifo_slots = 2;
+  if (cfg.wg_size == 0) cfg.wg_size = 256;
+  if (cfg.spin_limit_us == 0) cfg.spin_limit_us = 10ull * 1000 * 1000;
+  if (cfg.fifo_slots < 1 || cfg.fifo_slots > 8) { msg = "fifo_slots must be 1..8"; return GC3_ERR_ARG; }
+  if (cfg.tile_bytes != 0 && (cfg.tile_bytes < 16 || cfg.tile_bytes % 16 || cfg.tile_bytes > (1 << 20))) {
+    msg = "tile_bytes must be a multiple of 16 in [16, 1 MiB]";
+    return GC3_ERR_ARG;
+  }
+  if (cfg.wg_size != 64 && cfg.wg_size != 128 && cfg.wg_size != 256 && cfg.wg_size != 512) {
+    msg = "wg_size must be 64, 128, 256 or 512";
+    return GC3_ERR_ARG;
+  }
+  if (cfg.team_width < 0 || cfg.team_width > 256) { msg = "team_width must be 0..256"; return GC3_ERR_ARG; }
+  if (cfg.xcd_placement < 0 || cfg.xcd_placement > 2) { msg = "xcd_placement must be 0, 1 or 2"; return GC3_ERR_ARG; }
+
+  if (cfg.target_wgs < 0) { msg = "target_wgs must not be negative"; return GC3_ERR_ARG; }
+  return GC3_OK;
+}
+
+int make_plan(const gc3_program& prog, const gc3_comm_config& cfg, int cus, long resident, Plan& plan, std::string& msg) {
+  if (cus < 1 || resident < 1) { msg = "device size must be positive"; return GC3_ERR_ARG; }
+  int rc = validate(prog, cfg.fifo_slots, msg);
+  if (rc != GC3_OK) return rc;
+  plan.cfg = cfg;
+
+  // ---- flatten the program -------------------------------------------------------------------
+  const int R = prog.ranks;
+  std::vector<int> tb_base(R + 1, 0);
+  for (int r = 0; r < R; ++r) tb_base[r + 1] = tb_base[r] + (int)prog.rank[r].tbs.size();
+  const int ntb = tb_base[R];
+  std::map<std::tuple<int, int, int>, int> conn_id;
+  auto conn_of = [&](int src, int dst, int ch) {
+    auto key = std::make_tuple(src, dst, ch);
+    auto it = conn_id.find(key);
+    if (it != conn_id.end()) return it->second;
+    int id = (int)conn_id.size();
+    conn_id[key] = id;
+    return id;
+  };
+  std::vector<DTb>& tbs = plan.tbs;
+  std::vector<DInstr>& instrs = plan.instrs;
+  std::vector<DDep>& deps = plan.deps;
+  tbs.assign(ntb, DTb{});
+  instrs.clear();
+  deps.clear();
+  Dsu groups(ntb);
+  std::map<int, int> conn_first_tb;
+  int max_count = 1;
+  uint64_t alg_chunks = 0;
+  for (int r = 0; r < R; ++r) {
+    for (size_t b = 0; b < prog.rank[r].tbs.size(); ++b) {
+      const ThreadBlock& tb = prog.rank[r].tbs[b];
+      const int g = tb_base[r] + (int)b;
+      DTb& d = tbs[g];
+      d = DTb{};
+      d.rank = (uint32_t)r;
+      d.instr_begin = (uint32_t)instrs.size();
+      d.ninstr = (uint32_t)tb.instrs.size();
+      d.send_conn = d.recv_conn = -1;
+      for (const Instr& in : tb.instrs) {
+        if (op_pushes(in.op)) d.send_conn = conn_of(r, tb.send, tb.chan);
+        if (op_pops(in.op)) d.recv_conn = conn_of(tb.recv, r, tb.chan);
+        DInstr di{};
+        di.op = in.op;
+        di.srcbuf = (in.srcbuf == BUF_OUT && prog.inplace) ? (uint32_t)BUF_IN : in.srcbuf;
+        di.dstbuf = (in.dstbuf == BUF_OUT && prog.inplace) ? (uint32_t)BUF_IN : in.dstbuf;
+        di.srcidx = (uint32_t)in.srcidx;
+        di.dstidx = (uint32_t)in.dstidx;
+        di.count = (uint32_t)in.count;
+        di.dep_begin = (uint32_t)deps.size();
+        di.ndeps_hasdep = ((uint32_t)in.deps.size() << 1) | (in.hasdep ? 1u : 0u);
+        for (auto& dp : in.deps) {
+          DDep dd{};
+          dd.tb = (uint32_t)(tb_base[r] + dp.first);
+          dd.step = (uint32_t)dp.second;
+          dd.ninstr = (uint32_t)prog.rank[r].tbs[dp.first].instrs.size();
+          deps.push_back(dd);
+          groups.join(g, (int)dd.tb);
+        }
+        instrs.push_back(di);
+        max_count = std::max(max_count, in.count);
+        alg_chunks += (uint64_t)op_traffic(in.op) * (uint64_t)in.count;
+      }
+      for (int c : {d.send_conn, d.recv_conn}) {
+        if (c < 0) continue;
+        auto it = conn_first_tb.find(c);
+        if (it == conn_first_tb.end()) conn_first_tb[c] = g;
+        else groups.join(g, it->second);
+      }
+    }
+  }
+  const int nconn = (int)conn_id.size();
+
+
+  // about four workgroups per compute unit give enough bytes in flight to cover memory latency
+  long target = cfg.target_wgs > 0 ? cfg.target_wgs : 4L * cus;
+  target = std::max<long>(1, std::min<long>(target, resident));
+
+  // ---- schedule: team width W and which thread blocks share a workgroup -----------------------------
+  // A workgroup multiplexes the lanes (fibers) of several thread blocks of one rank.  The weight of
+  // a thread block is its traffic per tile; the thread blocks of a rank are packed into k bins
+  // (largest first into the lightest bin) and every (bin, lane) pair becomes one workgroup.  W and
+  // the bin counts are chosen to minimise the heaviest workgroup's traffic, bin weight / W, with at
+  // most `target` workgroups.
+  std::vector<uint64_t> weight(ntb, 0);
+  for (int r = 0; r < R; ++r)
+    for (size_t b = 0; b < prog.rank[r].tbs.size(); ++b)
+      for (const Instr& in : prog.rank[r].tbs[b].instrs)
+        weight[tb_base[r] + b] += (uint64_t)op_traffic(in.op) * (uint64_t)in.count;
+  uint64_t total_weight = 0;
+  for (uint64_t w : weight) total_weight += std::max<uint64_t>(w, 1);
+  auto pack = [&](int W, bool round_up, std::vector<std::vector<int>>* bins_out, double* heaviest) -> long {
+    // returns the number of workgroups, or -1 when a workgroup would exceed the fiber limit
+    const double ideal = (double)total_weight * W / (double)target;   // traffic of one workgroup if perfectly spread
+    long wgs = 0;
+    double worst = 0;
+    for (int r = 0; r < R; ++r) {
+      const int n = tb_base[r + 1] - tb_base[r];
+      if (n == 0) continue;
+      std::vector<int> order(n);
+      std::iota(order.begin(), order.end(), tb_base[r]);
+      std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return weight[a] > weight[b]; });
+      double rank_weight = 0;
+      for (int g : order) rank_weight += (double)std::max<uint64_t>(weight[g], 1);
+      const double cap = std::max(ideal, (double)std::max<uint64_t>(weight[order[0]], 1));
+      int k = round_up ? (int)std::ceil(rank_weight / cap - 1e-9) : (int)std::floor(rank_weight / cap + 1e-9);
+      k = std::max(1, std::min(k, n));
+      k = std::max(k, (n + kMaxFibersPerWg - 1) / kMaxFibersPerWg);
+      std::vector<std::vector<int>> bins(k);
+      std::vector<double> load(k, 0.0);
+      for (int g : order) {
+        int best = -1;
+        for (int i = 0; i < k; ++i)
+          if ((int)bins[i].size() < kMaxFibersPerWg && (best < 0 || load[i] < load[best])) best = i;
+        if (best < 0) return -1;
+        bins[best].push_back(g);
+        load[best] += (double)std::max<uint64_t>(weight[g], 1);
+      }
+      for (int i = 0; i < k; ++i) {
+        worst = std::max(worst, load[i]);
+        std::sort(bins[i].begin(), bins[i].end());   // program order inside a workgroup
+        if (bins_out) bins_out->push_back(bins[i]);
+      }
+      wgs += (long)k * W;
+    }
+    if (heaviest) *heaviest = worst;
+    return wgs;
+  };
+  int W = cfg.team_width;
+  bool round_up = true;
+  if (ntb == 0) {
+    W = std::max(W, 1);   // a program without thread blocks is a valid no-op (e.g. AllToNext on one rank)
+  } else if (W == 0) {
+    double best_cost = 0;
+    for (int cand : {1, 2, 3, 4, 6, 8, 12, 16, 24, 32, 48, 64}) {
+      for (bool up : {true, false}) {
+        double heaviest = 0;
+        long wgs = pack(cand, up, nullptr, &heaviest);
+        if (wgs < 0 || wgs > target) continue;
+        double cost = heaviest / cand;
+        // fewer lanes mean larger shares per lane and less FIFO memory: take more only for a clear gain
+        if (W == 0 || cost < best_cost * 0.97) { W = cand; round_up = up; best_cost = cost; }
+      }
+    }
+    if (W == 0) { W = 1; round_up = false; }
+  } else {
+    // explicit team width: use the sharing that gives the lighter heaviest workgroup within the target
+    double h_up = 0, h_dn = 0;
+    long n_up = pack(W, true, nullptr, &h_up), n_dn = pack(W, false, nullptr, &h_dn);
+    if (n_up < 0 || n_up > target) round_up = false;
+    else if (n_dn >= 0 && h_dn < h_up) round_up = false;
+  }
+  std::vector<std::vector<int>> bins;
+  {
+    long wgs = pack(W, round_up, &bins, nullptr);
+    if (wgs < 0) { msg = "a workgroup would have to multiplex too many thread blocks"; return GC3_ERR_RESIDENCY; }
+  }
+  const long active = (long)bins.size() * W;
+  if (active > resident) {
+    msg = "program needs " + std::to_string(active) + " resident workgroups of " + std::to_string(cfg.wg_size) +
+          " threads, the device holds " + std::to_string(resident);
+    return GC3_ERR_RESIDENCY;
+  }
+
+  // ---- placement: which die (XCD) runs which workgroup -----------------------------------------------
+  // Workgroup i is dispatched to die i mod 8.  Bins whose thread blocks talk to each other (connection
+  // or dependency) form a group; one copy of the group per lane is kept on one die where it fits.
+  std::vector<int> bin_of_tb(ntb, 0);
+  for (size_t b = 0; b < bins.size(); ++b)
+    for (int g : bins[b]) bin_of_tb[g] = (int)b;
+  Dsu bin_groups((int)bins.size());
+  for (int g = 0; g < ntb; ++g) bin_groups.join(bin_of_tb[g], bin_of_tb[groups.find(g)]);
+  std::vector<std::vector<uint32_t>> wg_lists;   // per workgroup: its fibers
+  if (cfg.xcd_placement == 2) {
+    for (size_t b = 0; b < bins.size(); ++b)
+      for (int w = 0; w < W; ++w) {
+        wg_lists.emplace_back();
+        for (int g : bins[b]) wg_lists.back().push_back((uint32_t)(g * W + w));
+      }
+  } else {
+    std::map<int, std::vector<int>> members;
+    for (int b = 0; b < (int)bins.size(); ++b) members[bin_groups.find(b)].push_back(b);
+    std::vector<std::vector<std::vector<uint32_t>>> per_xcd(kXcds);
+    std::vector<std::pair<size_t, int>> order;  // (size, root), large groups first
+    for (auto& kv : members) order.emplace_back(kv.second.size(), kv.first);
+    std::stable_sort(order.begin(), order.end(), [](auto& a, auto& b) { return a.first > b.first; });
+    // no die takes more than its fair share, so a group larger than that spills onto the next die
+    const size_t fair = (size_t)((active + kXcds - 1) / kXcds);
+    auto least_loaded = [&]() {
+      int best = 0;
+      for (int x = 1; x < kXcds; ++x)
+        if (per_xcd[x].size() < per_xcd[best].size()) best = x;
+      return best;
+    };
+    for (auto& o : order) {
+      for (int w = 0; w < W; ++w) {
+        int cur = least_loaded();
+        for (int b : members[o.second]) {
+          if (per_xcd[cur].size() >= fair) cur = least_loaded();
+          per_xcd[cur].emplace_back();
+          for (int g : bins[b]) per_xcd[cur].back().push_back((uint32_t)(g * W + w));
+        }
+      }
+    }
+    size_t longest = 0;
+    for (auto& v : per_xcd) longest = std::max(longest, v.size());
+    wg_lists.assign(longest * kXcds, {});
+    for (int x = 0; x < kXcds; ++x)
+      for (size_t k = 0; k < per_xcd[x].size(); ++k) wg_lists[k * kXcds + x] = per_xcd[x][k];
+  }
+  std::vector<uint32_t>& wg_begin = plan.wg_begin;
+  std::vector<uint32_t>& wg_fibers = plan.wg_fibers;
+  wg_begin.assign(1, 0);
+  wg_fibers.clear();
+  int max_fibers = 0;
+  for (auto& l : wg_lists) {
+    wg_fibers.insert(wg_fibers.end(), l.begin(), l.end());
+    wg_begin.push_back((uint32_t)wg_fibers.size());
+    max_fibers = std::max(max_fibers, (int)l.size());
+  }
+  const long grid = (long)wg_lists.size();
+
+
+  // Tile size: 32 KiB per chunk and workgroup unless given; halved (not below 16 KiB) while all FIFOs
+  // together exceed 256 MiB, the size of the memory-side cache they should stay in.
+  int tile_bytes = cfg.tile_bytes;
+  if (tile_bytes == 0) {
+    tile_bytes = 32768;
+    while (tile_bytes > 16384 && (uint64_t)nconn * W * cfg.fifo_slots * max_count * (uint64_t)tile_bytes > (256ull << 20))
+      tile_bytes /= 2;
+  }
+  plan.cfg.tile_bytes = tile_bytes;
+  const uint64_t slot_bytes = (uint64_t)max_count * (uint64_t)tile_bytes;
+  const uint64_t fifo_bytes = std::max<uint64_t>(16, (uint64_t)nconn * W * cfg.fifo_slots * slot_bytes);
+  if (slot_bytes > (1ull << 30) || fifo_bytes > (64ull << 30)) { msg = "FIFO memory too large"; return GC3_ERR_SIZE; }
+  plan.nconn = nconn;
+  plan.ntb = ntb;
+  plan.max_count = max_count;
+  plan.algorithmic_chunks = alg_chunks;
+  plan.info = gc3_comm_info{};
+  plan.info.team_width = W;
+  plan.info.wg_size = cfg.wg_size;
+  plan.info.grid = (int32_t)grid;
+  plan.info.active_wgs = (int32_t)active;
+  plan.info.max_resident_wgs = (int32_t)std::min<long>(resident, INT32_MAX);
+  plan.info.fifo_slots = cfg.fifo_slots;
+  plan.info.tile_bytes = tile_bytes;
+  plan.info.slot_bytes = (int32_t)slot_bytes;
+  plan.info.fifo_bytes = fifo_bytes;
+  plan.info.compute_units = cus;
+  plan.info.max_fibers_per_wg = max_fibers;
+  return GC3_OK;
+}
+
+}  // namespace gc3
+
+extern "C" int gc3_program_plan(const gc3_program* prog, const gc3_comm_config* cfg_in, int compute_units,
+                                int max_resident_wgs, gc3_comm_info* out) {
+  if (!prog || !out) { gc3::set_error("null argument"); return GC3_ERR_ARG; }
+  gc3_comm_config cfg{};
+  std::string msg;
+  int rc = gc3::resolve_config(cfg_in, cfg, msg);
+  gc3::Plan plan;
+  if (rc == GC3_OK) rc = gc3::make_plan(*prog, cfg, compute_units, max_resident_wgs, plan, msg);
+  if (rc != GC3_OK) { gc3::set_error(msg); return rc; }
+  *out = plan.info;
+  return GC3_OK;
+}

@@ -14,9 +14,7 @@ from . import binding as B
 from .inputs import ITEMSIZE, SENTINEL16, STORAGE
 
 
-def make_config(fifo_slots: int = 0, tile_bytes: int = 0, team_width: int = 0, wg_size: int = 0,
-                xcd_placement: int = 0, spin_limit_us: int = 0) -> B.CommConfig:
-    return B.CommConfig(fifo_slots, tile_bytes, team_width, wg_size, xcd_placement, 0, spin_limit_us)
+make_config = B.make_config
 
 
 class Collective:

@@ -121,6 +121,13 @@ def test_empty_input_is_a_noop():
     coll.run()
     coll.status()
     coll.close()
+    # AllToNext on a single rank has no thread block at all: nothing is launched, the output is untouched
+    coll = H.Collective(programs.alltonext(1, 1).to_text(), "f16", 64)
+    coll.fill_outputs_with_sentinel()
+    coll.run()
+    coll.status()
+    assert set(np.unique(coll.download("out")[0].view(np.uint16))) == {inputs.SENTINEL16}
+    coll.close()
 
 
 def test_largest_tile_and_slot_settings():
@@ -200,10 +207,10 @@ def test_api_errors_without_launch():
         B.gc3_comm_run(comm, 64, B.GC3_F16)
     assert e.value.status == B.GC3_ERR_UNBOUND
     B.gc3_comm_destroy(comm)
-    # a program that cannot be resident: 396 thread blocks x 64 lanes
+    # a program that cannot be resident: 24 ranks x 256 lanes
     prog = B.gc3_program_load(programs.alltonext(3, 8).to_text())
     with pytest.raises(B.Gc3Error) as e:
-        B.gc3_comm_create(prog, H.make_config(team_width=64, wg_size=512))
+        B.gc3_comm_create(prog, H.make_config(team_width=256, wg_size=512))
     assert e.value.status == B.GC3_ERR_RESIDENCY
     with pytest.raises(B.Gc3Error) as e:
         B.gc3_comm_create(prog, H.make_config(fifo_slots=9))

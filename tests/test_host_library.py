@@ -1,0 +1,227 @@
+"""Host-side logic of libgc3.so, no GPU needed: exports, IR loader, validator, planner."""
+import os
+import re
+
+import pytest
+
+import oracle
+from paper_2201_11840_amd import binding as B
+from paper_2201_11840_amd import programs
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def load(text):
+    return B.gc3_program_load(text)
+
+
+def status_of(fn, *a):
+    try:
+        fn(*a)
+        return B.GC3_OK
+    except B.Gc3Error as e:
+        return e.status
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "gc3.h")).read()
+    declared = set(re.findall(r"^(?:int|void|const char\*)\s+(gc3_[a-z_]+)\s*\(", header, flags=re.M))
+    assert declared == set(B.EXPORTS)
+    L = B.lib()
+    for name in declared:
+        assert hasattr(L, name), name
+
+
+def generated():
+    out = [programs.ring_allreduce(R, instances=k, fuse=f) for R in (2, 3, 8) for k in (1, 3) for f in (True, False)]
+    out += [programs.ring_allreduce(5, use_rrs=True), programs.multichannel_ring_allreduce(5, 2),
+            programs.allpairs_allreduce(4), programs.direct_alltoall(1), programs.direct_alltoall(8)]
+    out += [programs.hierarchical_allreduce(N, G) for N, G in ((2, 2), (2, 3), (3, 2), (2, 8), (3, 8))]
+    out += [programs.alltonext(N, G) for N, G in ((1, 1), (1, 4), (4, 1), (3, 8))]
+    out += [programs.twostep_alltoall(N, G) for N, G in ((1, 4), (4, 1), (2, 3), (3, 8))]
+    return out
+
+
+@pytest.mark.parametrize("prog", generated(), ids=lambda p: f"{p.name}_{p.num_ops()}")
+def test_loader_info_matches_the_generator(prog):
+    h = load(prog.to_text())
+    try:
+        B.gc3_program_validate(h, 2)
+        i = B.gc3_program_info_get(h)
+        assert (i.ranks, i.in_chunks, i.out_chunks, i.inplace) == (prog.ranks, prog.in_chunks, prog.out_chunks, int(prog.inplace))
+        assert i.num_tbs == prog.num_tbs() and i.num_instructions == prog.num_ops()
+        assert i.algorithmic_chunks == prog.algorithmic_chunks() and i.max_count == prog.max_count()
+        conns = {(r, t.send, t.chan) for r in range(prog.ranks) for t in prog.tbs[r]
+                 if any(o.opcode in ("send", "rcs", "rrcs", "rrs") for o in t.ops)}
+        assert i.num_connections == len(conns)
+        for r in range(prog.ranks):
+            assert B.gc3_program_scratch_chunks(h, r) == prog.scratch_chunks(r)
+    finally:
+        B.gc3_program_free(h)
+
+
+@pytest.mark.parametrize("prog", generated(), ids=lambda p: f"{p.name}_{p.num_ops()}")
+@pytest.mark.parametrize("slots", [1, 2, 8])
+def test_validator_deadlock_verdict_matches_the_oracle(prog, slots):
+    # two independent implementations of the bounded-FIFO execution must agree
+    h = load(prog.to_text())
+    try:
+        st = status_of(B.gc3_program_validate, h, slots)
+    finally:
+        B.gc3_program_free(h)
+    try:
+        oracle.run_symbolic(oracle.parse_program(prog.to_text()), slots=slots, order="random", seed=slots)
+        want = B.GC3_OK
+    except oracle.OracleDeadlock:
+        want = B.GC3_ERR_DEADLOCK
+    assert st == want
+
+
+GOOD = ("gc3ir 1\nname t\ncollective custom\ninplace 0\nprotocol simple\nranks 2\nchunks 2 2\n"
+        "rank 0 scratch 1 tbs 1\ntb 0 send 1 recv 1 chan 0 ops 2\nop send i 0 - 0 1 0 0\nop recv - 0 o 1 1 0 0\n"
+        "rank 1 scratch 0 tbs 1\ntb 0 send 0 recv 0 chan 0 ops 2\nop send i 1 - 0 1 0 0\nop recv - 0 o 0 1 0 0\nend\n")
+
+
+def test_good_text_loads_and_comments_are_ignored():
+    for text in (GOOD, "# leading comment\n" + GOOD.replace("ranks 2", "ranks 2   # two ranks"), GOOD.replace("\n", "\r\n")):
+        h = load(text)
+        B.gc3_program_validate(h, 1)
+        B.gc3_program_free(h)
+
+
+@pytest.mark.parametrize("mutate", [
+    lambda t: t.replace("gc3ir 1", "gc3ir 2"),
+    lambda t: t.replace("end\n", ""),
+    lambda t: t.replace("op send i 0 - 0 1 0 0", "op fly i 0 - 0 1 0 0"),
+    lambda t: t.replace("op send i 0 - 0 1 0 0", "op send q 0 - 0 1 0 0"),
+    lambda t: t.replace("op send i 0 - 0 1 0 0", "op send i 0 - 0 1 0 1 0"),      # dependency list too short
+    lambda t: t.replace("op send i 0 - 0 1 0 0", "op send i 0 - 0 0 0 0"),        # count 0
+    lambda t: t.replace("ops 2\nop send i 0", "ops 3\nop send i 0", 1),            # fewer ops than declared
+    lambda t: t.replace("rank 1 scratch", "rank 2 scratch"),
+    lambda t: t.replace("tb 0 send 0 recv 0", "tb 1 send 0 recv 0"),
+    lambda t: t.replace("ranks 2", "ranks two"),
+    lambda t: t + "name again\n",
+    lambda t: t.replace("chunks 2 2\n", ""),
+    lambda t: "",
+])
+def test_malformed_text_is_a_parse_error(mutate):
+    with pytest.raises(B.Gc3Error) as e:
+        load(mutate(GOOD))
+    assert e.value.status == B.GC3_ERR_PARSE
+
+
+def two_rank(ops0, ops1, tbs0=None, scratch=0):
+    def rank(r, tbs):
+        out = f"rank {r} scratch {scratch} tbs {len(tbs)}\n"
+        for b, (send, recv, chan, ops) in enumerate(tbs):
+            out += f"tb {b} send {send} recv {recv} chan {chan} ops {len(ops)}\n" + "".join(o + "\n" for o in ops)
+        return out
+    t0 = tbs0 if tbs0 is not None else [(1, 1, 0, ops0)]
+    return ("gc3ir 1\nname t\ncollective custom\ninplace 0\nprotocol simple\nranks 2\nchunks 2 2\n"
+            + rank(0, t0) + rank(1, [(0, 0, 0, ops1)]) + "end\n")
+
+
+SEND, RECV = "op send i 0 - 0 1 0 0", "op recv - 0 o 0 1 0 0"
+
+
+@pytest.mark.parametrize("text,want", [
+    (two_rank([SEND], [RECV]), B.GC3_OK),
+    # two thread blocks sending on one connection
+    (two_rank(None, [RECV, RECV], tbs0=[(1, -1, 0, [SEND]), (1, 1, 0, [SEND])]), B.GC3_ERR_INVALID_PROGRAM),
+    # send / receive size mismatch
+    (two_rank(["op send i 0 - 0 2 0 0"], [RECV]), B.GC3_ERR_INVALID_PROGRAM),
+    # message never received / receive never fed
+    (two_rank([SEND], []), B.GC3_ERR_INVALID_PROGRAM),
+    (two_rank([], [RECV]), B.GC3_ERR_INVALID_PROGRAM),
+    # dependency on a step that does not exist, on a step without has-dependent flag, on itself
+    (two_rank(None, [], tbs0=[(-1, -1, 0, ["op copy i 0 o 0 1 0 1 1 5"]), (-1, -1, 1, ["op copy i 1 o 1 1 1 0"])]), B.GC3_ERR_INVALID_PROGRAM),
+    (two_rank(None, [], tbs0=[(-1, -1, 0, ["op copy i 0 o 0 1 0 1 1 0"]), (-1, -1, 1, ["op copy i 1 o 1 1 0 0"])]), B.GC3_ERR_INVALID_PROGRAM),
+    (two_rank(None, [], tbs0=[(-1, -1, 0, ["op copy i 0 o 0 1 1 1 0 0"])]), B.GC3_ERR_INVALID_PROGRAM),
+    (two_rank(None, [], tbs0=[(-1, -1, 0, ["op copy i 0 o 0 1 0 1 1 0"]), (-1, -1, 1, ["op copy i 1 o 1 1 1 0"])]), B.GC3_OK),
+    # chunk index outside the buffer; scratch not declared; missing operand
+    (two_rank(["op send i 2 - 0 1 0 0"], [RECV]), B.GC3_ERR_INVALID_PROGRAM),
+    (two_rank(["op send i 1 - 0 2 0 0"], ["op recv - 0 o 0 2 0 0"]), B.GC3_ERR_INVALID_PROGRAM),
+    (two_rank(["op send s 0 - 0 1 0 0"], [RECV]), B.GC3_ERR_INVALID_PROGRAM),
+    (two_rank(["op send - 0 - 0 1 0 0"], [RECV]), B.GC3_ERR_INVALID_PROGRAM),
+    # send without a send peer, a rank as its own peer, peer out of range
+    (two_rank(None, [RECV], tbs0=[(-1, 1, 0, [SEND])]), B.GC3_ERR_INVALID_PROGRAM),
+    (two_rank(None, [RECV], tbs0=[(0, 1, 0, [SEND])]), B.GC3_ERR_INVALID_PROGRAM),
+    (two_rank(None, [RECV], tbs0=[(7, 1, 0, [SEND])]), B.GC3_ERR_INVALID_PROGRAM),
+    # cyclic wait: both receive first
+    (two_rank([RECV, SEND], [RECV, SEND]), B.GC3_ERR_DEADLOCK),
+    # cyclic dependency between two thread blocks of one rank
+    (two_rank(None, [], tbs0=[(-1, -1, 0, ["op copy i 0 o 0 1 1 1 1 0"]), (-1, -1, 1, ["op copy i 1 o 1 1 1 1 0 0"])]), B.GC3_ERR_DEADLOCK),
+    # three sends before the peer receives anything: fine with 2 slots only if the peer drains
+    (two_rank([SEND, SEND, SEND, RECV], [SEND, RECV, RECV, RECV]), B.GC3_OK),
+])
+def test_validator_cases(text, want):
+    h = load(text)
+    try:
+        assert status_of(B.gc3_program_validate, h, 2) == want, B.gc3_last_error()
+    finally:
+        B.gc3_program_free(h)
+
+
+def test_outstanding_sends_beyond_the_slot_count_deadlock():
+    # Section 6.1: a schedule with more than s outstanding sends deadlocks
+    text = two_rank([SEND, SEND, SEND, RECV, RECV, RECV], [SEND, SEND, SEND, RECV, RECV, RECV])
+    h = load(text)
+    try:
+        assert status_of(B.gc3_program_validate, h, 2) == B.GC3_ERR_DEADLOCK
+        assert status_of(B.gc3_program_validate, h, 3) == B.GC3_OK
+        assert status_of(B.gc3_program_validate, h, 0) == B.GC3_ERR_ARG
+        assert status_of(B.gc3_program_validate, h, 9) == B.GC3_ERR_ARG
+    finally:
+        B.gc3_program_free(h)
+
+
+# ---- planner ---------------------------------------------------------------------------------------
+
+def plan(prog, cus=256, resident=1792, **kw):
+    h = load(prog.to_text())
+    try:
+        return B.gc3_program_plan(h, B.make_config(**kw), cus, resident)
+    finally:
+        B.gc3_program_free(h)
+
+
+def test_plan_fills_the_device_without_exceeding_it():
+    for prog in generated():
+        i = plan(prog)
+        assert 1 <= i.team_width <= 64
+        assert i.active_wgs <= 4 * 256 or i.team_width == 1
+        assert i.active_wgs <= i.grid <= i.active_wgs + 7          # padding to a multiple of the 8 dies at most
+        assert (1 <= i.max_fibers_per_wg <= 32) or prog.num_tbs() == 0
+        assert i.slot_bytes == prog.max_count() * i.tile_bytes
+    i = plan(programs.ring_allreduce(8, instances=8))
+    assert (i.team_width, i.active_wgs, i.max_fibers_per_wg) == (16, 1024, 1)     # one lane per workgroup
+    assert i.fifo_bytes == 64 * 16 * 2 * 32768 and i.tile_bytes == 32768
+    i = plan(programs.hierarchical_allreduce(2, 8))
+    assert i.max_fibers_per_wg >= 2 and i.active_wgs == 1024     # light phases share workgroups
+    assert i.fifo_bytes <= 256 << 20 and i.tile_bytes < 32768   # tile shrunk to keep the FIFOs cache sized
+    i = plan(programs.alltonext(3, 8))
+    assert i.active_wgs <= 1024 and i.max_fibers_per_wg >= 2      # 396 thread blocks cannot each own 4 lanes
+
+
+def test_plan_respects_configuration_and_limits():
+    prog = programs.ring_allreduce(8, instances=8)
+    i = plan(prog, team_width=4, tile_bytes=4096, fifo_slots=2, wg_size=512)
+    assert (i.team_width, i.tile_bytes, i.fifo_slots, i.wg_size) == (4, 4096, 2, 512)
+    assert i.active_wgs == 64 * 4 and i.fifo_bytes == 64 * 4 * 2 * 4096
+    i = plan(prog, target_wgs=128)
+    assert i.active_wgs <= 128
+    i = plan(prog, xcd_placement=2)
+    assert i.grid == i.active_wgs
+    small = plan(prog, cus=8, resident=16)                     # a tiny device: thread blocks must share
+    assert small.active_wgs <= 16 and small.max_fibers_per_wg >= 4
+    for bad in (dict(fifo_slots=9), dict(tile_bytes=24), dict(tile_bytes=2 << 20), dict(wg_size=100),
+                dict(team_width=257), dict(xcd_placement=3), dict(target_wgs=-1)):
+        with pytest.raises(B.Gc3Error) as e:
+            plan(prog, **bad)
+        assert e.value.status == B.GC3_ERR_ARG
+    with pytest.raises(B.Gc3Error) as e:
+        plan(programs.alltonext(3, 8), team_width=256)             # 24 ranks x 256 lanes cannot be resident
+    assert e.value.status == B.GC3_ERR_RESIDENCY
+    with pytest.raises(B.Gc3Error) as e:
+        plan(programs.ring_allreduce(4), fifo_slots=1)             # fused ring needs two slots
+    assert e.value.status == B.GC3_ERR_DEADLOCK
