@@ -115,7 +115,6 @@ def main() -> int:
     ap.add_argument("--team-width", type=int, default=0)
     ap.add_argument("--fifo-slots", type=int, default=0)
     ap.add_argument("--wg-size", type=int, default=0)
-    ap.add_argument("--xcd-placement", type=int, default=0)
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py: this build runs on ONE GPU: the ranks of a GC3-IR program are virtual ranks in one "
@@ -131,7 +130,7 @@ def main() -> int:
         log(f"unknown workload {args.workload}; known: {sorted(table)}")
         return 2
     cfg = harness.make_config(fifo_slots=args.fifo_slots, tile_bytes=args.tile_bytes, team_width=args.team_width,
-                              wg_size=args.wg_size, xcd_placement=args.xcd_placement)
+                              wg_size=args.wg_size)
 
     # ---- headline workload: seeded host inputs (shared with the CPU baseline) ---------------------
     w = table[args.workload]
@@ -162,7 +161,7 @@ def main() -> int:
         p = oracle.parse_program(text)
         log("[bench] cpu baseline (oracle) ...")
         t_total, reps = 0.0, 0
-        while reps < 3 and t_total < 10.0:
+        while reps < 200 and t_total < 10.0:          # about 10 s of oracle work
             host_in = [a.copy() for a in ins]
             host_out = None if p.inplace else inputs.sentinel_outputs(p.ranks, gpu_out[0].size, w.dtype)
             t0 = time.perf_counter()
@@ -180,7 +179,7 @@ def main() -> int:
     # ---- the other configurations (timing only, device-generated inputs) ---------------------------
     sweep = [head]
     if not args.no_sweep:
-        for w2 in workloads.all_workloads():
+        for w2 in workloads.all_workloads() + workloads.next_row_workloads():
             if w2.name == w.name:
                 continue
             log(f"[bench] timing {w2.name}")

@@ -88,18 +88,22 @@ typedef struct gc3_comm_config {
                               rank may share a workgroup.  0 = choose W and the sharing so that the
                               heaviest workgroup is lightest */
   int32_t wg_size;         /* threads per workgroup: 64, 128, 256 or 512; default 256 */
-  int32_t xcd_placement;   /* 0 default (on), 1 on: place the workgroups of connected thread blocks
-                              on one XCD; 2 off: workgroups in program order */
+  int32_t reserved0;       /* must be 0 */
   int32_t target_wgs;      /* workgroups the schedule aims at (never more than can be resident);
                               0 = four per compute unit */
   uint64_t spin_limit_us;  /* longest a workgroup waits on one flag before the run is abandoned
                               with GC3_ERR_TIMEOUT; default 10 s */
+  int32_t debug_hold;      /* test facility for the failure path: 1 = every workgroup first waits for a
+                              start word that nobody sets, so each run ends, after spin_limit_us, with
+                              GC3_ERR_TIMEOUT and all workgroups leaving through the error path */
+  int32_t min_lane_bytes;  /* a run splits a chunk over at most chunk bytes / min_lane_bytes lanes (at least
+                              one): small chunks are not worth spreading; multiple of 16, default 8192 */
 } gc3_comm_config;
 
 typedef struct gc3_comm_info {
   int32_t team_width;        /* W in use */
   int32_t wg_size;
-  int32_t grid;              /* workgroups launched per run (including idle padding) */
+  int32_t grid;              /* workgroups of a run that uses all lanes: team_width x wgs_per_lane */
   int32_t active_wgs;        /* workgroups that execute at least one thread-block lane */
   int32_t max_resident_wgs;  /* occupancy x compute units */
   int32_t fifo_slots;
@@ -108,6 +112,8 @@ typedef struct gc3_comm_info {
   uint64_t fifo_bytes;       /* device memory held by all FIFOs */
   int32_t compute_units;
   int32_t max_fibers_per_wg; /* most thread-block lanes multiplexed by one workgroup (1 = none shared) */
+  int32_t wgs_per_lane;      /* a run on small chunks launches only active lanes x wgs_per_lane workgroups */
+  int32_t reserved0;
 } gc3_comm_info;
 
 /* Message for the most recent error on this thread.  host; owned by the library; never null. */

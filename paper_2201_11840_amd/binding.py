@@ -44,21 +44,24 @@ class ProgramInfo(C.Structure):
 
 class CommConfig(C.Structure):
     _fields_ = [("fifo_slots", C.c_int32), ("tile_bytes", C.c_int32), ("team_width", C.c_int32),
-                ("wg_size", C.c_int32), ("xcd_placement", C.c_int32), ("target_wgs", C.c_int32),
-                ("spin_limit_us", C.c_uint64)]
+                ("wg_size", C.c_int32), ("reserved0", C.c_int32), ("target_wgs", C.c_int32),
+                ("spin_limit_us", C.c_uint64), ("debug_hold", C.c_int32), ("min_lane_bytes", C.c_int32)]
 
 
 def make_config(fifo_slots: int = 0, tile_bytes: int = 0, team_width: int = 0, wg_size: int = 0,
-                xcd_placement: int = 0, spin_limit_us: int = 0, target_wgs: int = 0) -> CommConfig:
+                spin_limit_us: int = 0, target_wgs: int = 0, debug_hold: int = 0,
+                min_lane_bytes: int = 0) -> CommConfig:
     """A gc3_comm_config; zero fields select the library's defaults."""
-    return CommConfig(fifo_slots, tile_bytes, team_width, wg_size, xcd_placement, target_wgs, spin_limit_us)
+    return CommConfig(fifo_slots, tile_bytes, team_width, wg_size, 0, target_wgs, spin_limit_us,
+                      debug_hold, min_lane_bytes)
 
 
 class CommInfo(C.Structure):
     _fields_ = [("team_width", C.c_int32), ("wg_size", C.c_int32), ("grid", C.c_int32),
                 ("active_wgs", C.c_int32), ("max_resident_wgs", C.c_int32), ("fifo_slots", C.c_int32),
                 ("tile_bytes", C.c_int32), ("slot_bytes", C.c_int32), ("fifo_bytes", C.c_uint64),
-                ("compute_units", C.c_int32), ("max_fibers_per_wg", C.c_int32)]
+                ("compute_units", C.c_int32), ("max_fibers_per_wg", C.c_int32),
+                ("wgs_per_lane", C.c_int32), ("reserved0", C.c_int32)]
 
 
 class Gc3Error(RuntimeError):

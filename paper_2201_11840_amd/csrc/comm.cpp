@@ -41,7 +41,9 @@ struct gc3_comm {
   int device = 0;
   int32_t ranks = 0, in_chunks = 0, out_chunks = 0;
   bool inplace = false;
-  bool has_deps = false;  // some instruction waits on another thread block's semaphore
+  bool has_deps = false;    // some instruction waits on another thread block's semaphore
+  bool debug_hold = false;  // failure-path test facility
+  uint64_t min_lane_bytes = 8192;
   uint64_t algorithmic_chunks = 0;
   std::vector<int32_t> scratch_chunks;
   gc3_comm_info info{};
@@ -138,6 +140,8 @@ int gc3_comm_create(const gc3_program* prog, const gc3_comm_config* cfg_in, gc3_
   c->inplace = prog->inplace;
   c->algorithmic_chunks = plan.algorithmic_chunks;
   c->has_deps = !plan.deps.empty();
+  c->debug_hold = cfg.debug_hold != 0;
+  c->min_lane_bytes = (uint64_t)cfg.min_lane_bytes;
   for (int r = 0; r < R; ++r) c->scratch_chunks.push_back(prog->rank[r].scratch_chunks);
   c->bufs.assign((size_t)R * 3, nullptr);
   c->scratch_bytes.assign(R, 0);
@@ -233,14 +237,19 @@ int gc3_comm_run(gc3_comm* comm, size_t elems_per_rank, gc3_dtype dtype, gc3_red
   p.flags = comm->d_flags;
   p.sems = comm->d_sems;
   p.error = comm->d_error;
+  p.hold = comm->debug_hold ? comm->d_error + 32 : nullptr;   // a word of the zeroed error block nobody writes
   p.run_base = (++comm->run_number) << 32;
   p.chunk_bytes = cb;
   p.spin_limit_ticks = comm->spin_limit_ticks;
   p.W = (uint32_t)comm->info.team_width;
+  // small chunks are not worth splitting over all lanes: every active lane gets at least min_lane_bytes
+  p.W_active = (uint32_t)std::max<uint64_t>(1, std::min<uint64_t>(p.W, cb / comm->min_lane_bytes));
   p.slots = (uint32_t)comm->info.fifo_slots;
   p.tile_bytes = (uint32_t)comm->info.tile_bytes;
   p.slot_bytes = (uint32_t)comm->info.slot_bytes;
-  int e = launch_interpreter((int)dtype, comm->has_deps, (unsigned)comm->info.grid, (unsigned)comm->info.wg_size, hip_stream, p);
+  // lane-major grid: the workgroups of the active lanes are a prefix
+  const unsigned grid = p.W_active * (unsigned)comm->info.wgs_per_lane;
+  int e = launch_interpreter((int)dtype, comm->has_deps, grid, (unsigned)comm->info.wg_size, hip_stream, p);
   if (e != 0) return hip_fail((hipError_t)e, "interpreter launch");
   return GC3_OK;
 }

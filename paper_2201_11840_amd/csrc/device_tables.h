@@ -43,10 +43,13 @@ struct KParams {
   uint64_t* flags;         // [((conn*W + lane)*2 + {0 tail, 1 head}) * kFlagStrideWords]
   uint64_t* sems;          // [(tb*W + lane) * kFlagStrideWords]
   uint32_t* error;         // 0 = fine, else a gc3_status (negated) set by the first failing workgroup
+  const uint32_t* hold;    // null, or a start word every workgroup waits for (failure-path tests)
   uint64_t run_base;       // run number << 32; all flag values of this run lie above it
   uint64_t chunk_bytes;
   uint64_t spin_limit_ticks;  // of the 100 MHz wall clock
   uint32_t W, slots, tile_bytes, slot_bytes;
+  uint32_t W_active;       // lanes that own bytes in this run (<= W); the others own nothing and finish at once
+  uint32_t pad0;
 };
 
 }  // namespace gc3

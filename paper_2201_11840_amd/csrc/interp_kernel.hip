@@ -111,6 +111,13 @@ constexpr int kPolNt = 2, kPolSc1 = 16;   // (bit 0 would be sc0)
 #ifndef GC3_UNROLL
 #define GC3_UNROLL 4
 #endif
+// 1 = stage the FIFO payload of the receiving instructions through LDS with direct-to-LDS buffer loads
+// (no VGPRs held by loads in flight).  Measured on MI355X it does not beat the register path (the
+// interpreter is bound by the fabric, not by registers), so it is off; kept for A/B measurements.
+#ifndef GC3_LDS_STAGE
+#define GC3_LDS_STAGE 0
+#endif
+constexpr uint32_t kStageBytes = 32768;   // LDS staging area per workgroup
 
 typedef __amdgpu_buffer_rsrc_t rsrc_t;
 
@@ -147,6 +154,47 @@ __device__ __forceinline__ void move_tile(rsrc_t in0, rsrc_t in1, rsrc_t out0, r
   }
 }
 
+// Same contract as move_tile, but in0 (a FIFO slot) is first brought into LDS by direct-to-LDS loads:
+// wavefront w's k-th load writes elements [k*nthreads + 64w, +64) to consecutive 16-byte LDS cells, so
+// element i sits at LDS byte 16*i and thread i mod nthreads reads back only what its own wavefront
+// loaded (no workgroup barrier, just the wait for the loads).
+template <bool IN1, bool OUT1, int DT, int P_IN0, int P_IN1, int P_OUT0, int P_OUT1>
+__device__ __forceinline__ void move_tile_staged(rsrc_t in0, rsrc_t in1, rsrc_t out0, rsrc_t out1, uint32_t nvec,
+                                                 uint32_t tid, uint32_t nthreads, unsigned char* stage) {
+  typedef __attribute__((address_space(3))) void lds_void;
+  const uint32_t cap = kStageBytes >> 4;                       // elements per staging round
+  const uint32_t wave_first = tid & ~63u;
+  for (uint32_t r0 = 0; r0 < nvec; r0 += cap) {
+    const uint32_t n = nvec - r0 < cap ? nvec - r0 : cap;
+    for (uint32_t k = 0; k < n; k += nthreads)
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(in0, (lds_void*)(stage + ((k + wave_first) << 4)), 16,
+                                               (r0 + k + tid) << 4, 0, 0, P_IN0);
+    const uint32_t step = nthreads * GC3_UNROLL;
+    for (uint32_t base = tid; base < n; base += step) {
+      u32x4 a[GC3_UNROLL], b[GC3_UNROLL];
+      if (IN1) {
+#pragma unroll
+        for (int u = 0; u < GC3_UNROLL; ++u)
+          b[u] = __builtin_amdgcn_raw_buffer_load_b128(in1, (r0 + base + u * nthreads) << 4, 0, P_IN1);
+      }
+      __builtin_amdgcn_s_waitcnt(0);                           // staged loads (and in1) have landed
+#pragma unroll
+      for (int u = 0; u < GC3_UNROLL; ++u) {
+        const uint32_t i = base + u * nthreads;
+        a[u] = i < n ? *(const u32x4*)(stage + (i << 4)) : u32x4{0, 0, 0, 0};
+        if (IN1) a[u] = add_vec<DT>(a[u], b[u]);
+      }
+#pragma unroll
+      for (int u = 0; u < GC3_UNROLL; ++u) {
+        __builtin_amdgcn_raw_buffer_store_b128(a[u], out0, (r0 + base + u * nthreads) << 4, 0, P_OUT0);
+        if (OUT1) __builtin_amdgcn_raw_buffer_store_b128(a[u], out1, (r0 + base + u * nthreads) << 4, 0, P_OUT1);
+      }
+    }
+    __builtin_amdgcn_s_waitcnt(0);
+    __builtin_amdgcn_wave_barrier();                           // this wavefront's cells may be reused
+  }
+}
+
 __device__ __forceinline__ uint64_t load_flag(const uint64_t* p) {
   return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
@@ -180,23 +228,46 @@ __global__ void __launch_bounds__(512) gc3_interpreter(KParams p) {
   __shared__ uint32_t f_send[kMaxFibersPerWg], f_recv[kMaxFibersPerWg];
   __shared__ uint64_t f_off0[kMaxFibersPerWg], f_share[kMaxFibersPerWg];
   __shared__ int s_res[2];
+#if GC3_LDS_STAGE
+  __shared__ __attribute__((aligned(16))) unsigned char s_stage[kStageBytes];
+#endif
   const uint32_t tid = threadIdx.x, nthreads = blockDim.x;
   const uint32_t fbeg = p.wg_begin[blockIdx.x];
   const uint32_t nf = p.wg_begin[blockIdx.x + 1] - fbeg;
   if (nf == 0) return;
+  if (p.hold) {
+    // failure-path test facility: wait (bounded) for a start word that the host never sets
+    if (tid == 0) {
+      int res = 1;
+      const uint64_t start = wall_clock64();
+      while (__hip_atomic_load(p.hold, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0) {
+        __builtin_amdgcn_s_sleep(8);
+        if (__hip_atomic_load(p.error, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) { res = -1; break; }
+        if (wall_clock64() - start > p.spin_limit_ticks) {
+          atomicCAS(p.error, 0u, (uint32_t)(-GC3_ERR_TIMEOUT));
+          res = -1;
+          break;
+        }
+      }
+      s_res[0] = res;
+    }
+    __syncthreads();
+    if (s_res[0] < 0) return;
+    __syncthreads();
+  }
   const uint32_t W = p.W;
   const uint32_t tile = p.tile_bytes;
   if (tid < nf) {
     const uint32_t fid = p.wg_fibers[fbeg + tid];
     const uint64_t U = p.chunk_bytes >> 4;
-    const uint64_t o = lane_begin(U, fid % W, W);
+    const uint64_t o = lane_begin(U, fid % W, p.W_active);
     f_id[tid] = fid;
     f_t[tid] = 0;
     f_s[tid] = 0;
     f_send[tid] = 0;
     f_recv[tid] = 0;
     f_off0[tid] = o;
-    f_share[tid] = lane_begin(U, fid % W + 1, W) - o;
+    f_share[tid] = lane_begin(U, fid % W + 1, p.W_active) - o;
   }
   uint32_t live = nf, phase = 0;
   uint64_t last_progress = wall_clock64();
@@ -298,13 +369,21 @@ __global__ void __launch_bounds__(512) gc3_interpreter(KParams p) {
           const rsrc_t ss = make_rsrc(sslot + (uint64_t)j * len, sslot ? len : 0);
           switch (op) {
             case GC3_OP_SEND:   move_tile<false, false, DT, UL, 0, SS, 0>(src, src, ss, ss, nvec, tid, nthreads); break;
-            case GC3_OP_RECV:   move_tile<false, false, DT, SL, 0, US, 0>(rs, rs, dst, dst, nvec, tid, nthreads); break;
             case GC3_OP_COPY:   move_tile<false, false, DT, UL, 0, US, 0>(src, src, dst, dst, nvec, tid, nthreads); break;
             case GC3_OP_REDUCE: move_tile<true, false, DT, UL, UL, US, 0>(dst, src, dst, dst, nvec, tid, nthreads); break;
+#if GC3_LDS_STAGE
+            case GC3_OP_RECV:   move_tile_staged<false, false, DT, SL, 0, US, 0>(rs, rs, dst, dst, nvec, tid, nthreads, s_stage); break;
+            case GC3_OP_RRC:    move_tile_staged<true, false, DT, SL, UL, US, 0>(rs, src, dst, dst, nvec, tid, nthreads, s_stage); break;
+            case GC3_OP_RCS:    move_tile_staged<false, true, DT, SL, 0, US, SS>(rs, rs, dst, ss, nvec, tid, nthreads, s_stage); break;
+            case GC3_OP_RRCS:   move_tile_staged<true, true, DT, SL, UL, US, SS>(rs, src, dst, ss, nvec, tid, nthreads, s_stage); break;
+            case GC3_OP_RRS:    move_tile_staged<true, false, DT, SL, UL, SS, 0>(rs, src, ss, ss, nvec, tid, nthreads, s_stage); break;
+#else
+            case GC3_OP_RECV:   move_tile<false, false, DT, SL, 0, US, 0>(rs, rs, dst, dst, nvec, tid, nthreads); break;
             case GC3_OP_RRC:    move_tile<true, false, DT, SL, UL, US, 0>(rs, src, dst, dst, nvec, tid, nthreads); break;
             case GC3_OP_RCS:    move_tile<false, true, DT, SL, 0, US, SS>(rs, rs, dst, ss, nvec, tid, nthreads); break;
             case GC3_OP_RRCS:   move_tile<true, true, DT, SL, UL, US, SS>(rs, src, dst, ss, nvec, tid, nthreads); break;
             case GC3_OP_RRS:    move_tile<true, false, DT, SL, UL, SS, 0>(rs, src, ss, ss, nvec, tid, nthreads); break;
+#endif
             default: break;
           }
         }

@@ -15,18 +15,6 @@
 
 namespace gc3 {
 
-namespace {
-constexpr int kXcds = 8;  // MI355X: 8 accelerator dies (XCDs), workgroup i is dispatched to die i mod 8
-
-// Union-find: thread blocks joined by a connection or a dependency form one group.
-struct Dsu {
-  std::vector<int> p;
-  explicit Dsu(int n) : p(n) { std::iota(p.begin(), p.end(), 0); }
-  int find(int x) { while (p[x] != x) x = p[x] = p[p[x]]; return x; }
-  void join(int a, int b) { p[find(a)] = find(b); }
-};
-}  // namespace
-
 int resolve_config(const gc3_comm_config* cfg_in, gc3_comm_config& cfg, std::string& msg) {
   cfg = gc3_comm_config{};
   if (cfg_in) cfg = *cfg_in;
@@ -43,9 +31,12 @@ int resolve_config(const gc3_comm_config* cfg_in, gc3_comm_config& cfg, std::str
     return GC3_ERR_ARG;
   }
   if (cfg.team_width < 0 || cfg.team_width > 256) { msg = "team_width must be 0..256"; return GC3_ERR_ARG; }
-  if (cfg.xcd_placement < 0 || cfg.xcd_placement > 2) { msg = "xcd_placement must be 0, 1 or 2"; return GC3_ERR_ARG; }
 
   if (cfg.target_wgs < 0) { msg = "target_wgs must not be negative"; return GC3_ERR_ARG; }
+  if (cfg.reserved0 != 0) { msg = "reserved0 must be 0"; return GC3_ERR_ARG; }
+  if (cfg.debug_hold < 0 || cfg.debug_hold > 1) { msg = "debug_hold must be 0 or 1"; return GC3_ERR_ARG; }
+  if (cfg.min_lane_bytes == 0) cfg.min_lane_bytes = 8192;
+  if (cfg.min_lane_bytes < 16 || cfg.min_lane_bytes % 16) { msg = "min_lane_bytes must be a positive multiple of 16"; return GC3_ERR_ARG; }
   return GC3_OK;
 }
 
@@ -75,8 +66,6 @@ int make_plan(const gc3_program& prog, const gc3_comm_config& cfg, int cus, long
   tbs.assign(ntb, DTb{});
   instrs.clear();
   deps.clear();
-  Dsu groups(ntb);
-  std::map<int, int> conn_first_tb;
   int max_count = 1;
   uint64_t alg_chunks = 0;
   for (int r = 0; r < R; ++r) {
@@ -107,17 +96,10 @@ int make_plan(const gc3_program& prog, const gc3_comm_config& cfg, int cus, long
           dd.step = (uint32_t)dp.second;
           dd.ninstr = (uint32_t)prog.rank[r].tbs[dp.first].instrs.size();
           deps.push_back(dd);
-          groups.join(g, (int)dd.tb);
         }
         instrs.push_back(di);
         max_count = std::max(max_count, in.count);
         alg_chunks += (uint64_t)op_traffic(in.op) * (uint64_t)in.count;
-      }
-      for (int c : {d.send_conn, d.recv_conn}) {
-        if (c < 0) continue;
-        auto it = conn_first_tb.find(c);
-        if (it == conn_first_tb.end()) conn_first_tb[c] = g;
-        else groups.join(g, it->second);
       }
     }
   }
@@ -214,52 +196,18 @@ int make_plan(const gc3_program& prog, const gc3_comm_config& cfg, int cus, long
     return GC3_ERR_RESIDENCY;
   }
 
-  // ---- placement: which die (XCD) runs which workgroup -----------------------------------------------
-  // Workgroup i is dispatched to die i mod 8.  Bins whose thread blocks talk to each other (connection
-  // or dependency) form a group; one copy of the group per lane is kept on one die where it fits.
-  std::vector<int> bin_of_tb(ntb, 0);
-  for (size_t b = 0; b < bins.size(); ++b)
-    for (int g : bins[b]) bin_of_tb[g] = (int)b;
-  Dsu bin_groups((int)bins.size());
-  for (int g = 0; g < ntb; ++g) bin_groups.join(bin_of_tb[g], bin_of_tb[groups.find(g)]);
+  // ---- grid order: lane-major ------------------------------------------------------------------------
+  // Workgroup index = lane * bins + bin.  A run whose chunks are too small to be worth W lanes uses only
+  // the first lanes and launches just that prefix of the grid.  Consecutive workgroups are dispatched
+  // round-robin over the 8 dies (XCDs), so every prefix is spread evenly.  (Placing connected thread
+  // blocks on one die was measured and makes no difference: FIFO payload and flags bypass the
+  // per-die L2 by design, so nothing is shared through it.)
   std::vector<std::vector<uint32_t>> wg_lists;   // per workgroup: its fibers
-  if (cfg.xcd_placement == 2) {
-    for (size_t b = 0; b < bins.size(); ++b)
-      for (int w = 0; w < W; ++w) {
-        wg_lists.emplace_back();
-        for (int g : bins[b]) wg_lists.back().push_back((uint32_t)(g * W + w));
-      }
-  } else {
-    std::map<int, std::vector<int>> members;
-    for (int b = 0; b < (int)bins.size(); ++b) members[bin_groups.find(b)].push_back(b);
-    std::vector<std::vector<std::vector<uint32_t>>> per_xcd(kXcds);
-    std::vector<std::pair<size_t, int>> order;  // (size, root), large groups first
-    for (auto& kv : members) order.emplace_back(kv.second.size(), kv.first);
-    std::stable_sort(order.begin(), order.end(), [](auto& a, auto& b) { return a.first > b.first; });
-    // no die takes more than its fair share, so a group larger than that spills onto the next die
-    const size_t fair = (size_t)((active + kXcds - 1) / kXcds);
-    auto least_loaded = [&]() {
-      int best = 0;
-      for (int x = 1; x < kXcds; ++x)
-        if (per_xcd[x].size() < per_xcd[best].size()) best = x;
-      return best;
-    };
-    for (auto& o : order) {
-      for (int w = 0; w < W; ++w) {
-        int cur = least_loaded();
-        for (int b : members[o.second]) {
-          if (per_xcd[cur].size() >= fair) cur = least_loaded();
-          per_xcd[cur].emplace_back();
-          for (int g : bins[b]) per_xcd[cur].back().push_back((uint32_t)(g * W + w));
-        }
-      }
+  for (int w = 0; w < W; ++w)
+    for (size_t b = 0; b < bins.size(); ++b) {
+      wg_lists.emplace_back();
+      for (int g : bins[b]) wg_lists.back().push_back((uint32_t)(g * W + w));
     }
-    size_t longest = 0;
-    for (auto& v : per_xcd) longest = std::max(longest, v.size());
-    wg_lists.assign(longest * kXcds, {});
-    for (int x = 0; x < kXcds; ++x)
-      for (size_t k = 0; k < per_xcd[x].size(); ++k) wg_lists[k * kXcds + x] = per_xcd[x][k];
-  }
   std::vector<uint32_t>& wg_begin = plan.wg_begin;
   std::vector<uint32_t>& wg_fibers = plan.wg_fibers;
   wg_begin.assign(1, 0);
@@ -293,6 +241,7 @@ int make_plan(const gc3_program& prog, const gc3_comm_config& cfg, int cus, long
   plan.info.team_width = W;
   plan.info.wg_size = cfg.wg_size;
   plan.info.grid = (int32_t)grid;
+  plan.info.wgs_per_lane = (int32_t)bins.size();
   plan.info.active_wgs = (int32_t)active;
   plan.info.max_resident_wgs = (int32_t)std::min<long>(resident, INT32_MAX);
   plan.info.fifo_slots = cfg.fifo_slots;

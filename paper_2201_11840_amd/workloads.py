@@ -62,5 +62,24 @@ def all_workloads() -> List[Workload]:
             hier_ar_2x8(), alltonext_3x8()]
 
 
+def next_row_workloads() -> List[Workload]:
+    """Programs beyond the five benchmark configurations: the rrs fusion (Section 4.2), All Pairs
+    AllReduce (Section 7.1.2), one logical ring spread over several channels in the paper's
+    32 KB - 3 MB regime (Section 7.1.1), and Two-Step AllToAll (Section 7.3)."""
+    return [
+        Workload("ring_allreduce_rrs_r8_x8_f32_64MiB", lambda: programs.ring_allreduce(8, instances=8, use_rrs=True),
+                 "f32", 64 * MiB, "uniform", 61840),
+        Workload("allpairs_allreduce_r8_f32_64MiB", lambda: programs.allpairs_allreduce(8), "f32", 64 * MiB, "uniform", 62840),
+        Workload("allpairs_allreduce_r8_f32_256KiB", lambda: programs.allpairs_allreduce(8), "f32", MiB // 4, "uniform", 62841),
+        Workload("mc_ring_allreduce_r8_c4_f32_256KiB", lambda: programs.multichannel_ring_allreduce(8, 4),
+                 "f32", MiB // 4, "uniform", 63840),
+        Workload("ring_allreduce_r8_f32_256KiB", lambda: programs.ring_allreduce(8), "f32", MiB // 4, "uniform", 63841),
+        Workload("mc_ring_allreduce_r8_c4_f32_2MiB", lambda: programs.multichannel_ring_allreduce(8, 4),
+                 "f32", 2 * MiB, "uniform", 63842),
+        Workload("ring_allreduce_r8_f32_2MiB", lambda: programs.ring_allreduce(8), "f32", 2 * MiB, "uniform", 63843),
+        Workload("twostep_alltoall_3x8_f16_48MiB", lambda: programs.twostep_alltoall(3, 8), "f16", 48 * MiB, "normal", 64840),
+    ]
+
+
 def by_name() -> Dict[str, Workload]:
-    return {w.name: w for w in all_workloads()}
+    return {w.name: w for w in all_workloads() + next_row_workloads()}

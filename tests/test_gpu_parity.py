@@ -61,7 +61,7 @@ def run_case(prog, dtype, elems, dist="normal", seed=1234, cfg=None, repeats=1, 
 
 def small_cfg(**kw):
     H = _harness()
-    base = dict(fifo_slots=2, tile_bytes=1024, team_width=3)
+    base = dict(fifo_slots=2, tile_bytes=1024, team_width=3, min_lane_bytes=16)   # every lane active even on tiny chunks
     base.update(kw)
     return H.make_config(**base)
 
@@ -131,8 +131,8 @@ def test_empty_input_is_a_noop():
 
 
 def test_largest_tile_and_slot_settings():
-    # tile_bytes at its maximum (1 MiB), 8 slots, 512-thread workgroups, placement off
-    cfg = _harness().make_config(fifo_slots=8, tile_bytes=1 << 20, team_width=1, wg_size=512, xcd_placement=2)
+    # tile_bytes at its maximum (1 MiB), 8 slots, 512-thread workgroups
+    cfg = _harness().make_config(fifo_slots=8, tile_bytes=1 << 20, team_width=1, wg_size=512)
     run_case(programs.ring_allreduce(3), "f32", 3 * (3 << 18) + 3 * 4, "uniform", 8, cfg)   # chunk = 3 MiB + 16 B
     cfg = _harness().make_config(fifo_slots=8, tile_bytes=16, team_width=1, wg_size=64)
     run_case(programs.ring_allreduce(3), "f32", 3 * 100, "uniform", 9, cfg)                 # 25 tiles of one unit
@@ -221,6 +221,33 @@ def test_api_errors_without_launch():
         B.gc3_comm_create(prog, H.make_config(fifo_slots=1))     # fused ring needs two slots
     assert e.value.status == B.GC3_ERR_DEADLOCK
     B.gc3_program_free(prog)
+
+
+def test_timeout_poisons_and_reset_recovers():
+    # every workgroup waits (bounded by spin_limit_us) for a start word the host never sets: the run is
+    # abandoned through the kernel's error path, all workgroups exit, the communicator is poisoned
+    H = _harness()
+    from paper_2201_11840_amd import binding as B
+    prog = programs.hierarchical_allreduce(2, 3)
+    text = prog.to_text()
+    elems = 6 * 4096
+    ins = inputs.make_inputs(6, elems, "f32", "uniform", 5)
+    coll = H.Collective(text, "f32", elems, H.make_config(spin_limit_us=20000, debug_hold=1))
+    coll.upload(ins)
+    for _ in range(2):
+        coll.run()
+        with pytest.raises(B.Gc3Error) as e:
+            coll.status()
+        assert e.value.status == B.GC3_ERR_TIMEOUT
+        with pytest.raises(B.Gc3Error) as e:
+            coll.run()
+        assert e.value.status == B.GC3_ERR_POISONED
+        coll.reset()
+    for g, a in zip(coll.download(), ins):
+        assert g.tobytes() == a.tobytes()                    # nothing was moved
+    coll.close()
+    # the same buffers' contents through a normal communicator afterwards
+    run_case(prog, "f32", elems, "uniform", 5, small_cfg())
 
 
 # ---- the benchmark configurations, default launch configuration -------------------------------------

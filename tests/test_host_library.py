@@ -190,7 +190,7 @@ def test_plan_fills_the_device_without_exceeding_it():
         i = plan(prog)
         assert 1 <= i.team_width <= 64
         assert i.active_wgs <= 4 * 256 or i.team_width == 1
-        assert i.active_wgs <= i.grid <= i.active_wgs + 7          # padding to a multiple of the 8 dies at most
+        assert i.grid == i.active_wgs == i.team_width * i.wgs_per_lane   # lane-major grid, no padding
         assert (1 <= i.max_fibers_per_wg <= 32) or prog.num_tbs() == 0
         assert i.slot_bytes == prog.max_count() * i.tile_bytes
     i = plan(programs.ring_allreduce(8, instances=8))
@@ -210,12 +210,10 @@ def test_plan_respects_configuration_and_limits():
     assert i.active_wgs == 64 * 4 and i.fifo_bytes == 64 * 4 * 2 * 4096
     i = plan(prog, target_wgs=128)
     assert i.active_wgs <= 128
-    i = plan(prog, xcd_placement=2)
-    assert i.grid == i.active_wgs
     small = plan(prog, cus=8, resident=16)                     # a tiny device: thread blocks must share
     assert small.active_wgs <= 16 and small.max_fibers_per_wg >= 4
     for bad in (dict(fifo_slots=9), dict(tile_bytes=24), dict(tile_bytes=2 << 20), dict(wg_size=100),
-                dict(team_width=257), dict(xcd_placement=3), dict(target_wgs=-1)):
+                dict(team_width=257), dict(target_wgs=-1), dict(min_lane_bytes=24), dict(debug_hold=2)):
         with pytest.raises(B.Gc3Error) as e:
             plan(prog, **bad)
         assert e.value.status == B.GC3_ERR_ARG
