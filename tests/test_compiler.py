@@ -1,0 +1,130 @@
+"""The DSL front end and the compiler (Sections 3-5): tracing rules, lowering, fusion, scheduling."""
+import numpy as np
+import pytest
+
+import oracle
+from oracle import numeric, postcond
+from paper_2201_11840_amd import binding as B
+from paper_2201_11840_amd import dsl_programs as D
+from paper_2201_11840_amd import inputs, programs
+from paper_2201_11840_amd.compiler import CompileError, compile_program
+from paper_2201_11840_amd.dsl import DslError, GC3Program, chunk, parallelize
+
+
+def compiled():
+    out = []
+    for R in (2, 3, 4, 8):
+        out += [D.ring_allreduce(R), D.ring_allreduce(R, fuse=False), D.ring_allreduce(R, use_rrs=True),
+                D.allpairs_allreduce(R), D.direct_alltoall(R)]
+    out += [D.ring_allreduce(8, instances=8), D.ring_allreduce(3, instances=2)]
+    for N, G in ((2, 2), (2, 3), (3, 2), (2, 8)):
+        out += [D.hierarchical_allreduce(N, G), D.hierarchical_allreduce(N, G, intra_parallel=False),
+                D.hierarchical_allreduce(N, G, fuse=False), D.twostep_alltoall(N, G), D.alltonext(N, G)]
+    out += [D.alltonext(3, 8), D.twostep_alltoall(3, 4)]
+    return out
+
+
+@pytest.mark.parametrize("prog", compiled(), ids=lambda p: f"{p.name}_{p.num_ops()}")
+def test_compiled_program_is_valid_and_meets_its_postcondition(prog):
+    text = prog.to_text()
+    h = B.gc3_program_load(text)
+    try:
+        B.gc3_program_validate(h, 2)            # structure, FIFO order, no deadlock with two slots
+    finally:
+        B.gc3_program_free(h)
+    p = oracle.parse_program(text)
+    for order, seed in (("round_robin", 0), ("random", 1), ("random", 2)):
+        bufs, _ = oracle.run_symbolic(p, slots=2, order=order, seed=seed)
+        postcond.check_symbolic(p.collective, p.ranks, p.in_chunks, p.out_chunks, [b["o"] for b in bufs])
+
+
+@pytest.mark.parametrize("R", [2, 3, 4, 8])
+def test_compiler_reproduces_the_fused_ring_schedule(R):
+    # one thread block per rank, 2R-1 instructions: send, rrcs x (R-1), rcs x (R-2), recv (Section 7.1.1)
+    auto, hand = D.ring_allreduce(R), programs.ring_allreduce(R)
+    for r in range(R):
+        assert len(auto.tbs[r]) == 1
+        a, h = auto.tbs[r][0], hand.tbs[r][0]
+        assert (a.send, a.recv) == (h.send, h.recv)
+        assert [(o.opcode, o.srcidx, o.dstidx, o.count) for o in a.ops] == [(o.opcode, o.srcidx, o.dstidx, o.count) for o in h.ops]
+    assert D.ring_allreduce(R, use_rrs=True).algorithmic_chunks() == hand.algorithmic_chunks() - 1 * R * max(R - 2, 0)
+    x8 = D.ring_allreduce(R, instances=4)
+    assert x8.in_chunks == 4 * R and all(len(t) == 4 for t in x8.tbs)        # 4 instances on 4 channels
+    assert sorted(t.chan for t in x8.tbs[0]) == [0, 1, 2, 3]
+
+
+def test_fusion_across_phases_and_aggregation():
+    # hierarchical AllReduce: the last rrc of a phase fuses with the first send of the next one
+    hand = programs.hierarchical_allreduce(2, 8)
+    auto = D.hierarchical_allreduce(2, 8, intra_parallel=False)
+    assert auto.algorithmic_chunks() < hand.algorithmic_chunks()
+    assert auto.max_count() == 2                                     # multi-count references aggregate
+    par = D.hierarchical_allreduce(2, 8)                             # parallelize(2) on the intra phases
+    assert par.in_chunks == 32 and par.max_count() == 2
+    chans = {t.chan for r in par.tbs for t in r}
+    assert len(chans) == 5                                           # ch 0 and 2 twice (instances), ch 1 once
+
+
+@pytest.mark.parametrize("prog", [D.ring_allreduce(4), D.hierarchical_allreduce(2, 3), D.allpairs_allreduce(4)],
+                         ids=lambda p: p.name)
+def test_compiled_allreduce_numeric(prog):
+    p = oracle.parse_program(prog.to_text())
+    ins = inputs.make_inputs(p.ranks, p.in_chunks * 16, "f32", "int8", 3)
+    want = postcond.allreduce_sum_f64(ins, "f32")
+    oracle.run_program(p, ins, None, "f32", slots=2)
+    for a in ins:
+        assert np.array_equal(numeric.to_float64(a, "f32"), want)
+
+
+def test_dsl_rules():
+    # stale reference (Section 3.3): only the latest reference to a location may be used
+    with pytest.raises(DslError, match="stale"):
+        with GC3Program("t", "custom", 2, 2, inplace=True):
+            old = chunk(0, "input", 0)
+            chunk(0, "input", 0).reduce(chunk(1, "input", 0))
+            old.copy(1, "input", 1)
+    # reading an uninitialised chunk
+    with pytest.raises(DslError, match="uninitialised"):
+        with GC3Program("t", "custom", 2, 2, 2):
+            chunk(0, "output", 0).copy(1, "output", 0)
+    # postcondition (Section 3.2)
+    with pytest.raises(DslError, match="postcondition"):
+        with GC3Program("t", "allreduce", 2, 1, inplace=True):
+            chunk(0, "input", 0).reduce(chunk(1, "input", 0))
+    with pytest.raises(DslError):
+        with GC3Program("t", "custom", 2, 2, inplace=True):
+            chunk(0, "input", 0, 2).reduce(chunk(1, "input", 0, 1))       # unequal counts
+    with pytest.raises(DslError):
+        with GC3Program("t", "custom", 2, 2, inplace=True):
+            chunk(0, "input", 2)                                          # outside the buffer
+    with pytest.raises(DslError):
+        chunk(0, "input", 0)                                              # no program being traced
+    # scratch grows with the highest index used (Section 3.2)
+    with GC3Program("t", "custom", 2, 1, 1) as p:
+        chunk(0, "input", 0).copy(1, "scratch", 4)
+    assert p.scratch_chunks(1) == 5 and compile_program(p).scratch_chunks(1) == 5
+
+
+def test_channel_directives():
+    # two transfers from one rank to two different peers, both forwarded: they cannot share a channel's
+    # thread block unless the peers match; the compiler picks the lowest valid channel for the second
+    with GC3Program("t", "custom", 4, 2, 2) as p:
+        chunk(0, "input", 0).copy(1, "output", 0).copy(2, "output", 0)
+        chunk(3, "input", 1).copy(1, "output", 1).copy(2, "output", 1)
+    out = compile_program(p)
+    rank1 = out.tbs[1]
+    assert sorted((t.send, t.recv, t.chan) for t in rank1) == [(2, 0, 0), (2, 3, 1)]
+    # the same with an impossible directive
+    with GC3Program("t", "custom", 4, 2, 2) as p:
+        chunk(0, "input", 0).copy(1, "output", 0, ch=0).copy(2, "output", 0, ch=0)
+        chunk(3, "input", 1).copy(1, "output", 1, ch=0).copy(2, "output", 1, ch=0)
+    with pytest.raises(CompileError):
+        compile_program(p)
+    with GC3Program("t", "custom", 2, 4, 4) as p:
+        with parallelize(3):
+            chunk(0, "input", 0).copy(1, "output", 0)
+        with pytest.raises(DslError):
+            with parallelize(2):
+                with parallelize(2):
+                    pass
+    assert compile_program(p).in_chunks == 12

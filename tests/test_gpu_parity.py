@@ -106,6 +106,22 @@ def test_twostep_alltoall_and_alltonext_grid(N, G):
     run_case(programs.alltonext(N, G), "f16", G * 5000, "normal", 51, small_cfg(team_width=min(wide, 2)), exact_only=True)
 
 
+# ---- programs produced by the DSL compiler (different thread-block structure, cross-phase fusion) -----
+
+def test_compiled_programs():
+    from paper_2201_11840_amd import dsl_programs as D
+    run_case(D.ring_allreduce(8, instances=2), "f32", 16 * 1252, "uniform", 81, small_cfg())
+    run_case(D.ring_allreduce(5, fuse=False), "bf16", 5 * 2000, "normal", 82, small_cfg(fifo_slots=1))
+    run_case(D.ring_allreduce(4, use_rrs=True), "f16", 4 * 2000, "normal", 83, small_cfg())
+    run_case(D.hierarchical_allreduce(2, 8), "bf16", 32 * 1000, "normal", 84, small_cfg())
+    run_case(D.hierarchical_allreduce(3, 2, intra_parallel=False), "f32", 6 * 1000, "uniform", 85, small_cfg(team_width=2))
+    run_case(D.allpairs_allreduce(8), "f32", 8 * 1000, "uniform", 86, small_cfg(team_width=2))
+    run_case(D.twostep_alltoall(2, 3), "f16", 6 * 1000, "normal", 87, small_cfg(), exact_only=True)
+    run_case(D.alltonext(3, 8), "f16", 8 * 2000, "normal", 88, small_cfg(team_width=1), exact_only=True)
+    # default configuration, 16 MiB per rank
+    run_case(D.hierarchical_allreduce(2, 8), "bf16", 8 << 20, "normal", 89)
+
+
 # ---- edge cases ------------------------------------------------------------------------------------
 
 def test_smallest_chunk_and_more_lanes_than_units():
