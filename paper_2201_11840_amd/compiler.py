@@ -211,133 +211,162 @@ def compile_program(prog: GC3Program, fuse: bool = True, use_rrs: bool = False) 
         if n.comm_to is not None or n.comm_from is not None:
             chains.setdefault(find(n.id), []).append(n)
 
-    state: List[Dict] = [{"send": {}, "recv": {}} for _ in range(R)]    # (peer, chan) -> _Tb
+    root_of = {id(c): r for r, c in chains.items()}
+    user_channels = [n.ch for n in alive if n.ch is not None]
+    base_fresh = max(user_channels, default=-1) + 1 + len(chains)      # beyond anything assigned otherwise
 
-    def place(chain: List[Node], chan: Tuple[int, int], commit: bool) -> bool:
-        """Can the chain's instructions live in thread blocks with one send and one receive peer each,
-        one sending and one receiving thread block per connection (Section 5, GC3-IR)?"""
-        trial = state if commit else copy.deepcopy(state)     # a dry run works on a copy
+    def attempt(separate: Dict[int, int]):
+        """Assign channels and thread blocks, then schedule.  Returns (order, None) or (None, a pop that
+        could not be scheduled because its connection would have to deliver out of order)."""
+        for n in alive:
+            n.tb = None
+        state: List[Dict] = [{"send": {}, "recv": {}} for _ in range(R)]    # (peer, chan) -> _Tb
 
-        for n in chain:
-            st = trial[n.rank]
-            ts = st["send"].get((n.send_peer, chan)) if n.send_peer >= 0 else None
-            tr = st["recv"].get((n.recv_peer, chan)) if n.recv_peer >= 0 else None
-            if n.send_peer >= 0 and n.recv_peer >= 0:
-                if ts is None and tr is None:
-                    t = _Tb(n.rank, n.send_peer, n.recv_peer, chan)
-                elif ts is not None and tr is None:
-                    if ts.recv not in (-1, n.recv_peer):
-                        return False
-                    ts.recv, t = n.recv_peer, ts
-                elif tr is not None and ts is None:
-                    if tr.send not in (-1, n.send_peer):
-                        return False
-                    tr.send, t = n.send_peer, tr
-                elif ts is tr:
-                    t = ts
-                elif ts.recv == -1 and tr.send == -1:
-                    # a send-only and a receive-only thread block on this channel become one
-                    ts.recv, tr.alias, t = tr.recv, ts, ts
-                    for d in (st["send"], st["recv"]):
-                        for key, val in d.items():
-                            if val is tr:
-                                d[key] = ts
+        def place(chain: List[Node], chan: Tuple[int, int], commit: bool) -> bool:
+            """Can the chain's instructions live in thread blocks with one send and one receive peer each,
+            one sending and one receiving thread block per connection (Section 5, GC3-IR)?"""
+            trial = state if commit else copy.deepcopy(state)     # a dry run works on a copy
+
+            for n in chain:
+                st = trial[n.rank]
+                ts = st["send"].get((n.send_peer, chan)) if n.send_peer >= 0 else None
+                tr = st["recv"].get((n.recv_peer, chan)) if n.recv_peer >= 0 else None
+                if n.send_peer >= 0 and n.recv_peer >= 0:
+                    if ts is None and tr is None:
+                        t = _Tb(n.rank, n.send_peer, n.recv_peer, chan)
+                    elif ts is not None and tr is None:
+                        if ts.recv not in (-1, n.recv_peer):
+                            return False
+                        ts.recv, t = n.recv_peer, ts
+                    elif tr is not None and ts is None:
+                        if tr.send not in (-1, n.send_peer):
+                            return False
+                        tr.send, t = n.send_peer, tr
+                    elif ts is tr:
+                        t = ts
+                    elif ts.recv == -1 and tr.send == -1:
+                        # a send-only and a receive-only thread block on this channel become one
+                        ts.recv, tr.alias, t = tr.recv, ts, ts
+                        for d in (st["send"], st["recv"]):
+                            for key, val in d.items():
+                                if val is tr:
+                                    d[key] = ts
+                    else:
+                        return False        # a thread block would need two send or two receive peers
+                    st["send"][(n.send_peer, chan)] = t
+                    st["recv"][(n.recv_peer, chan)] = t
+                elif n.send_peer >= 0:
+                    t = ts if ts is not None else _Tb(n.rank, n.send_peer, -1, chan)
+                    st["send"][(n.send_peer, chan)] = t
                 else:
-                    return False        # a thread block would need two send or two receive peers
-                st["send"][(n.send_peer, chan)] = t
-                st["recv"][(n.recv_peer, chan)] = t
-            elif n.send_peer >= 0:
-                t = ts if ts is not None else _Tb(n.rank, n.send_peer, -1, chan)
-                st["send"][(n.send_peer, chan)] = t
+                    t = tr if tr is not None else _Tb(n.rank, -1, n.recv_peer, chan)
+                    st["recv"][(n.recv_peer, chan)] = t
+                if commit:
+                    n.tb = t
+            return True
+
+        for chain in sorted(chains.values(), key=lambda c: min(n.order for n in c)):
+            wanted = {n.ch for n in chain if n.ch is not None}
+            insts = {n.inst for n in chain}
+            if len(wanted) > 1 or len(insts) > 1:
+                raise CompileError("a chain of fused instructions carries conflicting channel directives")
+            inst = insts.pop()
+            if wanted:
+                c = wanted.pop()
+                if not place(chain, (c, inst), commit=False):
+                    raise CompileError(f"channel {c} cannot serve this transfer: a thread block would need two peers; use another ch=")
             else:
-                t = tr if tr is not None else _Tb(n.rank, -1, n.recv_peer, chan)
-                st["recv"][(n.recv_peer, chan)] = t
-            if commit:
-                n.tb = t
-        return True
+                c = 0
+                if root_of[id(chain)] in separate:                   # a channel of its own (see below)
+                    c = base_fresh + separate[root_of[id(chain)]]
+                while not place(chain, (c, inst), commit=False):     # the lowest valid channel
+                    c += 1
+                    if c > 4096:
+                        raise CompileError("no valid channel found")
+            place(chain, (c, inst), commit=True)
 
-    for chain in sorted(chains.values(), key=lambda c: min(n.order for n in c)):
-        wanted = {n.ch for n in chain if n.ch is not None}
-        insts = {n.inst for n in chain}
-        if len(wanted) > 1 or len(insts) > 1:
-            raise CompileError("a chain of fused instructions carries conflicting channel directives")
-        inst = insts.pop()
-        if wanted:
-            c = wanted.pop()
-            if not place(chain, (c, inst), commit=False):
-                raise CompileError(f"channel {c} cannot serve this transfer: a thread block would need two peers; use another ch=")
-        else:
-            c = 0
-            while not place(chain, (c, inst), commit=False):     # the lowest valid channel
-                c += 1
-                if c > 4096:
-                    raise CompileError("no valid channel found")
-        place(chain, (c, inst), commit=True)
+        for n in alive:
+            if n.tb is not None:
+                n.tb = n.tb.resolve()
 
-    for n in alive:
-        if n.tb is not None:
-            n.tb = n.tb.resolve()
+        # ---- global order (Section 5.2): list scheduling by dependency depth, then reverse depth -------------
+        # Instructions are taken one by one in a topological order of the processing and communication
+        # edges, lower depth first, higher reverse depth second.  A connection is a FIFO, so the order in
+        # which its pushes are scheduled is the order in which the matching pops must be scheduled: a pop
+        # becomes eligible only when its push is the oldest unconsumed one on its connection.
+        preds_all = {n.id: set(n.preds) | ({n.comm_from} if n.comm_from is not None else set()) for n in alive}
+        succ_all: Dict[int, List[int]] = {n.id: [] for n in alive}
+        for i, ps in preds_all.items():
+            for p in ps:
+                succ_all[p].append(i)
+        order_ids = [n.id for n in alive]                      # trace order is a topological order
+        depth = {i: 0 for i in order_ids}
+        for i in order_ids:
+            for p in preds_all[i]:
+                depth[i] = max(depth[i], depth[p] + 1)
+        rdep = {i: 0 for i in order_ids}
+        for i in reversed(order_ids):
+            for sx in succ_all[i]:
+                rdep[i] = max(rdep[i], rdep[sx] + 1)
+        indeg = {i: len(ps) for i, ps in preds_all.items()}
+        key = lambda i: (depth[i], -rdep[i], nodes[i].order, i)
+        fifo: Dict[Tuple[int, int, Tuple[int, int]], List[int]] = {}
+        blocked: Dict[Tuple[int, int, Tuple[int, int]], Dict[int, int]] = {}
+        heap: List[Tuple[int, int, int, int]] = []
 
-    # ---- global order (Section 5.2): list scheduling by dependency depth, then reverse depth -------------
-    # Instructions are taken one by one in a topological order of the processing and communication
-    # edges, lower depth first, higher reverse depth second.  A connection is a FIFO, so the order in
-    # which its pushes are scheduled is the order in which the matching pops must be scheduled: a pop
-    # becomes eligible only when its push is the oldest unconsumed one on its connection.
-    preds_all = {n.id: set(n.preds) | ({n.comm_from} if n.comm_from is not None else set()) for n in alive}
-    succ_all: Dict[int, List[int]] = {n.id: [] for n in alive}
-    for i, ps in preds_all.items():
-        for p in ps:
-            succ_all[p].append(i)
-    order_ids = [n.id for n in alive]                      # trace order is a topological order
-    depth = {i: 0 for i in order_ids}
-    for i in order_ids:
-        for p in preds_all[i]:
-            depth[i] = max(depth[i], depth[p] + 1)
-    rdep = {i: 0 for i in order_ids}
-    for i in reversed(order_ids):
-        for sx in succ_all[i]:
-            rdep[i] = max(rdep[i], rdep[sx] + 1)
-    indeg = {i: len(ps) for i, ps in preds_all.items()}
-    key = lambda i: (depth[i], -rdep[i], nodes[i].order, i)
-    fifo: Dict[Tuple[int, int, Tuple[int, int]], List[int]] = {}
-    blocked: Dict[Tuple[int, int, Tuple[int, int]], Dict[int, int]] = {}
-    heap: List[Tuple[int, int, int, int]] = []
+        def conn_in(n: Node):
+            return (n.recv_peer, n.rank, n.tb.chan)
 
-    def conn_in(n: Node):
-        return (n.recv_peer, n.rank, n.tb.chan)
+        def offer(i: int) -> None:
+            n = nodes[i]
+            if n.comm_from is not None:
+                q = fifo.get(conn_in(n), [])
+                if not q or q[0] != n.comm_from:
+                    blocked.setdefault(conn_in(n), {})[n.comm_from] = i
+                    return
+            heapq.heappush(heap, key(i))
 
-    def offer(i: int) -> None:
-        n = nodes[i]
-        if n.comm_from is not None:
-            q = fifo.get(conn_in(n), [])
-            if not q or q[0] != n.comm_from:
-                blocked.setdefault(conn_in(n), {})[n.comm_from] = i
-                return
-        heapq.heappush(heap, key(i))
+        for i in order_ids:
+            if indeg[i] == 0:
+                offer(i)
+        sorted_ids: List[int] = []
+        while heap:
+            i = heapq.heappop(heap)[3]
+            n = nodes[i]
+            sorted_ids.append(i)
+            if n.comm_from is not None:
+                q = fifo[conn_in(n)]
+                q.pop(0)
+                if q and q[0] in blocked.get(conn_in(n), {}):
+                    heapq.heappush(heap, key(blocked[conn_in(n)].pop(q[0])))
+            if n.comm_to is not None:
+                conn = (n.rank, n.send_peer, n.tb.chan)
+                fifo.setdefault(conn, []).append(i)
+            for sx in succ_all[i]:
+                indeg[sx] -= 1
+                if indeg[sx] == 0:
+                    offer(sx)
+        if len(sorted_ids) != len(order_ids):
+            stuck = [i for d in blocked.values() for i in d.values()]
+            return None, min(stuck, key=lambda i: nodes[i].order) if stuck else None
+        return sorted_ids, None
 
-    for i in order_ids:
-        if indeg[i] == 0:
-            offer(i)
-    sorted_ids: List[int] = []
-    while heap:
-        i = heapq.heappop(heap)[3]
-        n = nodes[i]
-        sorted_ids.append(i)
-        if n.comm_from is not None:
-            q = fifo[conn_in(n)]
-            q.pop(0)
-            if q and q[0] in blocked.get(conn_in(n), {}):
-                heapq.heappush(heap, key(blocked[conn_in(n)].pop(q[0])))
-        if n.comm_to is not None:
-            conn = (n.rank, n.send_peer, n.tb.chan)
-            fifo.setdefault(conn, []).append(i)
-        for sx in succ_all[i]:
-            indeg[sx] -= 1
-            if indeg[sx] == 0:
-                offer(sx)
-    if len(sorted_ids) != len(order_ids):
-        raise CompileError("no schedule keeps every connection first-in first-out: two transfers on one connection "
-                           "are needed in the opposite order of their sends; give them different channels")
+
+    # Fusion can tie a receive early in the program to a send late in it; two such transfers sharing a
+    # connection may then be needed in opposite orders at its two ends.  Such a chain is moved to a
+    # channel of its own and the schedule is tried again.
+    separate: Dict[int, int] = {}
+    while True:
+        sorted_ids, stuck = attempt(separate)
+        if sorted_ids is not None:
+            break
+        if stuck is None:
+            raise CompileError("the instruction graph cannot be scheduled")
+        root = find(stuck)
+        if root in separate or any(n.ch is not None for n in chains[root]):
+            raise CompileError("no schedule keeps every connection first-in first-out: two transfers on one "
+                               "connection are needed in opposite orders at its two ends; give them different channels")
+        separate[root] = len(separate)
 
     # ---- thread blocks and emission ----------------------------------------------------------------------
     chan_ids = sorted({n.tb.chan for n in alive if n.tb is not None})

@@ -19,8 +19,8 @@
 //                     stores the bare step; the tile term and the +1 make the value monotone and
 //                     distinguish "step 0 done" from the initial 0)
 // A sender waits for head >= run_base + k + 1 - s before its k-th push (k >= s), a receiver for
-// tail >= run_base + k + 1 before its k-th pop.  Publishing is: workgroup barrier (every wavefront
-// first waits until its device-scope stores have completed), then one thread stores the flags with
+// tail >= run_base + k + 1 before its k-th pop.  Publishing is: every wavefront waits (s_waitcnt) until
+// its device-scope stores have completed, workgroup barrier, then one thread stores the flags with
 // relaxed agent-scope atomics; waiting is relaxed agent-scope loads by the first wavefront, then a
 // workgroup barrier, then device-scope loads of the payload.
 #include <hip/hip_runtime.h>
@@ -392,6 +392,11 @@ __global__ void __launch_bounds__(512) gc3_interpreter(KParams p) {
         if (pushes) ++send_seq;
         if (pops) ++recv_seq;
         if (pushes || pops || hasdep) {
+          // Every wavefront waits until its own stores have completed at device scope (the store counter
+          // retires a device-scope store only then) BEFORE the barrier: a workgroup-scope barrier alone
+          // does not wait for outstanding global stores on this target, and the flag written below
+          // must never overtake the payload.
+          __builtin_amdgcn_s_waitcnt(0);
           __syncthreads();
           if (tid == 0) {
             if (GC3_CONSERVATIVE_FENCES) __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");

@@ -128,3 +128,58 @@ def test_channel_directives():
                 with parallelize(2):
                     pass
     assert compile_program(p).in_chunks == 12
+
+
+def _random_program(seed, ranks, chunks, n_ops, use_channels):
+    """A random well-formed DSL program: random copies and reductions between random locations."""
+    import random
+    rng = random.Random(seed)
+    with GC3Program(f"rand{seed}", "custom", ranks, chunks, chunks, inplace=False) as p:
+        made = 0
+        while made < n_ops:
+            cnt = rng.choice([1, 1, 1, 2])
+            sr, dr = rng.randrange(ranks), rng.randrange(ranks)
+            sbuf = rng.choice(["input", "output", "scratch"])
+            dbuf = rng.choice(["output", "scratch", "output"])
+            si, di = rng.randrange(chunks - cnt + 1), rng.randrange(chunks - cnt + 1)
+            ch = rng.randrange(3) if use_channels else None
+            try:
+                src = chunk(sr, sbuf, si, cnt)
+                if rng.random() < 0.4:
+                    chunk(dr, dbuf, di, cnt).reduce(src, ch=ch)
+                else:
+                    src.copy(dr, dbuf, di, ch=ch)
+                made += 1
+            except DslError:
+                continue                    # uninitialised source, overlap, ... : try another operation
+    return p
+
+
+@pytest.mark.parametrize("seed", range(40))
+def test_random_programs_keep_the_traced_semantics(seed):
+    # the DSL's own symbolic state after tracing is the specification; the compiled IR, executed by the
+    # oracle in random orders, must leave exactly that content in every buffer of every rank
+    ranks, chunks = 2 + seed % 4, 3 + seed % 3
+    p = _random_program(seed, ranks, chunks, 12 + seed % 17, use_channels=seed % 3 == 0)
+    for opts in (dict(), dict(fuse=False), dict(use_rrs=True)):
+        try:
+            ir = compile_program(p, **opts)
+        except CompileError:
+            if opts or seed % 3 == 0:
+                continue                    # explicit channels can be unsatisfiable; nothing to check then
+            raise
+        text = ir.to_text()
+        h = B.gc3_program_load(text)
+        try:
+            B.gc3_program_validate(h, 8)
+        finally:
+            B.gc3_program_free(h)
+        op = oracle.parse_program(text)
+        for order_seed in range(3):
+            bufs, _ = oracle.run_symbolic(op, slots=8, order="random", seed=order_seed)
+            for r in range(ranks):
+                for buf in ("i", "o"):
+                    assert bufs[r][buf] == p.content[r][buf], (seed, opts, r, buf)
+                for j, want in enumerate(p.content[r]["s"]):
+                    if want is not None and "use_rrs" not in opts:
+                        assert bufs[r]["s"][j] == want, (seed, opts, r, j)

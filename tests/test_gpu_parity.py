@@ -25,8 +25,13 @@ def compare(got, want, dtype, exact_only=False):
     if dtype == "f32" or exact_only:
         assert got.tobytes() == want.tobytes(), f"{np.count_nonzero(got != want)} of {got.size} elements differ"
         return
-    tol = 1e-3 * np.abs(w64) + 1e-5 * (np.abs(w64).max() if w64.size else 0.0)
-    assert np.all(np.abs(g64 - w64) <= tol), f"max err {np.abs(g64 - w64).max()}"
+    # locations the program never writes keep the NaN sentinel: they must match bitwise; the tolerance
+    # applies to the finite values
+    fin = np.isfinite(w64)
+    assert np.array_equal(got[~fin].view(np.uint16), want[~fin].view(np.uint16))
+    scale = np.abs(w64[fin]).max() if fin.any() else 0.0
+    tol = 1e-3 * np.abs(w64[fin]) + 1e-5 * scale
+    assert np.all(np.abs(g64[fin] - w64[fin]) <= tol), f"max err {np.abs(g64[fin] - w64[fin]).max()}"
     assert got.tobytes() == want.tobytes(), f"within tolerance but {np.count_nonzero(got != want)} elements not bitwise equal"
 
 
@@ -120,6 +125,20 @@ def test_compiled_programs():
     run_case(D.alltonext(3, 8), "f16", 8 * 2000, "normal", 88, small_cfg(team_width=1), exact_only=True)
     # default configuration, 16 MiB per rank
     run_case(D.hierarchical_allreduce(2, 8), "bf16", 8 << 20, "normal", 89)
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_random_compiled_programs(seed):
+    # random copy / reduce programs: many peers per rank, scratch use, dependencies in all directions
+    from tests.test_compiler import _random_program
+    from paper_2201_11840_amd.compiler import compile_program
+    p = _random_program(100 + seed, 2 + seed % 4, 3 + seed % 3, 14 + seed % 11, use_channels=False)
+    ir = compile_program(p, fuse=seed % 4 != 3)
+    dtype = ("f32", "f16", "bf16")[seed % 3]
+    # copies of uninitialised scratch never happen (the DSL rejects them), so every value is defined;
+    # outputs start from the sentinel pattern on both sides
+    run_case(ir, dtype, ir.in_chunks * (1000 if dtype == "f32" else 2000), "normal", 500 + seed,
+             small_cfg(fifo_slots=8, team_width=1 + seed % 3), repeats=3)
 
 
 # ---- edge cases ------------------------------------------------------------------------------------
