@@ -1,0 +1,93 @@
+"""Repeated full-size runs checked on the device: a rare ordering bug (a flag overtaking its payload, a
+stale cache line) would show up as a run whose output differs from the verified first one."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2201_11840_amd import harness as H
+from paper_2201_11840_amd import inputs, programs, workloads
+
+pytestmark = pytest.mark.gpu
+
+
+def _verified_first_run(w, coll, ins):
+    """Upload, run once, check against the oracle on sampled element positions (every instruction is
+    element-wise and chunk-uniform, so the oracle on the gathered positions is exact for them)."""
+    p = oracle.parse_program(w.build().to_text())
+    ce = w.elems_per_rank // p.in_chunks
+    coll.fill_outputs_with_sentinel()
+    coll.upload(ins)
+    coll.run()
+    coll.status()
+    got = coll.download("out")
+    pos = np.unique(np.random.Generator(np.random.PCG64(1)).integers(0, ce, 4096))
+    gather = lambda a, n: a.reshape(n, ce)[:, pos].reshape(-1).copy()
+    small_in = [gather(a, p.in_chunks) for a in ins]
+    st = inputs.STORAGE[w.dtype]
+    small_out = None if p.inplace else [np.full(pos.size * p.out_chunks * inputs.ITEMSIZE[w.dtype] // 2, inputs.SENTINEL16,
+                                                np.uint16).view(st).copy() for _ in range(p.ranks)]
+    oracle.run_program(p, small_in, small_out, w.dtype, slots=coll.info.fifo_slots)
+    want = small_in if p.inplace else small_out
+    for r in range(p.ranks):
+        assert gather(got[r], p.out_chunks).tobytes() == want[r].tobytes()
+
+
+@pytest.mark.parametrize("w", [workloads.ring_ar_r8x8(16), workloads.hier_ar_2x8(16), workloads.alltonext_3x8(8),
+                               workloads.Workload("allpairs_r8_f32_8MiB", lambda: programs.allpairs_allreduce(8),
+                                                  "f32", 8 << 20, "uniform", 7)],
+                         ids=lambda w: w.name)
+def test_many_runs_give_the_same_verified_result(w):
+    prog = w.build()
+    ins = inputs.make_inputs(prog.ranks, w.elems_per_rank, w.dtype, w.dist, w.seed)
+    coll = H.Collective(prog.to_text(), w.dtype, w.elems_per_rank)
+    try:
+        _verified_first_run(w, coll, ins)
+        good = [t.clone() for t in coll.outputs]
+        pristine = None
+        if coll.inplace:
+            coll.upload(ins)
+            pristine = [t.clone() for t in coll.inputs]
+        for it in range(150):
+            if pristine is not None:
+                for d, s in zip(coll.inputs, pristine):
+                    d.copy_(s)
+            coll.run()
+            if it % 10 == 9:
+                coll.status()
+                for r in range(coll.ranks):
+                    assert torch.equal(coll.outputs[r], good[r]), f"run {it}, rank {r}"
+    finally:
+        coll.close()
+
+
+def test_two_communicators_and_a_side_stream():
+    # two communicators alive at once, launched alternately on a non-default stream
+    a = workloads.ring_ar_r8x8(1)
+    b = workloads.direct_a2a_r8()
+    ca = H.Collective(a.build().to_text(), a.dtype, a.elems_per_rank)
+    cb = H.Collective(b.build().to_text(), b.dtype, b.elems_per_rank)
+    ia = inputs.make_inputs(8, a.elems_per_rank, a.dtype, a.dist, a.seed)
+    ib = inputs.make_inputs(8, b.elems_per_rank, b.dtype, b.dist, b.seed)
+    wa = [x.copy() for x in ia]
+    oracle.run_program(oracle.parse_program(a.build().to_text()), wa, None, a.dtype, slots=2)
+    wb = [np.concatenate([ib[j].reshape(8, -1)[i] for j in range(8)]) for i in range(8)]
+    side = torch.cuda.Stream()
+    try:
+        for it in range(5):
+            ca.upload(ia)
+            cb.fill_outputs_with_sentinel()
+            cb.upload(ib)
+            with torch.cuda.stream(side):
+                ca.run()
+                cb.run()
+            side.synchronize()
+            ca.status()
+            cb.status()
+            for g, w_ in zip(ca.download(), wa):
+                assert g.tobytes() == w_.tobytes()
+            for g, w_ in zip(cb.download(), wb):
+                assert g.tobytes() == w_.tobytes()
+    finally:
+        ca.close()
+        cb.close()
