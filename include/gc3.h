@@ -98,6 +98,13 @@ typedef struct gc3_comm_config {
                               GC3_ERR_TIMEOUT and all workgroups leaving through the error path */
   int32_t min_lane_bytes;  /* a run splits a chunk over at most chunk bytes / min_lane_bytes lanes (at least
                               one): small chunks are not worth spreading; multiple of 16, default 8192 */
+  int32_t protocol;        /* Section 6.1 "Protocols".  0 = what the program's `protocol` line says:
+                              `simple` (payload, then a separate flag), `ll` (every 8 bytes carry 4 bytes of
+                              data and a 4-byte flag: lowest latency, half the bandwidth) or `auto` (LL when
+                              a lane's share of a chunk is at most ll_max_lane_bytes); 1 = force simple,
+                              2 = force LL, 3 = force auto */
+  int32_t ll_max_lane_bytes; /* `auto` switches to LL up to this many bytes per lane and chunk; also the LL
+                              tile size; multiple of 16, at most 65536; default 8192 */
 } gc3_comm_config;
 
 typedef struct gc3_comm_info {
@@ -113,7 +120,8 @@ typedef struct gc3_comm_info {
   int32_t compute_units;
   int32_t max_fibers_per_wg; /* most thread-block lanes multiplexed by one workgroup (1 = none shared) */
   int32_t wgs_per_lane;      /* a run on small chunks launches only active lanes x wgs_per_lane workgroups */
-  int32_t reserved0;
+  int32_t protocol;          /* 1 simple, 2 LL, 3 auto (after applying the configuration's override) */
+  uint64_t ll_fifo_bytes;    /* device memory held by the LL slots */
 } gc3_comm_info;
 
 /* Message for the most recent error on this thread.  host; owned by the library; never null. */
@@ -123,7 +131,7 @@ const char* gc3_last_error(void);
 
 /* Parse GC3-IR text (`text`: host, `len` bytes, need not be NUL-terminated).  On success *out is
  * a new program.  The text format is line oriented:
- *   gc3ir 1 / name T / collective T / inplace 0|1 / protocol T / ranks R / chunks IN OUT
+ *   gc3ir 1 / name T / collective T / inplace 0|1 / protocol simple|ll|ll128|auto / ranks R / chunks IN OUT
  *   rank r scratch N tbs K            (ranks in order)
  *   tb id send P recv Q chan C ops n  (ids in order; -1 = no peer)
  *   op OPCODE SRCBUF SRCIDX DSTBUF DSTIDX COUNT HASDEP NDEPS {TB STEP}...

@@ -27,6 +27,7 @@ GC3_ERR_POISONED = -10
 
 GC3_F32, GC3_F16, GC3_BF16 = 0, 1, 2
 GC3_SUM = 0
+PROTO_PROGRAM, PROTO_SIMPLE, PROTO_LL, PROTO_AUTO = 0, 1, 2, 3
 DTYPE_CODE = {"f32": GC3_F32, "f16": GC3_F16, "bf16": GC3_BF16}
 
 EXPORTS = ("gc3_last_error", "gc3_program_load", "gc3_program_free", "gc3_program_validate",
@@ -45,15 +46,16 @@ class ProgramInfo(C.Structure):
 class CommConfig(C.Structure):
     _fields_ = [("fifo_slots", C.c_int32), ("tile_bytes", C.c_int32), ("team_width", C.c_int32),
                 ("wg_size", C.c_int32), ("reserved0", C.c_int32), ("target_wgs", C.c_int32),
-                ("spin_limit_us", C.c_uint64), ("debug_hold", C.c_int32), ("min_lane_bytes", C.c_int32)]
+                ("spin_limit_us", C.c_uint64), ("debug_hold", C.c_int32), ("min_lane_bytes", C.c_int32),
+                ("protocol", C.c_int32), ("ll_max_lane_bytes", C.c_int32)]
 
 
 def make_config(fifo_slots: int = 0, tile_bytes: int = 0, team_width: int = 0, wg_size: int = 0,
                 spin_limit_us: int = 0, target_wgs: int = 0, debug_hold: int = 0,
-                min_lane_bytes: int = 0) -> CommConfig:
+                min_lane_bytes: int = 0, protocol: int = 0, ll_max_lane_bytes: int = 0) -> CommConfig:
     """A gc3_comm_config; zero fields select the library's defaults."""
     return CommConfig(fifo_slots, tile_bytes, team_width, wg_size, 0, target_wgs, spin_limit_us,
-                      debug_hold, min_lane_bytes)
+                      debug_hold, min_lane_bytes, protocol, ll_max_lane_bytes)
 
 
 class CommInfo(C.Structure):
@@ -61,7 +63,7 @@ class CommInfo(C.Structure):
                 ("active_wgs", C.c_int32), ("max_resident_wgs", C.c_int32), ("fifo_slots", C.c_int32),
                 ("tile_bytes", C.c_int32), ("slot_bytes", C.c_int32), ("fifo_bytes", C.c_uint64),
                 ("compute_units", C.c_int32), ("max_fibers_per_wg", C.c_int32),
-                ("wgs_per_lane", C.c_int32), ("reserved0", C.c_int32)]
+                ("wgs_per_lane", C.c_int32), ("protocol", C.c_int32), ("ll_fifo_bytes", C.c_uint64)]
 
 
 class Gc3Error(RuntimeError):

@@ -17,7 +17,7 @@
 #include "program.h"
 
 namespace gc3 {
-int launch_interpreter(int dtype, bool coherent_user, unsigned grid, unsigned block, void* stream, const KParams& p);
+int launch_interpreter(int dtype, bool coherent_user, bool ll, unsigned grid, unsigned block, void* stream, const KParams& p);
 int interpreter_occupancy(unsigned block, int* out);
 }  // namespace gc3
 
@@ -44,6 +44,10 @@ struct gc3_comm {
   bool has_deps = false;    // some instruction waits on another thread block's semaphore
   bool debug_hold = false;  // failure-path test facility
   uint64_t min_lane_bytes = 8192;
+  uint64_t ll_max_lane_bytes = 8192;
+  uint32_t ll_slot_bytes = 0;
+  int max_pushes = 0;
+  uint64_t ll_next = 0;     // LL message numbers handed out so far (64-bit; flags are its low 32 bits)
   uint64_t algorithmic_chunks = 0;
   std::vector<int32_t> scratch_chunks;
   gc3_comm_info info{};
@@ -57,6 +61,7 @@ struct gc3_comm {
   uint32_t* d_wg_fibers = nullptr;
   void** d_bufs = nullptr;
   unsigned char* d_fifo = nullptr;
+  unsigned char* d_ll_fifo = nullptr;
   uint64_t* d_flags = nullptr;
   uint64_t* d_sems = nullptr;
   uint32_t* d_error = nullptr;
@@ -73,7 +78,7 @@ struct gc3_comm {
   ~gc3_comm() {
     // best effort; errors on teardown are ignored
     for (void* q : {(void*)d_tbs, (void*)d_instrs, (void*)d_deps, (void*)d_wg_begin, (void*)d_wg_fibers, (void*)d_bufs,
-                    (void*)d_fifo, (void*)d_flags, (void*)d_sems, (void*)d_error})
+                    (void*)d_fifo, (void*)d_ll_fifo, (void*)d_flags, (void*)d_sems, (void*)d_error})
       if (q) (void)hipFree(q);
   }
 };
@@ -126,6 +131,11 @@ int gc3_comm_create(const gc3_program* prog, const gc3_comm_config* cfg_in, gc3_
   if ((rc = upload(&c->d_wg_fibers, plan.wg_fibers)) != GC3_OK) return rc;
   HIP_TRY(hipMalloc((void**)&c->d_bufs, (size_t)R * 3 * sizeof(void*)));
   HIP_TRY(hipMalloc((void**)&c->d_fifo, plan.info.fifo_bytes));
+  if (plan.info.ll_fifo_bytes) {
+    // LL slots must never hold anything but (data, flag) pairs: start from zero, flags start at 1
+    HIP_TRY(hipMalloc((void**)&c->d_ll_fifo, plan.info.ll_fifo_bytes));
+    HIP_TRY(hipMemset(c->d_ll_fifo, 0, plan.info.ll_fifo_bytes));
+  }
   HIP_TRY(hipMalloc((void**)&c->d_flags, c->flags_bytes));
   HIP_TRY(hipMalloc((void**)&c->d_sems, c->sems_bytes));
   HIP_TRY(hipMalloc((void**)&c->d_error, 256));
@@ -142,6 +152,9 @@ int gc3_comm_create(const gc3_program* prog, const gc3_comm_config* cfg_in, gc3_
   c->has_deps = !plan.deps.empty();
   c->debug_hold = cfg.debug_hold != 0;
   c->min_lane_bytes = (uint64_t)cfg.min_lane_bytes;
+  c->ll_max_lane_bytes = (uint64_t)cfg.ll_max_lane_bytes;
+  c->ll_slot_bytes = (uint32_t)(2ull * plan.max_count * (uint64_t)cfg.ll_max_lane_bytes);
+  c->max_pushes = plan.max_pushes;
   for (int r = 0; r < R; ++r) c->scratch_chunks.push_back(prog->rank[r].scratch_chunks);
   c->bufs.assign((size_t)R * 3, nullptr);
   c->scratch_bytes.assign(R, 0);
@@ -247,9 +260,34 @@ int gc3_comm_run(gc3_comm* comm, size_t elems_per_rank, gc3_dtype dtype, gc3_red
   p.slots = (uint32_t)comm->info.fifo_slots;
   p.tile_bytes = (uint32_t)comm->info.tile_bytes;
   p.slot_bytes = (uint32_t)comm->info.slot_bytes;
+  // Protocol of this run (Section 6.1): LL when forced, or in auto mode when the largest share a lane
+  // has of a chunk is small.  Shares are computed exactly as the kernel does.
+  uint64_t lane_share = 0;
+  {
+    const uint64_t U = cb >> 4, Wa = p.W_active;
+    auto begin = [&](uint64_t w) -> uint64_t {
+      if (w >= Wa) return U << 4;
+      if (U >= 16 * Wa) return (((U >> 4) * w) / Wa) << 8;
+      return ((U * w) / Wa) << 4;
+    };
+    for (uint64_t w = 0; w < Wa; ++w) lane_share = std::max(lane_share, begin(w + 1) - begin(w));
+  }
+  const bool ll = comm->info.protocol == 2 || (comm->info.protocol == 3 && lane_share <= comm->ll_max_lane_bytes);
+  p.ll_fifo = comm->d_ll_fifo;
+  p.ll_slot_bytes = comm->ll_slot_bytes;
+  if (ll) {
+    p.tile_bytes = (uint32_t)comm->ll_max_lane_bytes;
+    // message numbers of this run: [ll_next + 1, ll_next + messages]; their low 32 bits are the flags and
+    // must never be 0 (the value untouched slot memory holds), so a range never crosses a multiple of 2^32
+    const uint64_t tiles = (lane_share + p.tile_bytes - 1) / p.tile_bytes;
+    const uint64_t messages = (uint64_t)comm->max_pushes * tiles + 1;
+    if (((comm->ll_next + messages) >> 32) != (comm->ll_next >> 32)) comm->ll_next = ((comm->ll_next >> 32) + 1) << 32;
+    p.ll_base = (uint32_t)comm->ll_next;
+    comm->ll_next += messages;
+  }
   // lane-major grid: the workgroups of the active lanes are a prefix
   const unsigned grid = p.W_active * (unsigned)comm->info.wgs_per_lane;
-  int e = launch_interpreter((int)dtype, comm->has_deps, grid, (unsigned)comm->info.wg_size, hip_stream, p);
+  int e = launch_interpreter((int)dtype, comm->has_deps, ll, grid, (unsigned)comm->info.wg_size, hip_stream, p);
   if (e != 0) return hip_fail((hipError_t)e, "interpreter launch");
   return GC3_OK;
 }

@@ -40,6 +40,7 @@ struct KParams {
   const uint32_t* wg_fibers;  // fiber = global thread-block index * W + lane
   void* const* bufs;       // [rank*3 + buffer] user buffers
   unsigned char* fifo;     // [(conn*W + lane) * slots + slot] * slot_bytes
+  unsigned char* ll_fifo;  // the same for the LL protocol, slots of ll_slot_bytes (data + flag pairs only)
   uint64_t* flags;         // [((conn*W + lane)*2 + {0 tail, 1 head}) * kFlagStrideWords]
   uint64_t* sems;          // [(tb*W + lane) * kFlagStrideWords]
   uint32_t* error;         // 0 = fine, else a gc3_status (negated) set by the first failing workgroup
@@ -48,8 +49,9 @@ struct KParams {
   uint64_t chunk_bytes;
   uint64_t spin_limit_ticks;  // of the 100 MHz wall clock
   uint32_t W, slots, tile_bytes, slot_bytes;
+  uint32_t ll_slot_bytes;  // 2 * max_count * LL tile bytes
+  uint32_t ll_base;        // LL flag of message k of this run = ll_base + k + 1 (never 0 within a run)
   uint32_t W_active;       // lanes that own bytes in this run (<= W); the others own nothing and finish at once
-  uint32_t pad0;
 };
 
 }  // namespace gc3

@@ -195,6 +195,73 @@ __device__ __forceinline__ void move_tile_staged(rsrc_t in0, rsrc_t in1, rsrc_t 
   }
 }
 
+// ---- LL protocol (Section 6.1, "Protocols": lowest latency, half the bandwidth) -------------------------
+// A message is not announced by a separate flag: every 8 bytes in the FIFO slot are 4 bytes of data plus
+// a 4-byte flag (an 8-byte store is indivisible), so a 16-byte element occupies 32 bytes
+// {d0 f d1 f | d2 f d3 f}.  The receiver polls the data itself until all four flags carry the
+// message's number; the sender needs neither a completion wait nor a barrier.  LL slots live in a
+// region of their own that only ever holds such pairs, so a stale word can never pass for a flag.
+//
+// out[i] = (POP ? unpack(in_ll[i]) : src[i]) (+ src[i] if POP && ADD); optionally stored to dst and/or
+// packed into out_ll with flag `fout`.  Returns false when the wait for data exceeded the spin limit.
+template <bool POP, bool ADD, bool OUT0, bool PUSH, int DT, int P_SRC, int P_DST>
+__device__ __forceinline__ bool move_tile_ll(rsrc_t in_ll, rsrc_t src, rsrc_t dst, rsrc_t out_ll, uint32_t nvec,
+                                             uint32_t tid, uint32_t nthreads, uint32_t fin, uint32_t fout,
+                                             const KParams& p) {
+  constexpr int UN = 2;
+  bool ok = true;
+  const uint32_t step = nthreads * UN;
+  for (uint32_t base = tid; base < nvec && ok; base += step) {
+    u32x4 v[UN], b[UN];
+    if (ADD || !POP) {
+#pragma unroll
+      for (int u = 0; u < UN; ++u) b[u] = __builtin_amdgcn_raw_buffer_load_b128(src, (base + u * nthreads) << 4, 0, P_SRC);
+    }
+    if (POP) {
+      const uint64_t start = wall_clock64();
+      uint32_t spins = 0;
+      for (;;) {
+        bool all = true;
+#pragma unroll
+        for (int u = 0; u < UN; ++u) {
+          const uint32_t i = base + u * nthreads;
+          const u32x4 lo = __builtin_amdgcn_raw_buffer_load_b128(in_ll, i << 5, 0, kPolSc1);
+          const u32x4 hi = __builtin_amdgcn_raw_buffer_load_b128(in_ll, (i << 5) + 16, 0, kPolSc1);
+          if (i < nvec && (lo.y != fin || lo.w != fin || hi.y != fin || hi.w != fin)) all = false;
+          v[u] = u32x4{lo.x, lo.z, hi.x, hi.z};
+        }
+        if (all) break;
+        if ((++spins & 1023u) == 0) {
+          if (__hip_atomic_load(p.error, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0 ||
+              wall_clock64() - start > p.spin_limit_ticks) {
+            atomicCAS(p.error, 0u, (uint32_t)(-GC3_ERR_TIMEOUT));
+            ok = false;
+            break;
+          }
+        }
+      }
+      if (ADD) {
+#pragma unroll
+        for (int u = 0; u < UN; ++u) v[u] = add_vec<DT>(v[u], b[u]);
+      }
+    } else {
+#pragma unroll
+      for (int u = 0; u < UN; ++u) v[u] = b[u];
+    }
+    if (!ok) break;
+#pragma unroll
+    for (int u = 0; u < UN; ++u) {
+      const uint32_t i = base + u * nthreads;
+      if (OUT0) __builtin_amdgcn_raw_buffer_store_b128(v[u], dst, i << 4, 0, P_DST);
+      if (PUSH) {
+        __builtin_amdgcn_raw_buffer_store_b128(u32x4{v[u].x, fout, v[u].y, fout}, out_ll, i << 5, 0, kPolSc1);
+        __builtin_amdgcn_raw_buffer_store_b128(u32x4{v[u].z, fout, v[u].w, fout}, out_ll, (i << 5) + 16, 0, kPolSc1);
+      }
+    }
+  }
+  return ok;
+}
+
 __device__ __forceinline__ uint64_t load_flag(const uint64_t* p) {
   return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
@@ -222,7 +289,7 @@ __device__ __forceinline__ uint32_t uni(uint32_t v) { return __builtin_amdgcn_re
 // unfinished a wait is a single poll (a fiber that is not ready yields to the next one, so thread
 // blocks sharing a workgroup can never block each other), and the last unfinished fiber waits by
 // spinning.  One fiber per workgroup is the paper's one-thread-block-per-block execution.
-template <int DT, bool COH>
+template <int DT, bool COH, bool LL>
 __global__ void __launch_bounds__(512) gc3_interpreter(KParams p) {
   __shared__ uint32_t f_id[kMaxFibersPerWg], f_t[kMaxFibersPerWg], f_s[kMaxFibersPerWg];
   __shared__ uint32_t f_send[kMaxFibersPerWg], f_recv[kMaxFibersPerWg];
@@ -290,8 +357,10 @@ __global__ void __launch_bounds__(512) gc3_interpreter(KParams p) {
       uint64_t* const head_send = tb.send_conn >= 0 ? p.flags + ((uint64_t)(tb.send_conn * W + lane) * 2 + 1) * kFlagStrideWords : nullptr;
       uint64_t* const tail_recv = tb.recv_conn >= 0 ? p.flags + ((uint64_t)(tb.recv_conn * W + lane) * 2 + 0) * kFlagStrideWords : nullptr;
       uint64_t* const head_recv = tb.recv_conn >= 0 ? p.flags + ((uint64_t)(tb.recv_conn * W + lane) * 2 + 1) * kFlagStrideWords : nullptr;
-      unsigned char* const fifo_send = tb.send_conn >= 0 ? p.fifo + (uint64_t)(tb.send_conn * W + lane) * p.slots * p.slot_bytes : nullptr;
-      unsigned char* const fifo_recv = tb.recv_conn >= 0 ? p.fifo + (uint64_t)(tb.recv_conn * W + lane) * p.slots * p.slot_bytes : nullptr;
+      unsigned char* const fifo_base = LL ? p.ll_fifo : p.fifo;            // LL slots have a region of their own
+      const uint32_t slot_bytes = LL ? p.ll_slot_bytes : p.slot_bytes;
+      unsigned char* const fifo_send = tb.send_conn >= 0 ? fifo_base + (uint64_t)(tb.send_conn * W + lane) * p.slots * slot_bytes : nullptr;
+      unsigned char* const fifo_recv = tb.recv_conn >= 0 ? fifo_base + (uint64_t)(tb.recv_conn * W + lane) * p.slots * slot_bytes : nullptr;
       uint64_t* const my_sem = p.sems + (uint64_t)(tbi * W + lane) * kFlagStrideWords;
 
       bool progressed = false;
@@ -308,8 +377,11 @@ __global__ void __launch_bounds__(512) gc3_interpreter(KParams p) {
         const bool wait_slot = pushes && send_seq >= p.slots;
 
         // ---- wait for dependencies, for a message, for a free slot -----------------------------
-        if (pops || wait_slot || ndeps) {
-          const bool block = live == 1;
+        // LL: the message's number doubles as the flag carried by every 8 bytes of its payload
+        const uint32_t ll_fin = p.ll_base + recv_seq + 1, ll_fout = p.ll_base + send_seq + 1;
+        const bool block = live == 1;
+        // (in LL mode a blocking receive needs no announcement: every thread polls its own data)
+        if ((pops && !(LL && block)) || wait_slot || ndeps) {
           if (tid < 64) {
             int res = 1;                                   // 1 ready, 0 not ready, -1 run abandoned
             const uint32_t total = 2 + ndeps;
@@ -318,7 +390,7 @@ __global__ void __launch_bounds__(512) gc3_interpreter(KParams p) {
               const uint64_t* ptr = nullptr;
               uint64_t want = 0;
               if (it == 0) {
-                if (pops) { ptr = tail_recv; want = p.run_base + recv_seq + 1; }
+                if (pops && !LL) { ptr = tail_recv; want = p.run_base + recv_seq + 1; }
               } else if (it == 1) {
                 if (wait_slot) { ptr = head_send; want = p.run_base + send_seq + 1 - p.slots; }
               } else if (it < total) {
@@ -344,6 +416,11 @@ __global__ void __launch_bounds__(512) gc3_interpreter(KParams p) {
                 }
               }
             }
+            if (LL && pops && !block && res == 1) {
+              // non-blocking readiness probe: has the first element of the message arrived?
+              const uint32_t* first = (const uint32_t*)(fifo_recv + (uint64_t)(recv_seq % p.slots) * slot_bytes);
+              if (__hip_atomic_load(first + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != ll_fin) res = 0;
+            }
             if (GC3_CONSERVATIVE_FENCES) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
             if (tid == 0) s_res[phase & 1] = res;
           }
@@ -358,13 +435,28 @@ __global__ void __launch_bounds__(512) gc3_interpreter(KParams p) {
         const uint64_t coff = off0 + toff;   // byte offset inside each chunk
         unsigned char* const srcb = ins.srcbuf < 3 ? (unsigned char*)p.bufs[tb.rank * 3 + ins.srcbuf] + (uint64_t)ins.srcidx * p.chunk_bytes + coff : nullptr;
         unsigned char* const dstb = ins.dstbuf < 3 ? (unsigned char*)p.bufs[tb.rank * 3 + ins.dstbuf] + (uint64_t)ins.dstidx * p.chunk_bytes + coff : nullptr;
-        unsigned char* const rslot = pops ? fifo_recv + (uint64_t)(recv_seq % p.slots) * p.slot_bytes : nullptr;
-        unsigned char* const sslot = pushes ? fifo_send + (uint64_t)(send_seq % p.slots) * p.slot_bytes : nullptr;
+        unsigned char* const rslot = pops ? fifo_recv + (uint64_t)(recv_seq % p.slots) * slot_bytes : nullptr;
+        unsigned char* const sslot = pushes ? fifo_send + (uint64_t)(send_seq % p.slots) * slot_bytes : nullptr;
+        bool data_ok = true;
         constexpr int UL = COH ? GC3_POL_USER_LD_COH : GC3_POL_USER_LD, US = COH ? GC3_POL_USER_ST_COH : GC3_POL_USER_ST;
         constexpr int SL = GC3_POL_SLOT_LD, SS = GC3_POL_SLOT_ST;
         for (uint32_t j = 0; j < ins.count; ++j) {
           const rsrc_t src = make_rsrc(srcb + (uint64_t)j * p.chunk_bytes, srcb ? len : 0);
           const rsrc_t dst = make_rsrc(dstb + (uint64_t)j * p.chunk_bytes, dstb ? len : 0);
+          if (LL && (pops || pushes)) {
+            const rsrc_t rl = make_rsrc(rslot + (uint64_t)j * len * 2, rslot ? len * 2 : 0);
+            const rsrc_t sl = make_rsrc(sslot + (uint64_t)j * len * 2, sslot ? len * 2 : 0);
+            switch (op) {
+              case GC3_OP_SEND: move_tile_ll<false, false, false, true, DT, UL, US>(rl, src, dst, sl, nvec, tid, nthreads, ll_fin, ll_fout, p); break;
+              case GC3_OP_RECV: data_ok &= move_tile_ll<true, false, true, false, DT, UL, US>(rl, src, dst, sl, nvec, tid, nthreads, ll_fin, ll_fout, p); break;
+              case GC3_OP_RRC:  data_ok &= move_tile_ll<true, true, true, false, DT, UL, US>(rl, src, dst, sl, nvec, tid, nthreads, ll_fin, ll_fout, p); break;
+              case GC3_OP_RCS:  data_ok &= move_tile_ll<true, false, true, true, DT, UL, US>(rl, src, dst, sl, nvec, tid, nthreads, ll_fin, ll_fout, p); break;
+              case GC3_OP_RRCS: data_ok &= move_tile_ll<true, true, true, true, DT, UL, US>(rl, src, dst, sl, nvec, tid, nthreads, ll_fin, ll_fout, p); break;
+              case GC3_OP_RRS:  data_ok &= move_tile_ll<true, true, false, true, DT, UL, US>(rl, src, dst, sl, nvec, tid, nthreads, ll_fin, ll_fout, p); break;
+              default: break;
+            }
+            continue;
+          }
           const rsrc_t rs = make_rsrc(rslot + (uint64_t)j * len, rslot ? len : 0);
           const rsrc_t ss = make_rsrc(sslot + (uint64_t)j * len, sslot ? len : 0);
           switch (op) {
@@ -391,16 +483,23 @@ __global__ void __launch_bounds__(512) gc3_interpreter(KParams p) {
         // ---- publish: slot filled, slot freed, semaphore ----------------------------------------
         if (pushes) ++send_seq;
         if (pops) ++recv_seq;
-        if (pushes || pops || hasdep) {
+        // Simple protocol: a push publishes tail, a pop publishes head.  LL: payload carries its own flag,
+        // so only head (slot free again) and semaphores are published, and only a semaphore - which
+        // covers plain user-buffer stores - needs the stores to have completed.
+        if (LL ? (pops || hasdep) : (pushes || pops || hasdep)) {
           // Every wavefront waits until its own stores have completed at device scope (the store counter
           // retires a device-scope store only then) BEFORE the barrier: a workgroup-scope barrier alone
           // does not wait for outstanding global stores on this target, and the flag written below
           // must never overtake the payload.
-          __builtin_amdgcn_s_waitcnt(0);
-          __syncthreads();
+          if (!LL || hasdep) __builtin_amdgcn_s_waitcnt(0);
+          if (LL) {
+            if (__syncthreads_or(data_ok ? 0 : 1)) return;     // a thread gave up waiting for data
+          } else {
+            __syncthreads();
+          }
           if (tid == 0) {
             if (GC3_CONSERVATIVE_FENCES) __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
-            if (pushes) store_flag(tail_send, p.run_base + send_seq);
+            if (pushes && !LL) store_flag(tail_send, p.run_base + send_seq);
             if (pops) store_flag(head_recv, p.run_base + recv_seq);
             if (hasdep) store_flag(my_sem, p.run_base + (uint64_t)t * tb.ninstr + s + 1);
           }
@@ -446,20 +545,22 @@ __global__ void __launch_bounds__(512) gc3_interpreter(KParams p) {
 }
 
 // Host-callable launcher; returns the hipError_t of the launch.  `coherent_user` selects the
-// instantiation for programs with cross-thread-block dependencies.
+// instantiation for programs with cross-thread-block dependencies, `ll` the LL protocol.
 template <int DT>
-static int launch_dt(bool coh, unsigned grid, unsigned block, hipStream_t st, const KParams& p) {
-  if (coh) hipLaunchKernelGGL((gc3_interpreter<DT, true>), dim3(grid), dim3(block), 0, st, p);
-  else hipLaunchKernelGGL((gc3_interpreter<DT, false>), dim3(grid), dim3(block), 0, st, p);
+static int launch_dt(bool coh, bool ll, unsigned grid, unsigned block, hipStream_t st, const KParams& p) {
+  if (coh && ll) hipLaunchKernelGGL((gc3_interpreter<DT, true, true>), dim3(grid), dim3(block), 0, st, p);
+  else if (coh) hipLaunchKernelGGL((gc3_interpreter<DT, true, false>), dim3(grid), dim3(block), 0, st, p);
+  else if (ll) hipLaunchKernelGGL((gc3_interpreter<DT, false, true>), dim3(grid), dim3(block), 0, st, p);
+  else hipLaunchKernelGGL((gc3_interpreter<DT, false, false>), dim3(grid), dim3(block), 0, st, p);
   return (int)hipGetLastError();
 }
 
-int launch_interpreter(int dtype, bool coherent_user, unsigned grid, unsigned block, void* stream, const KParams& p) {
+int launch_interpreter(int dtype, bool coherent_user, bool ll, unsigned grid, unsigned block, void* stream, const KParams& p) {
   hipStream_t st = (hipStream_t)stream;
   switch (dtype) {
-    case GC3_F32: return launch_dt<GC3_F32>(coherent_user, grid, block, st, p);
-    case GC3_F16: return launch_dt<GC3_F16>(coherent_user, grid, block, st, p);
-    case GC3_BF16: return launch_dt<GC3_BF16>(coherent_user, grid, block, st, p);
+    case GC3_F32: return launch_dt<GC3_F32>(coherent_user, ll, grid, block, st, p);
+    case GC3_F16: return launch_dt<GC3_F16>(coherent_user, ll, grid, block, st, p);
+    case GC3_BF16: return launch_dt<GC3_BF16>(coherent_user, ll, grid, block, st, p);
     default: return (int)hipErrorInvalidValue;
   }
 }
@@ -468,9 +569,13 @@ int launch_interpreter(int dtype, bool coherent_user, unsigned grid, unsigned bl
 // instantiations.
 int interpreter_occupancy(unsigned block, int* out) {
   int best = 1 << 30;
-  const void* fns[] = {(const void*)gc3_interpreter<GC3_F32, false>, (const void*)gc3_interpreter<GC3_F32, true>,
-                       (const void*)gc3_interpreter<GC3_F16, false>, (const void*)gc3_interpreter<GC3_F16, true>,
-                       (const void*)gc3_interpreter<GC3_BF16, false>, (const void*)gc3_interpreter<GC3_BF16, true>};
+  const void* fns[] = {
+      (const void*)gc3_interpreter<GC3_F32, false, false>, (const void*)gc3_interpreter<GC3_F32, true, false>,
+      (const void*)gc3_interpreter<GC3_F16, false, false>, (const void*)gc3_interpreter<GC3_F16, true, false>,
+      (const void*)gc3_interpreter<GC3_BF16, false, false>, (const void*)gc3_interpreter<GC3_BF16, true, false>,
+      (const void*)gc3_interpreter<GC3_F32, false, true>, (const void*)gc3_interpreter<GC3_F32, true, true>,
+      (const void*)gc3_interpreter<GC3_F16, false, true>, (const void*)gc3_interpreter<GC3_F16, true, true>,
+      (const void*)gc3_interpreter<GC3_BF16, false, true>, (const void*)gc3_interpreter<GC3_BF16, true, true>};
   for (const void* f : fns) {
     int n = 0;
     hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, f, (int)block, 0);

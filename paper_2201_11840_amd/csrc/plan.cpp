@@ -35,6 +35,12 @@ int resolve_config(const gc3_comm_config* cfg_in, gc3_comm_config& cfg, std::str
   if (cfg.target_wgs < 0) { msg = "target_wgs must not be negative"; return GC3_ERR_ARG; }
   if (cfg.reserved0 != 0) { msg = "reserved0 must be 0"; return GC3_ERR_ARG; }
   if (cfg.debug_hold < 0 || cfg.debug_hold > 1) { msg = "debug_hold must be 0 or 1"; return GC3_ERR_ARG; }
+  if (cfg.protocol < 0 || cfg.protocol > 3) { msg = "protocol must be 0..3"; return GC3_ERR_ARG; }
+  if (cfg.ll_max_lane_bytes == 0) cfg.ll_max_lane_bytes = 8192;
+  if (cfg.ll_max_lane_bytes < 16 || cfg.ll_max_lane_bytes % 16 || cfg.ll_max_lane_bytes > 65536) {
+    msg = "ll_max_lane_bytes must be a multiple of 16 in [16, 65536]";
+    return GC3_ERR_ARG;
+  }
   if (cfg.min_lane_bytes == 0) cfg.min_lane_bytes = 8192;
   if (cfg.min_lane_bytes < 16 || cfg.min_lane_bytes % 16) { msg = "min_lane_bytes must be a positive multiple of 16"; return GC3_ERR_ARG; }
   return GC3_OK;
@@ -233,6 +239,19 @@ int make_plan(const gc3_program& prog, const gc3_comm_config& cfg, int cus, long
   const uint64_t slot_bytes = (uint64_t)max_count * (uint64_t)tile_bytes;
   const uint64_t fifo_bytes = std::max<uint64_t>(16, (uint64_t)nconn * W * cfg.fifo_slots * slot_bytes);
   if (slot_bytes > (1ull << 30) || fifo_bytes > (64ull << 30)) { msg = "FIFO memory too large"; return GC3_ERR_SIZE; }
+  int protocol = cfg.protocol;
+  if (protocol == 0) protocol = prog.protocol == "simple" ? 1 : (prog.protocol == "ll" || prog.protocol == "ll128") ? 2 : 3;
+  const uint64_t ll_slot_bytes = 2ull * max_count * (uint64_t)cfg.ll_max_lane_bytes;
+  const uint64_t ll_fifo_bytes = protocol == 1 ? 0 : std::max<uint64_t>(16, (uint64_t)nconn * W * cfg.fifo_slots * ll_slot_bytes);
+  if (ll_fifo_bytes > (64ull << 30)) { msg = "LL FIFO memory too large"; return GC3_ERR_SIZE; }
+  int max_pushes = 0;
+  for (int r = 0; r < R; ++r)
+    for (auto& tb : prog.rank[r].tbs) {
+      int n = 0;
+      for (auto& in : tb.instrs) n += op_pushes(in.op) ? 1 : 0;
+      max_pushes = std::max(max_pushes, n);
+    }
+  plan.max_pushes = max_pushes;
   plan.nconn = nconn;
   plan.ntb = ntb;
   plan.max_count = max_count;
@@ -250,6 +269,8 @@ int make_plan(const gc3_program& prog, const gc3_comm_config& cfg, int cus, long
   plan.info.fifo_bytes = fifo_bytes;
   plan.info.compute_units = cus;
   plan.info.max_fibers_per_wg = max_fibers;
+  plan.info.protocol = protocol;
+  plan.info.ll_fifo_bytes = ll_fifo_bytes;
   return GC3_OK;
 }
 

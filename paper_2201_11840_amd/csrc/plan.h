@@ -17,6 +17,7 @@ struct Plan {
   std::vector<uint32_t> wg_begin;  // [grid + 1]
   std::vector<uint32_t> wg_fibers;
   int nconn = 0, ntb = 0, max_count = 1;
+  int max_pushes = 0;              // most send-type instructions in one thread block (messages per tile)
   uint64_t algorithmic_chunks = 0;
   gc3_comm_info info{};
 };

@@ -99,6 +99,8 @@ static int parse(const char* text, size_t len, gc3_program& p, std::string& msg)
     } else if (k == "name" || k == "collective" || k == "protocol") {
       if (t.size() != 2) return fail("expected one token after " + k);
       (k == "name" ? p.name : k == "collective" ? p.collective : p.protocol) = t[1];
+      if (k == "protocol" && t[1] != "simple" && t[1] != "ll" && t[1] != "ll128" && t[1] != "auto")
+        return fail("protocol must be simple, ll, ll128 or auto");
     } else if (k == "inplace") {
       int32_t v;
       if (t.size() != 2 || !parse_int(t[1], 0, 1, &v)) return fail("inplace takes 0 or 1");

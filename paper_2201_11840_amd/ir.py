@@ -15,7 +15,7 @@ comment, one statement per line):
     name <token>
     collective <token>
     inplace <0|1>
-    protocol <token>                 (stored, ignored by the runtime)
+    protocol <simple|ll|ll128|auto>  (Section 6.1 protocols; auto = the runtime picks by message size)
     ranks <R>
     chunks <in_chunks> <out_chunks>  (per rank)
     rank <r> scratch <n_chunks> tbs <n_tbs>      (ranks in order 0..R-1)

@@ -37,31 +37,40 @@ def compare(got, want, dtype, exact_only=False):
 
 def run_case(prog, dtype, elems, dist="normal", seed=1234, cfg=None, repeats=1, exact_only=False):
     """Run `prog` on the GPU and in the oracle on the same seeded inputs; compare every output element
-    of every rank (and the inputs of out-of-place programs, which must be untouched)."""
+    of every rank (and the inputs of out-of-place programs, which must be untouched).  With an explicit
+    configuration both protocols (payload + flag, and LL) are exercised unless it fixes one."""
     H = _harness()
     text = prog.to_text()
     p = oracle.parse_program(text)
     ins = inputs.make_inputs(p.ranks, elems, dtype, dist, seed)
     out_elems = elems // p.in_chunks * p.out_chunks
     outs = None if p.inplace else inputs.sentinel_outputs(p.ranks, out_elems, dtype)
-    coll = H.Collective(text, dtype, elems, cfg)
-    try:
-        want_in = [a.copy() for a in ins]
-        want_out = None if p.inplace else [a.copy() for a in outs]
-        oracle.run_program(p, want_in, want_out, dtype, slots=coll.info.fifo_slots)
-        for _ in range(repeats):
-            coll.upload(ins, outs)
-            coll.run()
-            coll.status()
-            got_out = coll.download("out")
-            for r in range(p.ranks):
-                compare(got_out[r], (want_in if p.inplace else want_out)[r], dtype, exact_only)
-            if not p.inplace:
-                got_in = coll.download("in")
+    want_in = [a.copy() for a in ins]
+    want_out = None if p.inplace else [a.copy() for a in outs]
+    oracle.run_program(p, want_in, want_out, dtype, slots=8)
+    protocols = [None]
+    if cfg is not None and cfg.protocol == 0:
+        protocols = [1, 2]
+    for proto in protocols:
+        if proto is not None:
+            cfg.protocol = proto
+        coll = H.Collective(text, dtype, elems, cfg)
+        try:
+            for _ in range(repeats):
+                coll.upload(ins, outs)
+                coll.run()
+                coll.status()
+                got_out = coll.download("out")
                 for r in range(p.ranks):
-                    assert got_in[r].tobytes() == ins[r].tobytes()
-    finally:
-        coll.close()
+                    compare(got_out[r], (want_in if p.inplace else want_out)[r], dtype, exact_only)
+                if not p.inplace:
+                    got_in = coll.download("in")
+                    for r in range(p.ranks):
+                        assert got_in[r].tobytes() == ins[r].tobytes()
+        finally:
+            coll.close()
+            if proto is not None:
+                cfg.protocol = 0
 
 
 def small_cfg(**kw):
