@@ -78,10 +78,11 @@ typedef struct gc3_program_info {
 /* Tunables of a communicator.  Zero in any field selects the default. */
 typedef struct gc3_comm_config {
   int32_t fifo_slots;      /* s of Section 6.1, 1..8; default 2 */
-  int32_t tile_bytes;      /* bytes of one chunk a workgroup moves per tile (Section 6.2, chunk
-                              tiling); multiple of 16, at most 1 MiB; default 32768, halved (not
-                              below 16384) while all FIFOs together exceed 256 MiB.  A FIFO slot
-                              holds max_count x tile_bytes. */
+  int32_t tile_bytes;      /* largest number of bytes of one chunk a workgroup moves per tile (Section 6.2,
+                              chunk tiling); multiple of 16, at most 1 MiB; default 65536, halved (not
+                              below 16384) while all FIFOs together exceed 256 MiB.  A FIFO slot holds
+                              max_count x tile_bytes.  A run tiles with about half a lane's share of a
+                              chunk, at least 16 KiB and at most this. */
   int32_t team_width;      /* W: lanes per IR thread block; lane w owns the w-th 1/W of every chunk and
                               has FIFO slots, flags and a semaphore of its own (the runtime applying
                               Section 5.1's parallelize(W)).  Lightly loaded thread blocks of one

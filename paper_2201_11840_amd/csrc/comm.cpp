@@ -272,6 +272,13 @@ int gc3_comm_run(gc3_comm* comm, size_t elems_per_rank, gc3_dtype dtype, gc3_red
     };
     for (uint64_t w = 0; w < Wa; ++w) lane_share = std::max(lane_share, begin(w + 1) - begin(w));
   }
+  // Tile of this run: about half of the largest lane share (two tiles per chunk keep sender and receiver
+  // overlapped), at least 16 KiB, at most the tile the FIFO slots were sized for.
+  {
+    uint64_t t = ((lane_share + 1) / 2 + 255) & ~255ull;
+    t = std::max<uint64_t>(t, 16384);
+    p.tile_bytes = (uint32_t)std::min<uint64_t>(t, (uint64_t)comm->info.tile_bytes);
+  }
   const bool ll = comm->info.protocol == 2 || (comm->info.protocol == 3 && lane_share <= comm->ll_max_lane_bytes);
   p.ll_fifo = comm->d_ll_fifo;
   p.ll_slot_bytes = comm->ll_slot_bytes;

@@ -405,8 +405,8 @@ __global__ void __launch_bounds__(512) gc3_interpreter(KParams p) {
                 if (pending && load_flag(ptr) >= want) pending = false;
                 if (!__any(pending)) break;
                 if (!block) { res = 0; break; }
-                __builtin_amdgcn_s_sleep(1);
-                if ((++spins & 255u) == 0) {
+                if (++spins > 16) __builtin_amdgcn_s_sleep(1);     // poll hard first, politely later
+                if ((spins & 255u) == 0) {
                   if (__hip_atomic_load(p.error, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) { res = -1; break; }
                   if (wall_clock64() - start > p.spin_limit_ticks) {
                     atomicCAS(p.error, 0u, (uint32_t)(-GC3_ERR_TIMEOUT));

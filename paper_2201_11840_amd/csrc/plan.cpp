@@ -227,11 +227,12 @@ int make_plan(const gc3_program& prog, const gc3_comm_config& cfg, int cus, long
   const long grid = (long)wg_lists.size();
 
 
-  // Tile size: 32 KiB per chunk and workgroup unless given; halved (not below 16 KiB) while all FIFOs
-  // together exceed 256 MiB, the size of the memory-side cache they should stay in.
+  // Largest tile (= what a FIFO slot holds per chunk): 64 KiB unless given; halved (not below 16 KiB)
+  // while all FIFOs together exceed 256 MiB, the size of the memory-side cache they should stay in.
+  // A run uses a tile of about half a lane's share of a chunk, within [16 KiB, this].
   int tile_bytes = cfg.tile_bytes;
   if (tile_bytes == 0) {
-    tile_bytes = 32768;
+    tile_bytes = 65536;
     while (tile_bytes > 16384 && (uint64_t)nconn * W * cfg.fifo_slots * max_count * (uint64_t)tile_bytes > (256ull << 20))
       tile_bytes /= 2;
   }

@@ -195,10 +195,10 @@ def test_plan_fills_the_device_without_exceeding_it():
         assert i.slot_bytes == prog.max_count() * i.tile_bytes
     i = plan(programs.ring_allreduce(8, instances=8))
     assert (i.team_width, i.active_wgs, i.max_fibers_per_wg) == (16, 1024, 1)     # one lane per workgroup
-    assert i.fifo_bytes == 64 * 16 * 2 * 32768 and i.tile_bytes == 32768
+    assert i.fifo_bytes == 64 * 16 * 2 * 65536 and i.tile_bytes == 65536
     i = plan(programs.hierarchical_allreduce(2, 8))
     assert i.max_fibers_per_wg >= 2 and i.active_wgs == 1024     # light phases share workgroups
-    assert i.fifo_bytes <= 256 << 20 and i.tile_bytes < 32768   # tile shrunk to keep the FIFOs cache sized
+    assert i.fifo_bytes <= 256 << 20 and i.tile_bytes < 65536   # tile shrunk to keep the FIFOs cache sized
     i = plan(programs.alltonext(3, 8))
     assert i.active_wgs <= 1024 and i.max_fibers_per_wg >= 2      # 396 thread blocks cannot each own 4 lanes
 
