@@ -11,6 +11,10 @@ device-side copy; that restore is outside the timed window (HIP events bracket t
 `value` = algorithmic bytes of one run / mean event time.  A second figure, `back_to_back`, times K
 launches wall-clock with no restore in between (values drift, throughput does not depend on them).
 
+Team width and workgroup target of every workload are picked by the library's own tuner (gc3_comm_tune:
+a few short runs per candidate plan at set-up, before the warm-up) unless --no-tune is given; the plan
+chosen and the planner's untuned figure for the headline workload are part of the output.
+
 Prints ONE JSON line on stdout.
 """
 from __future__ import annotations
@@ -92,8 +96,27 @@ def device_inputs(coll, w, seed):
     torch.cuda.synchronize()
 
 
-def report(w, coll, mean_ms, min_ms, wall_ms):
+TUNE_LAUNCHES_PER_PLAN = 7   # gc3_comm_tune: 2 warm-up + 5 timed runs per plan
+
+
+def report(w, coll, mean_ms, min_ms, wall_ms, prog=None, launches_before_timed=0):
     gbs = coll.algorithmic_bytes / (mean_ms * 1e-3) / 1e9
+    extra = {}
+    if prog is not None:
+        # traffic that has to touch the user buffers even with perfectly cached FIFOs
+        user = coll.algorithmic_bytes - prog.fifo_chunks() * coll.chunk_bytes
+        extra = {"user_buffer_bytes": user, "user_buffer_GBps": round(user / (mean_ms * 1e-3) / 1e9, 1)}
+    rep = coll.tune_report
+    if rep is not None:
+        extra["tuned"] = {"team_width": coll.cfg.team_width, "target_wgs": coll.cfg.target_wgs,
+                          "plans_timed": rep.count,
+                          "untuned_plan_ms_in_tuner": round(rep.tried[0].ms, 5),
+                          "chosen_plan_ms_in_tuner": round(rep.tried[rep.best].ms, 5)}
+    extra["interpreter_launches_before_timed"] = launches_before_timed
+    return {**_report_base(w, coll, mean_ms, min_ms, wall_ms, gbs), **extra}
+
+
+def _report_base(w, coll, mean_ms, min_ms, wall_ms, gbs):
     return {"workload": w.name, "dtype": w.dtype, "ranks": coll.ranks, "bytes_per_rank": w.bytes_per_rank,
             "algorithmic_bytes": coll.algorithmic_bytes, "ms_mean": round(mean_ms, 5), "ms_min": round(min_ms, 5),
             "ms_back_to_back": round(wall_ms, 5), "aggregate_GBps": round(gbs, 1),
@@ -112,6 +135,7 @@ def main() -> int:
     ap.add_argument("--workload", default=HEADLINE)
     ap.add_argument("--no-sweep", action="store_true", help="time the headline workload only")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-tune", action="store_true", help="use the planner's plan as is (no gc3_comm_tune)")
     ap.add_argument("--tile-bytes", type=int, default=0)
     ap.add_argument("--team-width", type=int, default=0)
     ap.add_argument("--fifo-slots", type=int, default=0)
@@ -139,7 +163,25 @@ def main() -> int:
     text = prog.to_text()
     log(f"[bench] generating inputs for {w.name}")
     ins = inputs.make_inputs(prog.ranks, w.elems_per_rank, w.dtype, w.dist, w.seed)
-    coll = harness.Collective(text, w.dtype, w.elems_per_rank, cfg)
+    tune = not args.no_tune
+    untuned = None
+    if tune:
+        # the planner's plan as is, for reference (same protocol)
+        c0 = harness.Collective(text, w.dtype, w.elems_per_rank, cfg)
+        c0.upload(ins)
+        pr0 = [t.clone() for t in c0.inputs] if c0.inplace else None
+        m0, mn0, _ = time_workload(c0, args.steps, args.warmup, pr0)
+        untuned = {"ms_mean": round(m0, 5), "aggregate_GBps": round(c0.algorithmic_bytes / (m0 * 1e-3) / 1e9, 1),
+                   "team_width": c0.info.team_width, "grid": c0.info.grid}
+        before = args.warmup + 2 * args.steps
+        c0.close()
+        del pr0, c0
+        torch.cuda.empty_cache()
+    else:
+        before = 0
+    coll = harness.Collective(text, w.dtype, w.elems_per_rank, cfg, tune=tune)
+    if coll.tune_report is not None:
+        before += coll.tune_report.count * TUNE_LAUNCHES_PER_PLAN
     coll.fill_outputs_with_sentinel()
     coll.upload(ins)
     pristine = [t.clone() for t in coll.inputs] if coll.inplace else None
@@ -148,7 +190,7 @@ def main() -> int:
     gpu_out = coll.download("out")
     log(f"[bench] timing {w.name}: grid={coll.info.grid} W={coll.info.team_width}")
     mean_ms, min_ms, wall_ms = time_workload(coll, args.steps, args.warmup, pristine)
-    head = report(w, coll, mean_ms, min_ms, wall_ms)
+    head = report(w, coll, mean_ms, min_ms, wall_ms, prog, before + 1 + args.warmup)
     alg_bytes = coll.algorithmic_bytes
     coll.close()
     del pristine
@@ -184,12 +226,14 @@ def main() -> int:
             if w2.name == w.name:
                 continue
             log(f"[bench] timing {w2.name}")
-            c2 = harness.Collective(w2.build().to_text(), w2.dtype, w2.elems_per_rank, cfg)
+            prog2 = w2.build()
+            c2 = harness.Collective(prog2.to_text(), w2.dtype, w2.elems_per_rank, cfg, tune=tune)
             device_inputs(c2, w2, w2.seed)
             c2.fill_outputs_with_sentinel()
             pr = [t.clone() for t in c2.inputs] if c2.inplace else None
             m, mn, wl = time_workload(c2, args.steps, args.warmup, pr)
-            sweep.append(report(w2, c2, m, mn, wl))
+            before2 = (c2.tune_report.count * TUNE_LAUNCHES_PER_PLAN if c2.tune_report is not None else 0) + args.warmup
+            sweep.append(report(w2, c2, m, mn, wl, prog2, before2))
             c2.close()
             del pr, c2
             torch.cuda.empty_cache()
@@ -203,9 +247,11 @@ def main() -> int:
         "config": {"workload": args.workload, "ranks": head["ranks"], "bytes_per_rank": head["bytes_per_rank"],
                    "grid": head["grid"], "team_width": head["team_width"], "wg_size": head["wg_size"],
                    "tile_bytes": head["tile_bytes"], "fifo_slots": head["fifo_slots"],
+                   "plan": "chosen by gc3_comm_tune at set-up" if tune else "planner default",
                    "timing": "HIP events around each run on the launch stream; inputs restored outside the window"},
         "frac_of_hbm_peak": round(gbs / HBM_PEAK_GBS, 4),
         "per_rank_algbw_GBps": head["per_rank_algbw_GBps"],
+        "untuned_plan": untuned,
         "ms_per_step_min": round(min_ms, 5),
         "ms_per_step_back_to_back_wall": round(wall_ms, 5),
         "roofline": {"bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",

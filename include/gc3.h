@@ -168,6 +168,35 @@ int gc3_comm_create(const gc3_program* prog, const gc3_comm_config* cfg, gc3_com
 
 int gc3_comm_info_get(const gc3_comm* comm, gc3_comm_info* out);
 
+/* What gc3_comm_tune tried. */
+#define GC3_TUNE_MAX_TRIED 24
+typedef struct gc3_tune_entry {
+  int32_t team_width;      /* W of the plan */
+  int32_t target_wgs;      /* as passed to the planner (0 = default) */
+  int32_t grid;            /* workgroups of the plan */
+  int32_t active_wgs;      /* of them, workgroups that hold work */
+  double ms;               /* mean duration of one run */
+} gc3_tune_entry;
+typedef struct gc3_tune_report {
+  int32_t count;           /* entries filled */
+  int32_t best;            /* index of the fastest */
+  gc3_tune_entry tried[GC3_TUNE_MAX_TRIED];
+} gc3_tune_report;
+
+/* Pick team width and workgroup target for `prog` at one buffer size by measurement (Section 7: the
+ * parallelization of every algorithm is tuned for the system and the buffer size; this does it for the
+ * parallelization the runtime applies).  For the configuration in `base` (may be null) and for team
+ * widths 4..64 x workgroup targets {default, 512, 768} - only over fields `base` leaves 0 - it creates
+ * a communicator on the current device, binds zero-filled stand-in buffers of the real sizes that it
+ * allocates and frees itself, times 5 runs after 2 warm-up runs on `hip_stream`, and writes the
+ * chosen configuration to `*best` (ready for gc3_comm_create): the fastest one if it beats `base`,
+ * which is timed first (report entry 0), by more than 3 %, else `base`.  `report` may be null.
+ * Synchronises the device.  Plans that do not fit the device are skipped.
+ * Errors: GC3_ERR_SIZE (size not a multiple of the chunk count / 16 bytes, or zero), validation errors,
+ * GC3_ERR_TIMEOUT or GC3_ERR_HIP from a tuning run, GC3_ERR_ARG. */
+int gc3_comm_tune(const gc3_program* prog, const gc3_comm_config* base, size_t elems_per_rank, gc3_dtype dtype,
+                  void* hip_stream, gc3_comm_config* best, gc3_tune_report* report);
+
 /* The plan gc3_comm_create would make for `prog` on a device with `compute_units` compute units that
  * holds `max_resident_wgs` workgroups of cfg->wg_size threads at once, without touching any device
  * (host only): team width, grid, sharing of workgroups, FIFO memory (Section 6.2, "Initial Setup":

@@ -7,7 +7,7 @@ from __future__ import annotations
 
 import ctypes as C
 import os
-from typing import Optional
+from typing import Optional, Tuple
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 # GC3_LIB_PATH selects another build of the same library (a tuning variant); there is no other path.
@@ -33,7 +33,7 @@ DTYPE_CODE = {"f32": GC3_F32, "f16": GC3_F16, "bf16": GC3_BF16}
 EXPORTS = ("gc3_last_error", "gc3_program_load", "gc3_program_free", "gc3_program_validate",
            "gc3_program_info_get", "gc3_program_scratch_chunks", "gc3_program_plan", "gc3_comm_create", "gc3_comm_info_get",
            "gc3_comm_bind", "gc3_comm_run", "gc3_comm_algorithmic_bytes", "gc3_comm_status",
-           "gc3_comm_reset", "gc3_comm_destroy")
+           "gc3_comm_reset", "gc3_comm_destroy", "gc3_comm_tune")
 
 
 class ProgramInfo(C.Structure):
@@ -64,6 +64,18 @@ class CommInfo(C.Structure):
                 ("tile_bytes", C.c_int32), ("slot_bytes", C.c_int32), ("fifo_bytes", C.c_uint64),
                 ("compute_units", C.c_int32), ("max_fibers_per_wg", C.c_int32),
                 ("wgs_per_lane", C.c_int32), ("protocol", C.c_int32), ("ll_fifo_bytes", C.c_uint64)]
+
+
+GC3_TUNE_MAX_TRIED = 24
+
+
+class TuneEntry(C.Structure):
+    _fields_ = [("team_width", C.c_int32), ("target_wgs", C.c_int32), ("grid", C.c_int32),
+                ("active_wgs", C.c_int32), ("ms", C.c_double)]
+
+
+class TuneReport(C.Structure):
+    _fields_ = [("count", C.c_int32), ("best", C.c_int32), ("tried", TuneEntry * GC3_TUNE_MAX_TRIED)]
 
 
 class Gc3Error(RuntimeError):
@@ -102,6 +114,8 @@ def lib() -> C.CDLL:
         L.gc3_comm_reset.argtypes = [C.c_void_p]
         L.gc3_comm_destroy.argtypes = [C.c_void_p]
         L.gc3_comm_destroy.restype = None
+        L.gc3_comm_tune.argtypes = [C.c_void_p, C.POINTER(CommConfig), C.c_size_t, C.c_int, C.c_void_p,
+                                    C.POINTER(CommConfig), C.POINTER(TuneReport)]
         _lib = L
     return _lib
 
@@ -188,3 +202,11 @@ def gc3_comm_reset(comm: C.c_void_p) -> None:
 
 def gc3_comm_destroy(comm: C.c_void_p) -> None:
     lib().gc3_comm_destroy(comm)
+
+
+def gc3_comm_tune(prog: C.c_void_p, base: Optional[CommConfig], elems_per_rank: int, dtype: int,
+                  stream: int = 0) -> Tuple[CommConfig, TuneReport]:
+    best, report = CommConfig(), TuneReport()
+    _check(lib().gc3_comm_tune(prog, C.byref(base) if base is not None else None, elems_per_rank, dtype,
+                               C.c_void_p(stream), C.byref(best), C.byref(report)))
+    return best, report

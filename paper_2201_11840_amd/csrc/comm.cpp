@@ -329,4 +329,113 @@ void gc3_comm_destroy(gc3_comm* comm) {
   delete comm;
 }
 
+int gc3_comm_tune(const gc3_program* prog, const gc3_comm_config* base, size_t elems_per_rank, gc3_dtype dtype,
+                  void* hip_stream, gc3_comm_config* best, gc3_tune_report* report) {
+  if (!prog || !best) { set_error("null argument"); return GC3_ERR_ARG; }
+  gc3_comm_config cfg0{};
+  if (base) cfg0 = *base;
+  if (report) std::memset(report, 0, sizeof(*report));
+  gc3_program_info pi{};
+  int rc = gc3_program_info_get(prog, &pi);
+  if (rc != GC3_OK) return rc;
+  const int es = dtype_size(dtype);
+  if (!es) { set_error("unknown dtype"); return GC3_ERR_ARG; }
+  if (elems_per_rank == 0 || elems_per_rank % (size_t)pi.in_chunks) {
+    set_error("elems_per_rank must be a positive multiple of the program's chunk count");
+    return GC3_ERR_SIZE;
+  }
+  const uint64_t cb = (uint64_t)(elems_per_rank / pi.in_chunks) * es;
+  if (cb % 16) { set_error("chunk size is not a multiple of 16 bytes"); return GC3_ERR_SIZE; }
+
+  // zero-filled stand-in buffers of the real sizes, one allocation: per rank input, output, scratch
+  const uint64_t in_b = cb * pi.in_chunks, out_b = pi.inplace ? 0 : cb * pi.out_chunks;
+  std::vector<uint64_t> off(pi.ranks * 3 + 1, 0);
+  uint64_t total = 0;
+  auto place = [&](int slot, uint64_t bytes) { off[slot] = total; total += (bytes + 255) & ~255ull; };
+  for (int r = 0; r < pi.ranks; ++r) {
+    int sc = 0;
+    rc = gc3_program_scratch_chunks(prog, r, &sc);
+    if (rc != GC3_OK) return rc;
+    place(r * 3 + 0, in_b);
+    place(r * 3 + 1, out_b);
+    place(r * 3 + 2, cb * (uint64_t)sc);
+  }
+  off[pi.ranks * 3] = total;
+  struct DeviceBlock { void* p = nullptr; ~DeviceBlock() { if (p) (void)hipFree(p); } } block;
+  struct Events { hipEvent_t a = nullptr, b = nullptr; ~Events() { if (a) (void)hipEventDestroy(a); if (b) (void)hipEventDestroy(b); } } ev;
+  HIP_TRY(hipMalloc(&block.p, std::max<uint64_t>(total, 256)));
+  HIP_TRY(hipMemset(block.p, 0, std::max<uint64_t>(total, 256)));
+  HIP_TRY(hipEventCreate(&ev.a));
+  HIP_TRY(hipEventCreate(&ev.b));
+  hipStream_t st = (hipStream_t)hip_stream;
+
+  static const int widths[] = {0, 4, 8, 16, 32, 64};
+  static const int targets[] = {0, 512, 768};
+  std::vector<std::pair<int, int>> seen;   // (team width, grid) of plans already timed
+  double best_ms = 0;
+  bool have = false, first_only = false;   // first_only: the best so far is still the caller's configuration
+  int last_err = GC3_OK;
+  std::string last_msg;
+  for (int w : widths)
+    for (int t : targets) {
+      gc3_comm_config cfg = cfg0;
+      if (w == 0 && t == 0) { /* the caller's configuration as given comes first */ }
+      else {
+        if ((cfg0.team_width && w) || (cfg0.target_wgs && t)) continue;   // fixed by the caller
+        if (w) cfg.team_width = w;
+        if (t) cfg.target_wgs = t;
+      }
+      gc3_comm* c = nullptr;
+      rc = gc3_comm_create(prog, &cfg, &c);
+      if (rc != GC3_OK) { last_err = rc; last_msg = gc3_last_error(); continue; }
+      struct CommGuard { gc3_comm* c; ~CommGuard() { gc3_comm_destroy(c); } } cg{c};
+      std::pair<int, int> key(c->info.team_width, c->info.grid);
+      if (std::find(seen.begin(), seen.end(), key) != seen.end()) continue;
+      seen.push_back(key);
+      unsigned char* basep = (unsigned char*)block.p;
+      for (int r = 0; r < pi.ranks && rc == GC3_OK; ++r) {
+        void* in = basep + off[r * 3];
+        void* outp = pi.inplace ? in : (void*)(basep + off[r * 3 + 1]);
+        uint64_t sb = off[r * 3 + 3] - off[r * 3 + 2];
+        rc = gc3_comm_bind(c, r, in, outp, basep + off[r * 3 + 2], sb);
+      }
+      const int warm = 2, timed = 5;
+      for (int i = 0; i < warm && rc == GC3_OK; ++i) rc = gc3_comm_run(c, elems_per_rank, dtype, GC3_SUM, st);
+      if (rc == GC3_OK) {
+        HIP_TRY(hipEventRecord(ev.a, st));
+        for (int i = 0; i < timed && rc == GC3_OK; ++i) rc = gc3_comm_run(c, elems_per_rank, dtype, GC3_SUM, st);
+        HIP_TRY(hipEventRecord(ev.b, st));
+      }
+      if (rc == GC3_OK) rc = gc3_comm_status(c);   // synchronises
+      if (rc != GC3_OK) {
+        last_err = rc; last_msg = gc3_last_error();
+        if (rc == GC3_ERR_TIMEOUT || rc == GC3_ERR_HIP) { set_error("tuning run failed: " + last_msg); return rc; }
+        continue;
+      }
+      float ms = 0;
+      HIP_TRY(hipEventElapsedTime(&ms, ev.a, ev.b));
+      double per = (double)ms / timed;
+      // the caller's configuration is timed first and is replaced only by a plan that is faster by more than
+      // the run-to-run noise (3 %); after that every strictly faster plan wins
+      const bool better = !have || (first_only ? per < 0.97 * best_ms : per < best_ms);
+      if (report && report->count < GC3_TUNE_MAX_TRIED) {
+        auto& e = report->tried[report->count];
+        e.team_width = c->info.team_width; e.target_wgs = cfg.target_wgs; e.grid = c->info.grid;
+        e.active_wgs = c->info.active_wgs; e.ms = per;
+        if (better) report->best = report->count;
+        ++report->count;
+      }
+      if (better) {
+        first_only = !have;
+        have = true; best_ms = per;
+        *best = cfg;
+      }
+    }
+  if (!have) {
+    set_error("no configuration could be timed: " + last_msg);
+    return last_err != GC3_OK ? last_err : GC3_ERR_ARG;
+  }
+  return GC3_OK;
+}
+
 }  // extern "C"

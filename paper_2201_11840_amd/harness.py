@@ -19,7 +19,8 @@ make_config = B.make_config
 
 class Collective:
     def __init__(self, ir_text: str, dtype: str, elems_per_rank: int, cfg: Optional[B.CommConfig] = None,
-                 device: str = "cuda:0"):
+                 device: str = "cuda:0", tune: bool = False):
+        """`tune=True` lets gc3_comm_tune pick team width and workgroup target for this size first."""
         if not torch.cuda.is_available():
             raise RuntimeError("no GPU: the GC3 runtime has no CPU path")
         self.device = torch.device(device)
@@ -31,6 +32,11 @@ class Collective:
         try:
             self.pinfo = B.gc3_program_info_get(prog)
             self.scratch_chunks = [B.gc3_program_scratch_chunks(prog, r) for r in range(self.pinfo.ranks)]
+            self.tune_report = None
+            if tune and elems_per_rank:
+                cfg, self.tune_report = B.gc3_comm_tune(prog, cfg, elems_per_rank, self.code,
+                                                        torch.cuda.current_stream().cuda_stream)
+            self.cfg = cfg
             self.comm = B.gc3_comm_create(prog, cfg)
         finally:
             B.gc3_program_free(prog)

@@ -149,6 +149,12 @@ class Program:
         w = {"send": 2, "recv": 2, "copy": 2, "reduce": 3, "rrc": 3, "rcs": 3, "rrcs": 4, "rrs": 3}
         return sum(w[op.opcode] * op.count for r in self.tbs for t in r for op in t.ops)
 
+    def fifo_chunks(self) -> int:
+        """The part of algorithmic_chunks() that is FIFO traffic: one chunk written per pushed and one
+        read per popped message chunk."""
+        return sum(op.count * ((op.opcode in PUSHES) + (op.opcode in POPS))
+                   for r in self.tbs for t in r for op in t.ops)
+
     def to_text(self) -> str:
         out = ["gc3ir 1", f"name {self.name}", f"collective {self.collective}",
                f"inplace {int(self.inplace)}", f"protocol {self.protocol}",

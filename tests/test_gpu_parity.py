@@ -294,6 +294,49 @@ def test_timeout_poisons_and_reset_recovers():
     run_case(prog, "f32", elems, "uniform", 5, small_cfg())
 
 
+def test_tune_measures_plans_and_the_chosen_one_is_correct():
+    H = _harness()
+    from paper_2201_11840_amd import binding as B
+    for prog, dtype, elems in [(programs.ring_allreduce(8, instances=2), "f32", 16 * 8192),
+                               (programs.hierarchical_allreduce(2, 3), "bf16", 6 * 16384),
+                               (programs.alltonext(2, 3), "f16", 3 * 8192)]:
+        text = prog.to_text()
+        p = oracle.parse_program(text)
+        ins = inputs.make_inputs(p.ranks, elems, dtype, "normal", 77)
+        outs = None if p.inplace else inputs.sentinel_outputs(p.ranks, elems // p.in_chunks * p.out_chunks, dtype)
+        want_in = [a.copy() for a in ins]
+        want_out = None if p.inplace else [a.copy() for a in outs]
+        oracle.run_program(p, want_in, want_out, dtype, slots=8)
+        coll = H.Collective(text, dtype, elems, tune=True)
+        rep = coll.tune_report
+        assert 2 <= rep.count <= B.GC3_TUNE_MAX_TRIED and 0 <= rep.best < rep.count
+        tried = [rep.tried[i] for i in range(rep.count)]
+        assert all(t.ms > 0 and t.grid >= t.active_wgs > 0 for t in tried)
+        fastest = min(t.ms for t in tried)
+        if rep.best == 0:                      # the default plan stays unless beaten by more than 3 %
+            assert fastest >= 0.97 * tried[0].ms
+        else:
+            assert tried[rep.best].ms == fastest < 0.97 * tried[0].ms
+        assert len({(t.team_width, t.grid) for t in tried}) == rep.count       # no plan timed twice
+        assert (coll.info.team_width, coll.info.grid) == (tried[rep.best].team_width, tried[rep.best].grid)
+        coll.upload(ins, outs)
+        coll.run()
+        coll.status()
+        for g, w in zip(coll.download("out"), want_in if p.inplace else want_out):
+            compare(g, w, dtype)
+        coll.close()
+    # fields the caller fixes are not varied
+    prog = B.gc3_program_load(programs.ring_allreduce(4).to_text())
+    best, rep = B.gc3_comm_tune(prog, H.make_config(team_width=8, tile_bytes=4096), 4 * 4096, B.GC3_F32)
+    assert best.team_width == 8 and best.tile_bytes == 4096
+    assert all(rep.tried[i].team_width == 8 for i in range(rep.count))
+    # a tuning run that fails ends the tuning with that error (forced from the host: no workgroup starts work)
+    with pytest.raises(B.Gc3Error) as e:
+        B.gc3_comm_tune(prog, H.make_config(spin_limit_us=20000, debug_hold=1), 4 * 4096, B.GC3_F32)
+    assert e.value.status == B.GC3_ERR_TIMEOUT
+    B.gc3_program_free(prog)
+
+
 # ---- the benchmark configurations, default launch configuration -------------------------------------
 
 def _sampled_case(w, n_samples, seed):
@@ -327,6 +370,45 @@ def _sampled_case(w, n_samples, seed):
     # and a property that holds at any size: all ranks of an AllReduce agree bitwise
     for r in range(1, p.ranks):
         assert got[r].tobytes() == got[0].tobytes()
+
+
+def test_headline_under_every_plan_the_tuner_may_choose():
+    # bench.py times the plan gc3_comm_tune picks; whichever it is, it is one of these
+    H = _harness()
+    w = workloads.ring_ar_r8x8(64)
+    prog = w.build()
+    text = prog.to_text()
+    p = oracle.parse_program(text)
+    ce = w.elems_per_rank // p.in_chunks
+    ins = inputs.make_inputs(p.ranks, w.elems_per_rank, w.dtype, w.dist, w.seed)
+    rng = np.random.Generator(np.random.PCG64(9))
+    pos = np.unique(np.concatenate([rng.integers(0, ce, 20000), np.array([0, 1, ce - 2, ce - 1])]))
+    for k in (1, 2, 3, 5, 7, 63):                       # lane boundaries of every width
+        for W in (4, 8, 12, 16, 32, 64):
+            b = min(((ce * 4 // W + 255) // 256 * 256 // 4) * k, ce - 1)
+            pos = np.union1d(pos, np.clip(np.array([b - 1, b, b + 1]), 0, ce - 1))
+    gather = lambda a: a.reshape(p.in_chunks, ce)[:, pos].reshape(-1).copy()
+    want = [gather(a) for a in ins]
+    oracle.run_program(p, want, None, w.dtype, slots=2)
+    seen = set()
+    for W in (0, 4, 8, 16, 32, 64):
+        for tgt in (0, 512, 768):
+            coll = H.Collective(text, w.dtype, w.elems_per_rank, H.make_config(team_width=W, target_wgs=tgt))
+            try:
+                key = (coll.info.team_width, coll.info.grid)
+                if key in seen:
+                    continue
+                seen.add(key)
+                coll.upload(ins)
+                coll.run()
+                coll.status()
+                got = coll.download("out")
+            finally:
+                coll.close()
+            for r in range(p.ranks):
+                assert gather(got[r]).tobytes() == want[r].tobytes(), f"plan W={key[0]} grid={key[1]} rank {r}"
+                assert got[r].tobytes() == got[0].tobytes()
+    assert len(seen) >= 8
 
 
 def test_config1_ring_allreduce_r4():

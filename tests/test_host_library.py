@@ -223,3 +223,22 @@ def test_plan_respects_configuration_and_limits():
     with pytest.raises(B.Gc3Error) as e:
         plan(programs.ring_allreduce(4), fifo_slots=1)             # fused ring needs two slots
     assert e.value.status == B.GC3_ERR_DEADLOCK
+
+
+def test_tune_rejects_bad_sizes_before_touching_a_device():
+    prog = B.gc3_program_load(programs.ring_allreduce(4).to_text())
+    for elems, dtype, status in [(0, B.GC3_F32, B.GC3_ERR_SIZE), (66, B.GC3_F32, B.GC3_ERR_SIZE),
+                                 (8, B.GC3_F32, B.GC3_ERR_SIZE), (64, 99, B.GC3_ERR_ARG)]:
+        with pytest.raises(B.Gc3Error) as e:
+            B.gc3_comm_tune(prog, None, elems, dtype)
+        assert e.value.status == status
+    B.gc3_program_free(prog)
+
+
+@pytest.mark.parametrize("R,k", [(4, 1), (8, 8), (5, 2)])
+def test_ring_user_buffer_traffic_closed_form(R, k):
+    # with perfectly cached FIFOs a fused in-place ring AllReduce still moves (3 - 2/R) x S per rank through the
+    # user buffers: R-1 reads for sends/reductions, R-1 + ... ; in chunks of S/(R k): (3R - 2) k per rank
+    p = programs.ring_allreduce(R, instances=k)
+    assert p.algorithmic_chunks() - p.fifo_chunks() == R * (3 * R - 2) * k
+    assert p.fifo_chunks() == R * k * 2 * (2 * R - 2)       # 2R-2 messages per thread block, written once and read once
