@@ -187,7 +187,7 @@ typedef struct gc3_tune_report {
  * parallelization of every algorithm is tuned for the system and the buffer size; this does it for the
  * parallelization the runtime applies).  For the configuration in `base` (may be null) and for team
  * widths 4..64 x workgroup targets {default, 512, 768} - only over fields `base` leaves 0 - it creates
- * a communicator on the current device, binds zero-filled stand-in buffers of the real sizes that it
+ * a communicator on the current device, binds stand-in buffers of the real sizes (non-zero filler) that it
  * allocates and frees itself, times 5 runs after 2 warm-up runs on `hip_stream`, and writes the
  * chosen configuration to `*best` (ready for gc3_comm_create): the fastest one if it beats `base`,
  * which is timed first (report entry 0), by more than 3 %, else `base`.  `report` may be null.
