@@ -69,13 +69,18 @@ def hierarchical_allreduce(N: int, G: int, intra_parallel: bool = True, **opts) 
     return compile_program(p, **opts)
 
 
-def allpairs_allreduce(R: int, **opts) -> Program:
-    """Section 7.1.2: every rank receives chunk r from every rank, sums, and broadcasts the result."""
-    with GC3Program(f"dsl_allpairs_allreduce_r{R}", "allreduce", R, R, inplace=True) as p:
+def allpairs_allreduce(R: int, via_scratch: bool = False, **opts) -> Program:
+    """Section 7.1.2: every rank receives chunk r from every rank, sums, and broadcasts the result.
+    `via_scratch`: the chunks are first copied into the receiver's scratch buffer and reduced locally."""
+    with GC3Program(f"dsl_allpairs_allreduce_r{R}" + ("_scratch" if via_scratch else ""), "allreduce", R, R,
+                    inplace=True) as p:
         for r in range(R):
             acc = chunk(r, "input", r)
             for d in range(1, R):
-                acc = acc.reduce(chunk((r + d) % R, "input", r))
+                c = chunk((r + d) % R, "input", r)
+                if via_scratch:
+                    c = c.copy(r, "scratch", d - 1)
+                acc = acc.reduce(c)
             for d in range(1, R):
                 acc.copy((r + d) % R, "input", r)
     return compile_program(p, **opts)

@@ -142,26 +142,37 @@ def multichannel_ring_allreduce(R: int, channels: int, name: Optional[str] = Non
 # All Pairs AllReduce (Section 7.1.2)
 # ---------------------------------------------------------------------------
 
-def allpairs_allreduce(R: int, name: Optional[str] = None) -> Program:
+def allpairs_allreduce(R: int, name: Optional[str] = None, via_scratch: bool = False) -> Program:
     """Two communication steps: every rank receives chunk r from every other rank,
     sums them, and broadcasts the result to every other rank (Section 7.1.2).
     R chunks, in-place.  Rank r has one thread block per peer p (send p, recv p,
     channel 0) running: send in[p]; rrc in[r]; send in[r]; recv in[p].  The
     reductions into chunk r by different thread blocks are chained by
     cross-thread-block dependencies so the association order is fixed, and the
-    broadcast waits for the last of them."""
+    broadcast waits for the last of them.
+
+    `via_scratch`: the unfused form - the chunk from the k-th peer is received into
+    scratch[k] and a thread block without peers adds the scratch chunks to in[r] one
+    by one with the local `reduce` instruction (same association order)."""
     if R < 2:
         raise ValueError("needs at least 2 ranks")
-    prog = Program(name or f"allpairs_allreduce_r{R}", "allreduce", R, R, R, inplace=True)
+    prog = Program(name or f"allpairs_allreduce_r{R}" + ("_scratch" if via_scratch else ""), "allreduce", R, R, R,
+                   inplace=True)
     for r in range(R):
         peers = [(r + d) % R for d in range(1, R)]
         tbs = [prog.tb(r, send=p, recv=p, chan=0) for p in peers]
         for tb, p in zip(tbs, peers):
             tb.add("send", src=("i", p))
         prev: Optional[Dep] = None
-        for tb in tbs:
-            step = tb.add("rrc", src=("i", r), dst=("i", r), deps=[prev] if prev else ())
-            prev = (tb, step)
+        if via_scratch:
+            arrived = [(tb, tb.add("recv", dst=("s", k))) for k, tb in enumerate(tbs)]
+            local = prog.tb(r, send=-1, recv=-1, chan=0)
+            for k in range(R - 1):
+                prev = (local, local.add("reduce", src=("s", k), dst=("i", r), deps=[arrived[k]]))
+        else:
+            for tb in tbs:
+                step = tb.add("rrc", src=("i", r), dst=("i", r), deps=[prev] if prev else ())
+                prev = (tb, step)
         for tb in tbs:
             tb.add("send", src=("i", r), deps=[prev])
         for tb, p in zip(tbs, peers):

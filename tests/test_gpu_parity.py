@@ -98,6 +98,10 @@ def test_allreduce_variants(dtype):
     run_case(programs.multichannel_ring_allreduce(5, 3), dtype, 5 * 1000 * m, "normal", 2, small_cfg())
     run_case(programs.allpairs_allreduce(4), dtype, 4 * 1000 * m, "normal", 3, small_cfg())
     run_case(programs.allpairs_allreduce(8), dtype, 8 * 1000 * m, "uniform", 4, small_cfg(team_width=2))
+    # the local `reduce` instruction: chunks land in scratch and a thread block without peers sums them
+    run_case(programs.allpairs_allreduce(4, via_scratch=True), dtype, 4 * 1000 * m, "normal", 5, small_cfg())
+    run_case(programs.allpairs_allreduce(8, via_scratch=True), dtype, 8 * 1000 * m, "uniform", 6, small_cfg(team_width=2))
+    run_case(programs.allpairs_allreduce(8, via_scratch=True), dtype, 8 * 65536 * m, "uniform", 7)
 
 
 @pytest.mark.parametrize("N,G", [(2, 2), (2, 3), (3, 2), (2, 8), (3, 8)])
@@ -130,6 +134,7 @@ def test_compiled_programs():
     run_case(D.hierarchical_allreduce(2, 8), "bf16", 32 * 1000, "normal", 84, small_cfg())
     run_case(D.hierarchical_allreduce(3, 2, intra_parallel=False), "f32", 6 * 1000, "uniform", 85, small_cfg(team_width=2))
     run_case(D.allpairs_allreduce(8), "f32", 8 * 1000, "uniform", 86, small_cfg(team_width=2))
+    run_case(D.allpairs_allreduce(5, via_scratch=True), "bf16", 5 * 2000, "normal", 90, small_cfg())
     run_case(D.twostep_alltoall(2, 3), "f16", 6 * 1000, "normal", 87, small_cfg(), exact_only=True)
     run_case(D.alltonext(3, 8), "f16", 8 * 2000, "normal", 88, small_cfg(team_width=1), exact_only=True)
     # default configuration, 16 MiB per rank

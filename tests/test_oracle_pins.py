@@ -33,7 +33,7 @@ def all_programs():
         out += [programs.ring_allreduce(R), programs.ring_allreduce(R, fuse=False),
                 programs.ring_allreduce(R, use_rrs=True), programs.ring_allreduce(R, instances=3),
                 programs.multichannel_ring_allreduce(R, 2), programs.allpairs_allreduce(R),
-                programs.direct_alltoall(R)]
+                programs.allpairs_allreduce(R, via_scratch=True), programs.direct_alltoall(R)]
     for N, G in GRIDS:
         out += [programs.hierarchical_allreduce(N, G), programs.hierarchical_allreduce(N, G, fuse=False),
                 programs.alltonext(N, G), programs.twostep_alltoall(N, G)]
@@ -144,13 +144,15 @@ def test_ring_closed_forms(R):
     for prog in (fused, unf, programs.multichannel_ring_allreduce(R, 3)):
         _, st = oracle.run_symbolic(parse(prog), slots=2)
         assert st["comm_steps"] == 2 * R - 2                        # ring: 2R-2 communication steps
-    _, st = oracle.run_symbolic(parse(programs.allpairs_allreduce(R)), slots=2)
-    assert st["comm_steps"] == 2                                    # all pairs: 2 steps
+    for ap in (programs.allpairs_allreduce(R), programs.allpairs_allreduce(R, via_scratch=True)):
+        _, st = oracle.run_symbolic(parse(ap), slots=2)
+        assert st["comm_steps"] == 2                                # all pairs: 2 steps
     _, st = oracle.run_symbolic(parse(programs.direct_alltoall(R)), slots=2)
     assert st["comm_steps"] == 1                                    # direct alltoall: one step
     # ring and all pairs exchange the same volume of data (Section 7.1.2)
     sent = lambda p: sum(o.count for r in p.tbs for t in r for o in t.ops if o.opcode in ("send", "rcs", "rrcs", "rrs"))
     assert sent(fused) == sent(programs.allpairs_allreduce(R)) == 2 * R * (R - 1)
+    assert sent(programs.allpairs_allreduce(R, via_scratch=True)) == 2 * R * (R - 1)
 
 
 @pytest.mark.parametrize("R,k", [(4, 2), (8, 8), (3, 5)])
@@ -185,7 +187,7 @@ def test_algorithmic_byte_totals():
 def _allreduce_programs():
     return [programs.ring_allreduce(4), programs.ring_allreduce(4, fuse=False), programs.ring_allreduce(5, use_rrs=True),
             programs.ring_allreduce(8, instances=8), programs.multichannel_ring_allreduce(5, 2),
-            programs.allpairs_allreduce(4), programs.hierarchical_allreduce(2, 3),
+            programs.allpairs_allreduce(4), programs.allpairs_allreduce(5, via_scratch=True), programs.hierarchical_allreduce(2, 3),
             programs.hierarchical_allreduce(2, 8), programs.hierarchical_allreduce(3, 2, fuse=False)]
 
 
