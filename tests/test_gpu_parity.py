@@ -472,3 +472,53 @@ def test_config5_alltonext_3x8():
         assert got[r].tobytes() == ins[r - 1].tobytes()                      # out[i+1] == in[i], bytewise
     # the oracle on a smaller buffer of the same program, element by element
     run_case(prog, w.dtype, 8 * 65536, w.dist, w.seed, exact_only=True)
+
+
+# ---- every opcode on its own: smallest program in which its effect is visible ---------------------------
+
+def _opcode_program(opcode, count):
+    """Three ranks, 2*count input / output chunks, scratch where needed.  Rank 0 feeds, rank 1 runs the
+    instruction under test, rank 2 drains what rank 1 forwards."""
+    from paper_2201_11840_amd.ir import Program
+    C = 2 * count
+    p = Program(f"op_{opcode}_x{count}", "custom", 3, C, C, inplace=False)
+    feed = p.tb(0, send=1, recv=-1, chan=0)
+    mid = p.tb(1, send=2, recv=0, chan=0)
+    drain = p.tb(2, send=-1, recv=1, chan=0)
+    hi = ("i", count)                      # second half of the input
+    if opcode in ("send", "recv"):
+        feed.add("send", src=hi, count=count)
+        mid.add("recv", dst=("o", 0), count=count)
+    elif opcode == "copy":
+        p.tb(1, chan=1).add("copy", src=hi, dst=("o", 0), count=count)
+        p.tb(1, chan=1).add("copy", src=("o", 0), dst=("s", 1), count=count)
+        p.tb(1, chan=1).add("copy", src=("s", 1), dst=("o", count), count=count)
+    elif opcode == "reduce":
+        t = p.tb(1, chan=1)
+        t.add("copy", src=("i", 0), dst=("o", 0), count=count)
+        t.add("reduce", src=hi, dst=("o", 0), count=count)
+    else:
+        feed.add("send", src=("i", 0), count=count)
+        if opcode == "rrc":
+            mid.add("rrc", src=hi, dst=("o", 0), count=count)
+        elif opcode == "rcs":
+            mid.add("rcs", dst=("o", count), count=count)
+        elif opcode == "rrcs":
+            mid.add("rrcs", src=hi, dst=("o", 0), count=count)
+        elif opcode == "rrs":
+            mid.add("rrs", src=hi, count=count)
+        if opcode != "rrc":
+            drain.add("recv", dst=("o", 0), count=count)
+    return p
+
+
+@pytest.mark.parametrize("opcode", ["send", "copy", "reduce", "rrc", "rcs", "rrcs", "rrs"])
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
+def test_single_opcode(opcode, dtype):
+    for count in (1, 3):
+        prog = _opcode_program(opcode, count)
+        es = inputs.ITEMSIZE[dtype]
+        for chunk_bytes in (16, 4096 + 16, 3 * 1024 + 48, 70000 // 16 * 16):
+            elems = 2 * count * chunk_bytes // es
+            run_case(prog, dtype, elems, "normal", 300 + count, small_cfg())
+        run_case(prog, dtype, 2 * count * (1 << 18) // es, "uniform", 310 + count)       # default plan, 256 KiB chunks
