@@ -282,6 +282,7 @@ __device__ __forceinline__ uint64_t lane_begin(uint64_t U, uint32_t w, uint32_t 
 constexpr uint32_t kFiberDone = 0xffffffffu;
 
 __device__ __forceinline__ uint32_t uni(uint32_t v) { return __builtin_amdgcn_readfirstlane(v); }
+__device__ __forceinline__ uint64_t uni64(uint64_t v) { return ((uint64_t)uni((uint32_t)(v >> 32)) << 32) | uni((uint32_t)v); }
 
 // A workgroup runs a short list of FIBERS.  A fiber is one lane of one IR thread block: its own
 // tile counter, step counter and FIFO sequence numbers.  The workgroup visits its unfinished
@@ -294,6 +295,15 @@ __global__ void __launch_bounds__(512) gc3_interpreter(KParams p) {
   __shared__ uint32_t f_id[kMaxFibersPerWg], f_t[kMaxFibersPerWg], f_s[kMaxFibersPerWg];
   __shared__ uint32_t f_send[kMaxFibersPerWg], f_recv[kMaxFibersPerWg];
   __shared__ uint64_t f_off0[kMaxFibersPerWg], f_share[kMaxFibersPerWg];
+  // per fiber: its thread block's record and the three buffer pointers of its rank, fetched once
+  __shared__ uint32_t f_rank[kMaxFibersPerWg], f_ibeg[kMaxFibersPerWg], f_ninstr[kMaxFibersPerWg], f_ilds[kMaxFibersPerWg];
+  __shared__ int32_t f_sconn[kMaxFibersPerWg], f_rconn[kMaxFibersPerWg];
+  __shared__ uint64_t f_buf[kMaxFibersPerWg][3];
+  // the instruction lists of this workgroup's fibers, when they fit (else they are read from global memory
+  // every time): an instruction is fetched once per tile, and a fetch is a dependent global access on the
+  // critical path of every hop
+  __shared__ uint32_t s_instr[kLdsInstrs * 8];
+  __shared__ uint32_t s_ilds_total;
   __shared__ int s_res[2];
 #if GC3_LDS_STAGE
   __shared__ __attribute__((aligned(16))) unsigned char s_stage[kStageBytes];
@@ -335,6 +345,28 @@ __global__ void __launch_bounds__(512) gc3_interpreter(KParams p) {
     f_recv[tid] = 0;
     f_off0[tid] = o;
     f_share[tid] = lane_begin(U, fid % W + 1, p.W_active) - o;
+    const DTb tb = p.tbs[fid / W];
+    f_rank[tid] = tb.rank;
+    f_ibeg[tid] = tb.instr_begin;
+    f_ninstr[tid] = tb.ninstr;
+    f_sconn[tid] = tb.send_conn;
+    f_rconn[tid] = tb.recv_conn;
+    for (int b = 0; b < 3; ++b) f_buf[tid][b] = (uint64_t)p.bufs[tb.rank * 3 + b];
+  }
+  __syncthreads();
+  if (tid == 0) {
+    uint32_t total = 0;
+    for (uint32_t i = 0; i < nf; ++i) { f_ilds[i] = total; total += f_ninstr[i]; }
+    s_ilds_total = total;
+  }
+  __syncthreads();
+  const bool instr_in_lds = s_ilds_total <= (uint32_t)kLdsInstrs;
+  if (instr_in_lds) {
+    const uint32_t* gi = (const uint32_t*)p.instrs;
+    for (uint32_t i = 0; i < nf; ++i) {
+      const uint32_t words = f_ninstr[i] * 8, from = f_ibeg[i] * 8, to = f_ilds[i] * 8;
+      for (uint32_t k = tid; k < words; k += nthreads) s_instr[to + k] = gi[from + k];
+    }
   }
   uint32_t live = nf, phase = 0;
   uint64_t last_progress = wall_clock64();
@@ -347,7 +379,13 @@ __global__ void __launch_bounds__(512) gc3_interpreter(KParams p) {
       if (t == kFiberDone) continue;
       const uint32_t fid = uni(f_id[fi]);
       const uint32_t tbi = fid / W, lane = fid % W;
-      const DTb tb = p.tbs[tbi];
+      DTb tb;
+      tb.rank = uni(f_rank[fi]);
+      tb.instr_begin = uni(f_ibeg[fi]);
+      tb.ninstr = uni(f_ninstr[fi]);
+      tb.send_conn = (int32_t)uni((uint32_t)f_sconn[fi]);
+      tb.recv_conn = (int32_t)uni((uint32_t)f_rconn[fi]);
+      const uint32_t ilds = uni(f_ilds[fi]) * 8;
       const uint64_t off0 = ((uint64_t)uni((uint32_t)(f_off0[fi] >> 32)) << 32) | uni((uint32_t)f_off0[fi]);
       const uint64_t share = ((uint64_t)uni((uint32_t)(f_share[fi] >> 32)) << 32) | uni((uint32_t)f_share[fi]);
       const uint32_t ntiles = (uint32_t)((share + tile - 1) / tile);
@@ -368,7 +406,14 @@ __global__ void __launch_bounds__(512) gc3_interpreter(KParams p) {
         const uint64_t toff = (uint64_t)t * tile;
         const uint32_t len = (uint32_t)(share - toff < tile ? share - toff : tile);   // bytes of this tile, per chunk
         const uint32_t nvec = len >> 4;
-        const DInstr ins = p.instrs[tb.instr_begin + s];
+        DInstr ins;
+        if (instr_in_lds) {
+          const uint32_t* w = s_instr + ilds + s * 8;
+          ins.op = uni(w[0]); ins.srcbuf = uni(w[1]); ins.dstbuf = uni(w[2]); ins.srcidx = uni(w[3]);
+          ins.dstidx = uni(w[4]); ins.count = uni(w[5]); ins.dep_begin = uni(w[6]); ins.ndeps_hasdep = uni(w[7]);
+        } else {
+          ins = p.instrs[tb.instr_begin + s];
+        }
         const uint32_t op = ins.op;
         const bool pops = op == GC3_OP_RECV || op == GC3_OP_RRC || op == GC3_OP_RCS || op == GC3_OP_RRCS || op == GC3_OP_RRS;
         const bool pushes = op == GC3_OP_SEND || op == GC3_OP_RCS || op == GC3_OP_RRCS || op == GC3_OP_RRS;
@@ -433,8 +478,8 @@ __global__ void __launch_bounds__(512) gc3_interpreter(KParams p) {
 
         // ---- move the tile --------------------------------------------------------------------
         const uint64_t coff = off0 + toff;   // byte offset inside each chunk
-        unsigned char* const srcb = ins.srcbuf < 3 ? (unsigned char*)p.bufs[tb.rank * 3 + ins.srcbuf] + (uint64_t)ins.srcidx * p.chunk_bytes + coff : nullptr;
-        unsigned char* const dstb = ins.dstbuf < 3 ? (unsigned char*)p.bufs[tb.rank * 3 + ins.dstbuf] + (uint64_t)ins.dstidx * p.chunk_bytes + coff : nullptr;
+        unsigned char* const srcb = ins.srcbuf < 3 ? (unsigned char*)uni64(f_buf[fi][ins.srcbuf]) + (uint64_t)ins.srcidx * p.chunk_bytes + coff : nullptr;
+        unsigned char* const dstb = ins.dstbuf < 3 ? (unsigned char*)uni64(f_buf[fi][ins.dstbuf]) + (uint64_t)ins.dstidx * p.chunk_bytes + coff : nullptr;
         unsigned char* const rslot = pops ? fifo_recv + (uint64_t)(recv_seq % p.slots) * slot_bytes : nullptr;
         unsigned char* const sslot = pushes ? fifo_send + (uint64_t)(send_seq % p.slots) * slot_bytes : nullptr;
         bool data_ok = true;
