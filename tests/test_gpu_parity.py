@@ -157,6 +157,12 @@ def test_random_compiled_programs(seed):
 
 # ---- edge cases ------------------------------------------------------------------------------------
 
+def test_instruction_lists_longer_than_the_workgroup_cache():
+    # 252 instructions per thread block: more than a workgroup keeps on chip, so they are fetched from global memory
+    run_case(programs.ring_allreduce(64, fuse=False), "f32", 64 * 260, "uniform", 71, small_cfg())
+    run_case(programs.ring_allreduce(64, fuse=False), "bf16", 64 * 4096, "normal", 72)
+
+
 def test_smallest_chunk_and_more_lanes_than_units():
     # chunk = 16 bytes (one unit): lanes beyond the first own nothing and must stay consistent
     run_case(programs.ring_allreduce(4), "f32", 16, "int8", 5, small_cfg(team_width=4))
@@ -522,3 +528,40 @@ def test_single_opcode(opcode, dtype):
             elems = 2 * count * chunk_bytes // es
             run_case(prog, dtype, elems, "normal", 300 + count, small_cfg())
         run_case(prog, dtype, 2 * count * (1 << 18) // es, "uniform", 310 + count)       # default plan, 256 KiB chunks
+
+
+def test_buffers_beyond_4GiB_sampled():
+    """Offsets past 2^32 bytes: 2 ranks x 5 GiB fp32, two chunks of 2.5 GiB.  The buffers repeat a seeded
+    64 MiB host block (so the oracle's inputs come from the shared generator); sampled positions, among them
+    the last elements and both sides of the 4 GiB line, are checked against the oracle."""
+    import torch
+    H = _harness()
+    prog = programs.ring_allreduce(2)
+    text = prog.to_text()
+    p = oracle.parse_program(text)
+    block_elems = 16 << 20                                   # 64 MiB of fp32
+    reps = 80
+    elems = block_elems * reps                               # 5 GiB per rank
+    blocks = inputs.make_inputs(2, block_elems, "f32", "uniform", 991)
+    coll = H.Collective(text, "f32", elems)
+    try:
+        for r in range(2):
+            dev_block = torch.from_numpy(blocks[r]).to(coll.device)
+            coll.inputs[r][:coll.in_bytes].view(torch.float32).view(reps, block_elems).copy_(dev_block.expand(reps, block_elems))
+        torch.cuda.synchronize()
+        coll.run()
+        coll.status()
+        ce = elems // 2
+        rng = np.random.Generator(np.random.PCG64(5))
+        line = (1 << 32) // 4 - ce                           # element of chunk 1 that starts at byte 2^32
+        pos = np.unique(np.concatenate([rng.integers(0, ce, 20000),
+                                        np.array([0, 1, ce - 2, ce - 1, line - 1, line, line + 1])]))
+        idx = torch.from_numpy(np.concatenate([pos, pos + ce])).to(coll.device)
+        got = [coll.inputs[r][:coll.in_bytes].view(torch.float32)[idx].cpu().numpy() for r in range(2)]
+    finally:
+        coll.close()
+    glob = np.concatenate([pos, pos + ce])
+    small = [blocks[r][glob % block_elems].copy() for r in range(2)]
+    oracle.run_program(p, small, None, "f32", slots=2)
+    for r in range(2):
+        assert got[r].tobytes() == small[r].tobytes()
