@@ -292,8 +292,13 @@ int gc3_comm_run(gc3_comm* comm, size_t elems_per_rank, gc3_dtype dtype, gc3_red
     p.ll_base = (uint32_t)comm->ll_next;
     comm->ll_next += messages;
   }
-  // lane-major grid: the workgroups of the active lanes are a prefix
-  const unsigned grid = p.W_active * (unsigned)comm->info.wgs_per_lane;
+  // Lane-major grid: the workgroups of the active lanes are a prefix.  When only some lanes own bytes, the
+  // workgroups of the others take over part of the work: the fiber list of every (lane, bin) is dealt
+  // round-robin to nsplit workgroups, so that on small buffers thread blocks that share a workgroup in the
+  // plan run side by side instead.  Never more workgroups than the plan's (resident) grid.
+  p.wgs_per_lane = (uint32_t)comm->info.wgs_per_lane;
+  p.nsplit = std::max<uint32_t>(1, std::min<uint32_t>(p.W / p.W_active, (uint32_t)comm->info.max_fibers_per_wg));
+  const unsigned grid = p.W_active * p.nsplit * p.wgs_per_lane;
   int e = launch_interpreter((int)dtype, comm->has_deps, ll, grid, (unsigned)comm->info.wg_size, hip_stream, p);
   if (e != 0) return hip_fail((hipError_t)e, "interpreter launch");
   return GC3_OK;

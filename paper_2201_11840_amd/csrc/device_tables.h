@@ -53,6 +53,9 @@ struct KParams {
   uint32_t ll_slot_bytes;  // 2 * max_count * LL tile bytes
   uint32_t ll_base;        // LL flag of message k of this run = ll_base + k + 1 (never 0 within a run)
   uint32_t W_active;       // lanes that own bytes in this run (<= W); the others own nothing and finish at once
+  uint32_t wgs_per_lane;   // workgroups per lane of the static plan (the grid is lane-major)
+  uint32_t nsplit;         // in this run the fiber list of every (lane, bin) is dealt round-robin to this many
+                           // workgroups (1 = as planned); uses the workgroups of lanes that own no bytes
 };
 
 }  // namespace gc3

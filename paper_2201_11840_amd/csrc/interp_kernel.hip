@@ -309,8 +309,13 @@ __global__ void __launch_bounds__(512) gc3_interpreter(KParams p) {
   __shared__ __attribute__((aligned(16))) unsigned char s_stage[kStageBytes];
 #endif
   const uint32_t tid = threadIdx.x, nthreads = blockDim.x;
-  const uint32_t fbeg = p.wg_begin[blockIdx.x];
-  const uint32_t nf = p.wg_begin[blockIdx.x + 1] - fbeg;
+  // blockIdx = (sub * W_active + lane) * wgs_per_lane + bin: this workgroup takes entries sub, sub + nsplit, ...
+  // of the fiber list the plan gives (lane, bin)
+  const uint32_t slot = blockIdx.x / p.wgs_per_lane, bin = blockIdx.x % p.wgs_per_lane;
+  const uint32_t wg = (slot % p.W_active) * p.wgs_per_lane + bin, sub = slot / p.W_active, nsplit = p.nsplit;
+  const uint32_t fbeg = p.wg_begin[wg] + sub;
+  const uint32_t nlist = p.wg_begin[wg + 1] - p.wg_begin[wg];
+  const uint32_t nf = nlist > sub ? (nlist - sub + nsplit - 1) / nsplit : 0;
   if (nf == 0) return;
   if (p.hold) {
     // failure-path test facility: wait (bounded) for a start word that the host never sets
@@ -335,7 +340,7 @@ __global__ void __launch_bounds__(512) gc3_interpreter(KParams p) {
   const uint32_t W = p.W;
   const uint32_t tile = p.tile_bytes;
   if (tid < nf) {
-    const uint32_t fid = p.wg_fibers[fbeg + tid];
+    const uint32_t fid = p.wg_fibers[fbeg + tid * nsplit];
     const uint64_t U = p.chunk_bytes >> 4;
     const uint64_t o = lane_begin(U, fid % W, p.W_active);
     f_id[tid] = fid;
