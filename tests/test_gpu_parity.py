@@ -163,6 +163,19 @@ def test_instruction_lists_longer_than_the_workgroup_cache():
     run_case(programs.ring_allreduce(64, fuse=False), "bf16", 64 * 4096, "normal", 72)
 
 
+@pytest.mark.parametrize("lanes_active", [1, 2, 3])
+def test_idle_lanes_take_over_fibers(lanes_active):
+    # chunks too small for all 8 lanes: the workgroups of the idle lanes run part of the fiber lists
+    # (both protocols, programs whose workgroups hold several thread blocks, cross-thread-block dependencies)
+    H = _harness()
+    cfg = lambda: H.make_config(team_width=8, min_lane_bytes=4096, tile_bytes=2048, target_wgs=64)
+    cb = 4096 * lanes_active + 1024                       # bytes per chunk
+    run_case(programs.hierarchical_allreduce(2, 3), "f32", 6 * cb // 4, "uniform", 61, cfg())
+    run_case(programs.allpairs_allreduce(4, via_scratch=True), "bf16", 4 * cb // 2, "normal", 62, cfg())
+    run_case(programs.alltonext(2, 3), "f16", 3 * cb // 2, "normal", 63, cfg(), exact_only=True)
+    run_case(programs.twostep_alltoall(2, 3), "f16", 6 * cb // 2, "normal", 64, cfg(), exact_only=True)
+
+
 def test_smallest_chunk_and_more_lanes_than_units():
     # chunk = 16 bytes (one unit): lanes beyond the first own nothing and must stay consistent
     run_case(programs.ring_allreduce(4), "f32", 16, "int8", 5, small_cfg(team_width=4))
