@@ -98,7 +98,8 @@ typedef struct gc3_comm_config {
                               start word that nobody sets, so each run ends, after spin_limit_us, with
                               GC3_ERR_TIMEOUT and all workgroups leaving through the error path */
   int32_t min_lane_bytes;  /* a run splits a chunk over at most chunk bytes / min_lane_bytes lanes (at least
-                              one): small chunks are not worth spreading; multiple of 16, default 8192 */
+                              one): small chunks are not worth spreading; multiple of 16, default 8192.  The workgroups of
+                              the lanes left without bytes then share the thread blocks of the active ones */
   int32_t protocol;        /* Section 6.1 "Protocols".  0 = what the program's `protocol` line says:
                               `simple` (payload, then a separate flag), `ll` (every 8 bytes carry 4 bytes of
                               data and a 4-byte flag: lowest latency, half the bandwidth) or `auto` (LL when
@@ -120,7 +121,9 @@ typedef struct gc3_comm_info {
   uint64_t fifo_bytes;       /* device memory held by all FIFOs */
   int32_t compute_units;
   int32_t max_fibers_per_wg; /* most thread-block lanes multiplexed by one workgroup (1 = none shared) */
-  int32_t wgs_per_lane;      /* a run on small chunks launches only active lanes x wgs_per_lane workgroups */
+  int32_t wgs_per_lane;      /* a run launches active lanes x split x wgs_per_lane workgroups: on small chunks only
+                                some lanes own bytes, and the fiber lists are then dealt to up to
+                                team_width / active lanes workgroups each (split) */
   int32_t protocol;          /* 1 simple, 2 LL, 3 auto (after applying the configuration's override) */
   uint64_t ll_fifo_bytes;    /* device memory held by the LL slots */
 } gc3_comm_info;
@@ -217,7 +220,8 @@ int gc3_comm_bind(gc3_comm* comm, int rank, void* input, void* output, void* scr
  * the output buffer holds out_chunks chunks.  The chunk must be a whole number of elements and
  * of 16-byte units.  elems_per_rank = 0 is a no-op.  Errors: GC3_ERR_UNBOUND, GC3_ERR_SIZE,
  * GC3_ERR_POISONED, GC3_ERR_HIP, GC3_ERR_ARG.  A GC3_ERR_TIMEOUT inside the kernel is reported by
- * gc3_comm_status. */
+ * gc3_comm_status.  Not for use under stream capture: the run number is a kernel argument (a captured
+ * launch must not be replayed) and the first run after a bind copies the pointer table and waits for the stream. */
 int gc3_comm_run(gc3_comm* comm, size_t elems_per_rank, gc3_dtype dtype, gc3_redop op, void* hip_stream);
 
 /* Bytes the method loads and stores through global memory in one run of this size:
