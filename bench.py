@@ -127,6 +127,39 @@ def _report_base(w, coll, mean_ms, min_ms, wall_ms, gbs):
             "fifo_MiB": round(coll.info.fifo_bytes / 2 ** 20, 1)}
 
 
+def size_sweep(steps, warmup, tune, cfg):
+    """AllReduce on 8 ranks, fp32, per-rank sizes 4 KiB .. 256 MiB, four schedules of Section 7.1: the time per
+    collective and the per-rank algorithm bandwidth S / time, to show which schedule wins at which size."""
+    import torch
+    from paper_2201_11840_amd import harness, programs, workloads
+    algos = [("ring_x1", lambda: programs.ring_allreduce(8)),
+             ("ring_x8", lambda: programs.ring_allreduce(8, instances=8)),
+             ("ring_4ch", lambda: programs.multichannel_ring_allreduce(8, 4)),
+             ("allpairs", lambda: programs.allpairs_allreduce(8))]
+    rows = []
+    for kib in (4, 16, 64, 256, 1024, 4096, 16384, 65536, 262144):
+        row = {"bytes_per_rank": kib * 1024}
+        for name, build in algos:
+            prog = build()
+            elems = kib * 1024 // 4
+            if elems % prog.in_chunks or (elems // prog.in_chunks * 4) % 16:
+                row[name] = None                      # chunk would not be a whole number of 16-byte units
+                continue
+            w = workloads.Workload(f"{name}_{kib}KiB", build, "f32", kib * 1024, "uniform", 71840)
+            c = harness.Collective(prog.to_text(), "f32", elems, cfg, tune=tune)
+            device_inputs(c, w, w.seed)
+            pr = [t.clone() for t in c.inputs]
+            m, mn, _ = time_workload(c, steps, warmup, pr)
+            row[name] = {"us": round(m * 1e3, 2), "algbw_GBps": round(kib * 1024 / (m * 1e-3) / 1e9, 2),
+                         "team_width": c.info.team_width, "grid": c.info.grid}
+            c.close()
+            del pr, c
+            torch.cuda.empty_cache()
+        log("[bench] size sweep " + json.dumps(row))
+        rows.append(row)
+    return rows
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -136,6 +169,8 @@ def main() -> int:
     ap.add_argument("--no-sweep", action="store_true", help="time the headline workload only")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-tune", action="store_true", help="use the planner's plan as is (no gc3_comm_tune)")
+    ap.add_argument("--size-sweep", action="store_true",
+                    help="also time four AllReduce schedules on 8 ranks from 4 KiB to 256 MiB per rank (adds about a minute)")
     ap.add_argument("--tile-bytes", type=int, default=0)
     ap.add_argument("--team-width", type=int, default=0)
     ap.add_argument("--fifo-slots", type=int, default=0)
@@ -263,6 +298,8 @@ def main() -> int:
                          "up to 1.3x over hand-optimised Two-Step AllToAll (16 nodes, 256xA100); not comparable",
         "workloads": sweep,
     }
+    if args.size_sweep:
+        out["allreduce_size_sweep"] = size_sweep(min(args.steps, 30), min(args.warmup, 10), tune, cfg)
     print(json.dumps(out), flush=True)
     return 0
 
