@@ -237,6 +237,29 @@ int gc3_comm_reset(gc3_comm* comm);
 
 void gc3_comm_destroy(gc3_comm* comm);
 
+/* ---- selection by buffer size (Section 6, introduction) ---- */
+
+/* A program may be fast only for a range of buffer sizes, so the paper's runtime picks the algorithm
+ * from user-configured size ranges (and otherwise falls back to the vendor library, which does not exist
+ * here: a size outside every range is an error).  A selector is an ordered list of (communicator, size
+ * range) entries for one collective; it does not own the communicators, which must outlive it and have
+ * their buffers bound by the caller. */
+typedef struct gc3_selector gc3_selector;
+
+int gc3_selector_create(gc3_selector** out);
+
+/* Append an entry: `comm` serves runs whose per-rank INPUT size in bytes lies in [min_bytes, max_bytes]
+ * (max_bytes = 0: no upper limit).  All entries must agree in the number of ranks and in being in place
+ * or not.  Errors: GC3_ERR_ARG. */
+int gc3_selector_add(gc3_selector* sel, gc3_comm* comm, uint64_t min_bytes, uint64_t max_bytes);
+
+/* gc3_comm_run on the first entry whose range holds elems_per_rank x element size; `chosen` (may be null)
+ * receives its index.  Errors: GC3_ERR_SIZE when no range matches, else those of gc3_comm_run. */
+int gc3_selector_run(gc3_selector* sel, size_t elems_per_rank, gc3_dtype dtype, gc3_redop op, void* hip_stream,
+                     int* chosen);
+
+void gc3_selector_destroy(gc3_selector* sel);
+
 #ifdef __cplusplus
 }
 #endif

@@ -33,7 +33,8 @@ DTYPE_CODE = {"f32": GC3_F32, "f16": GC3_F16, "bf16": GC3_BF16}
 EXPORTS = ("gc3_last_error", "gc3_program_load", "gc3_program_free", "gc3_program_validate",
            "gc3_program_info_get", "gc3_program_scratch_chunks", "gc3_program_plan", "gc3_comm_create", "gc3_comm_info_get",
            "gc3_comm_bind", "gc3_comm_run", "gc3_comm_algorithmic_bytes", "gc3_comm_status",
-           "gc3_comm_reset", "gc3_comm_destroy", "gc3_comm_tune")
+           "gc3_comm_reset", "gc3_comm_destroy", "gc3_comm_tune",
+           "gc3_selector_create", "gc3_selector_add", "gc3_selector_run", "gc3_selector_destroy")
 
 
 class ProgramInfo(C.Structure):
@@ -116,6 +117,11 @@ def lib() -> C.CDLL:
         L.gc3_comm_destroy.restype = None
         L.gc3_comm_tune.argtypes = [C.c_void_p, C.POINTER(CommConfig), C.c_size_t, C.c_int, C.c_void_p,
                                     C.POINTER(CommConfig), C.POINTER(TuneReport)]
+        L.gc3_selector_create.argtypes = [C.POINTER(C.c_void_p)]
+        L.gc3_selector_add.argtypes = [C.c_void_p, C.c_void_p, C.c_uint64, C.c_uint64]
+        L.gc3_selector_run.argtypes = [C.c_void_p, C.c_size_t, C.c_int, C.c_int, C.c_void_p, C.POINTER(C.c_int)]
+        L.gc3_selector_destroy.argtypes = [C.c_void_p]
+        L.gc3_selector_destroy.restype = None
         _lib = L
     return _lib
 
@@ -210,3 +216,23 @@ def gc3_comm_tune(prog: C.c_void_p, base: Optional[CommConfig], elems_per_rank: 
     _check(lib().gc3_comm_tune(prog, C.byref(base) if base is not None else None, elems_per_rank, dtype,
                                C.c_void_p(stream), C.byref(best), C.byref(report)))
     return best, report
+
+
+def gc3_selector_create() -> C.c_void_p:
+    h = C.c_void_p()
+    _check(lib().gc3_selector_create(C.byref(h)))
+    return h
+
+
+def gc3_selector_add(sel: C.c_void_p, comm: C.c_void_p, min_bytes: int, max_bytes: int) -> None:
+    _check(lib().gc3_selector_add(sel, comm, min_bytes, max_bytes))
+
+
+def gc3_selector_run(sel: C.c_void_p, elems_per_rank: int, dtype: int, op: int = GC3_SUM, stream: int = 0) -> int:
+    chosen = C.c_int(-1)
+    _check(lib().gc3_selector_run(sel, elems_per_rank, dtype, op, C.c_void_p(stream), C.byref(chosen)))
+    return chosen.value
+
+
+def gc3_selector_destroy(sel: C.c_void_p) -> None:
+    lib().gc3_selector_destroy(sel)

@@ -446,3 +446,52 @@ int gc3_comm_tune(const gc3_program* prog, const gc3_comm_config* base, size_t e
 }
 
 }  // extern "C"
+
+// ---- selection by buffer size (Section 6, introduction) -----------------------------------------------
+
+struct gc3_selector {
+  struct Entry { gc3_comm* comm; uint64_t lo, hi; };
+  std::vector<Entry> entries;
+};
+
+extern "C" {
+
+int gc3_selector_create(gc3_selector** out) {
+  if (!out) { set_error("null argument"); return GC3_ERR_ARG; }
+  *out = new gc3_selector();
+  return GC3_OK;
+}
+
+int gc3_selector_add(gc3_selector* sel, gc3_comm* comm, uint64_t min_bytes, uint64_t max_bytes) {
+  if (!sel || !comm) { set_error("null argument"); return GC3_ERR_ARG; }
+  if (max_bytes != 0 && max_bytes < min_bytes) { set_error("empty size range"); return GC3_ERR_ARG; }
+  if (!sel->entries.empty()) {
+    const gc3_comm* first = sel->entries.front().comm;
+    if (first->ranks != comm->ranks || first->inplace != comm->inplace) {
+      set_error("entries of a selector must agree in rank count and in being in place or not");
+      return GC3_ERR_ARG;
+    }
+  }
+  sel->entries.push_back({comm, min_bytes, max_bytes == 0 ? UINT64_MAX : max_bytes});
+  return GC3_OK;
+}
+
+int gc3_selector_run(gc3_selector* sel, size_t elems_per_rank, gc3_dtype dtype, gc3_redop op, void* hip_stream,
+                     int* chosen) {
+  if (!sel) { set_error("null selector"); return GC3_ERR_ARG; }
+  const int es = dtype_size(dtype);
+  if (!es) { set_error("unknown dtype"); return GC3_ERR_ARG; }
+  const uint64_t bytes = (uint64_t)elems_per_rank * (uint64_t)es;
+  for (size_t i = 0; i < sel->entries.size(); ++i) {
+    const auto& e = sel->entries[i];
+    if (bytes < e.lo || bytes > e.hi) continue;
+    if (chosen) *chosen = (int)i;
+    return gc3_comm_run(e.comm, elems_per_rank, dtype, op, hip_stream);
+  }
+  set_error("no program is registered for " + std::to_string(bytes) + " bytes per rank");
+  return GC3_ERR_SIZE;
+}
+
+void gc3_selector_destroy(gc3_selector* sel) { delete sel; }
+
+}  // extern "C"

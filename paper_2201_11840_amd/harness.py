@@ -19,8 +19,10 @@ make_config = B.make_config
 
 class Collective:
     def __init__(self, ir_text: str, dtype: str, elems_per_rank: int, cfg: Optional[B.CommConfig] = None,
-                 device: str = "cuda:0", tune: bool = False):
-        """`tune=True` lets gc3_comm_tune pick team width and workgroup target for this size first."""
+                 device: str = "cuda:0", tune: bool = False, share_buffers_with: Optional["Collective"] = None):
+        """`tune=True` lets gc3_comm_tune pick team width and workgroup target for this size first.
+        `share_buffers_with`: use that object's input / output tensors (another program of the same collective on
+        the same data, e.g. for a Selector) instead of allocating new ones; scratch is always this object's own."""
         if not torch.cuda.is_available():
             raise RuntimeError("no GPU: the GC3 runtime has no CPU path")
         self.device = torch.device(device)
@@ -50,8 +52,15 @@ class Collective:
         in_bytes = elems_per_rank * es
         out_bytes = self.chunk_bytes * self.pinfo.out_chunks
         alloc = lambda n: torch.empty(max(n, 16), dtype=torch.uint8, device=self.device)
-        self.inputs = [alloc(in_bytes) for _ in range(self.ranks)]
-        self.outputs = self.inputs if self.inplace else [alloc(out_bytes) for _ in range(self.ranks)]
+        if share_buffers_with is not None:
+            o = share_buffers_with
+            if (o.ranks, o.inplace) != (self.ranks, self.inplace) or o.inputs[0].numel() < in_bytes \
+                    or o.outputs[0].numel() < out_bytes:
+                raise ValueError("cannot share buffers: different rank count / in-place kind, or buffers too small")
+            self.inputs, self.outputs = o.inputs, o.outputs
+        else:
+            self.inputs = [alloc(in_bytes) for _ in range(self.ranks)]
+            self.outputs = self.inputs if self.inplace else [alloc(out_bytes) for _ in range(self.ranks)]
         self.scratch = [alloc(self.scratch_chunks[r] * self.chunk_bytes) if self.scratch_chunks[r] else None
                         for r in range(self.ranks)]
         self.in_bytes, self.out_bytes = in_bytes, out_bytes
@@ -119,3 +128,59 @@ class Collective:
             self.close()
         except Exception:
             pass
+
+
+class Selector:
+    """Several programs of one collective on the same per-rank buffers, each with the range of per-rank input
+    sizes (bytes) it serves; run(elems) executes the first whose range holds the size (gc3_selector_run)."""
+
+    def __init__(self, entries: Sequence[tuple], dtype: str, max_elems_per_rank: int, tune: bool = False,
+                 device: str = "cuda:0"):
+        """entries: (ir_text, min_bytes, max_bytes [, cfg]); max_bytes 0 = unbounded.  With `tune`, every entry is
+        tuned at the largest size of its range (bounded by max_elems_per_rank)."""
+        self.dtype = dtype
+        self.code = B.DTYPE_CODE[dtype]
+        es = ITEMSIZE[dtype]
+        self.colls: List[Collective] = []
+        self.sel = B.gc3_selector_create()
+        first: Optional[Collective] = None
+        for e in entries:
+            text, lo, hi = e[0], e[1], e[2]
+            cfg = e[3] if len(e) > 3 else None
+            if tune:
+                top = max_elems_per_rank if hi == 0 else min(max_elems_per_rank, hi // es)
+                cfg = self._tuned_cfg(text, top, cfg)
+            c = Collective(text, dtype, max_elems_per_rank, cfg, device, share_buffers_with=first)
+            first = first or c
+            self.colls.append(c)
+            B.gc3_selector_add(self.sel, c.comm, lo, hi)
+        self.inputs, self.outputs = first.inputs, first.outputs
+        self.chosen = -1
+
+    def _tuned_cfg(self, text: str, top_elems: int, cfg: Optional[B.CommConfig]) -> Optional[B.CommConfig]:
+        prog = B.gc3_program_load(text)
+        try:
+            chunks = B.gc3_program_info_get(prog).in_chunks
+            top_elems -= top_elems % chunks
+            if top_elems <= 0:
+                return cfg
+            best, _ = B.gc3_comm_tune(prog, cfg, top_elems, self.code, torch.cuda.current_stream().cuda_stream)
+            return best
+        finally:
+            B.gc3_program_free(prog)
+
+    def run(self, elems_per_rank: int) -> int:
+        self.chosen = B.gc3_selector_run(self.sel, elems_per_rank, self.code, B.GC3_SUM,
+                                         torch.cuda.current_stream().cuda_stream)
+        return self.chosen
+
+    def status(self) -> None:
+        for c in self.colls:
+            c.status()
+
+    def close(self) -> None:
+        if getattr(self, "sel", None) is not None:
+            B.gc3_selector_destroy(self.sel)
+            self.sel = None
+        for c in self.colls:
+            c.close()

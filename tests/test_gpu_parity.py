@@ -578,3 +578,37 @@ def test_buffers_beyond_4GiB_sampled():
     oracle.run_program(p, small, None, "f32", slots=2)
     for r in range(2):
         assert got[r].tobytes() == small[r].tobytes()
+
+
+def test_selector_picks_the_program_by_size():
+    # All Pairs for small buffers, the ring above (Section 6: user-configured size ranges; Section 7.1.2)
+    H = _harness()
+    from paper_2201_11840_amd import binding as B
+    small, large = programs.allpairs_allreduce(8), programs.ring_allreduce(8, instances=2)
+    max_elems = 16 * 16384
+    sel = H.Selector([(small.to_text(), 0, 64 * 1024), (large.to_text(), 64 * 1024 + 1, 0)], "f32", max_elems, tune=True)
+    try:
+        for elems, want_idx, prog in ((16 * 64, 0, small), (16 * 1024, 0, small), (16 * 1024 + 64, 1, large), (max_elems, 1, large)):
+            ins = inputs.make_inputs(8, elems, "f32", "uniform", 400 + elems % 97)
+            want = [a.copy() for a in ins]
+            oracle.run_program(oracle.parse_program(prog.to_text()), want, None, "f32", slots=2)
+            import torch
+            for r in range(8):
+                sel.inputs[r][:elems * 4].copy_(torch.from_numpy(ins[r].view(np.uint8)))
+            assert sel.run(elems) == want_idx
+            sel.status()
+            for r in range(8):
+                got = sel.inputs[r][:elems * 4].cpu().numpy().view(np.float32)
+                assert got.tobytes() == want[r].tobytes()
+        # a range that ends: sizes beyond it are refused
+        bounded = B.gc3_selector_create()
+        B.gc3_selector_add(bounded, sel.colls[0].comm, 1024, 4096)
+        with pytest.raises(B.Gc3Error) as e:
+            B.gc3_selector_run(bounded, 16 * 1024, B.GC3_F32)
+        assert e.value.status == B.GC3_ERR_SIZE
+        with pytest.raises(B.Gc3Error) as e:
+            B.gc3_selector_add(bounded, sel.colls[0].comm, 10, 5)
+        assert e.value.status == B.GC3_ERR_ARG
+        B.gc3_selector_destroy(bounded)
+    finally:
+        sel.close()

@@ -243,3 +243,17 @@ def test_ring_user_buffer_traffic_closed_form(R, k):
     p = programs.ring_allreduce(R, instances=k)
     assert p.algorithmic_chunks() - p.fifo_chunks() == R * (3 * R - 2) * k
     assert p.fifo_chunks() == R * k * 2 * (2 * R - 2)       # 2R-2 messages per thread block, written once and read once
+
+
+def test_selector_argument_checks_without_a_device():
+    sel = B.gc3_selector_create()
+    with pytest.raises(B.Gc3Error) as e:
+        B.gc3_selector_run(sel, 1024, B.GC3_F32)          # nothing registered
+    assert e.value.status == B.GC3_ERR_SIZE
+    with pytest.raises(B.Gc3Error) as e:
+        B.gc3_selector_run(sel, 1024, 99)
+    assert e.value.status == B.GC3_ERR_ARG
+    with pytest.raises(B.Gc3Error) as e:
+        B.gc3_selector_add(sel, None, 0, 0)
+    assert e.value.status == B.GC3_ERR_ARG
+    B.gc3_selector_destroy(sel)
