@@ -294,6 +294,10 @@ template <int DT, bool COH, bool LL>
 __global__ void __launch_bounds__(512) gc3_interpreter(KParams p) {
   __shared__ uint32_t f_id[kMaxFibersPerWg], f_t[kMaxFibersPerWg], f_s[kMaxFibersPerWg];
   __shared__ uint32_t f_send[kMaxFibersPerWg], f_recv[kMaxFibersPerWg];
+  // messages of this run the fiber's receiver is known to have consumed (last head flag value seen): a push
+  // polls the head flag only when this does not already show a free slot
+  __shared__ uint32_t f_head[kMaxFibersPerWg];
+  __shared__ uint32_t s_headv[2];
   __shared__ uint64_t f_off0[kMaxFibersPerWg], f_share[kMaxFibersPerWg];
   // per fiber: its thread block's record and the three buffer pointers of its rank, fetched once
   __shared__ uint32_t f_rank[kMaxFibersPerWg], f_ibeg[kMaxFibersPerWg], f_ninstr[kMaxFibersPerWg], f_ilds[kMaxFibersPerWg];
@@ -348,6 +352,7 @@ __global__ void __launch_bounds__(512) gc3_interpreter(KParams p) {
     f_s[tid] = 0;
     f_send[tid] = 0;
     f_recv[tid] = 0;
+    f_head[tid] = 0;
     f_off0[tid] = o;
     f_share[tid] = lane_begin(U, fid % W + 1, p.W_active) - o;
     const DTb tb = p.tbs[fid / W];
@@ -395,6 +400,7 @@ __global__ void __launch_bounds__(512) gc3_interpreter(KParams p) {
       const uint64_t share = ((uint64_t)uni((uint32_t)(f_share[fi] >> 32)) << 32) | uni((uint32_t)f_share[fi]);
       const uint32_t ntiles = (uint32_t)((share + tile - 1) / tile);
       uint32_t s = uni(f_s[fi]), send_seq = uni(f_send[fi]), recv_seq = uni(f_recv[fi]);
+      uint32_t head_known = uni(f_head[fi]);
 
       uint64_t* const tail_send = tb.send_conn >= 0 ? p.flags + ((uint64_t)(tb.send_conn * W + lane) * 2 + 0) * kFlagStrideWords : nullptr;
       uint64_t* const head_send = tb.send_conn >= 0 ? p.flags + ((uint64_t)(tb.send_conn * W + lane) * 2 + 1) * kFlagStrideWords : nullptr;
@@ -424,7 +430,7 @@ __global__ void __launch_bounds__(512) gc3_interpreter(KParams p) {
         const bool pushes = op == GC3_OP_SEND || op == GC3_OP_RCS || op == GC3_OP_RRCS || op == GC3_OP_RRS;
         const uint32_t ndeps = ins.ndeps_hasdep >> 1;
         const bool hasdep = ins.ndeps_hasdep & 1;
-        const bool wait_slot = pushes && send_seq >= p.slots;
+        const bool wait_slot = pushes && send_seq >= head_known + p.slots;
 
         // ---- wait for dependencies, for a message, for a free slot -----------------------------
         // LL: the message's number doubles as the flag carried by every 8 bytes of its payload
@@ -434,6 +440,7 @@ __global__ void __launch_bounds__(512) gc3_interpreter(KParams p) {
         if ((pops && !(LL && block)) || wait_slot || ndeps) {
           if (tid < 64) {
             int res = 1;                                   // 1 ready, 0 not ready, -1 run abandoned
+            uint64_t seen = 0;                             // last flag value this lane loaded
             const uint32_t total = 2 + ndeps;
             for (uint32_t it0 = 0; it0 < total && res == 1; it0 += 64) {
               const uint32_t it = it0 + tid;
@@ -452,7 +459,10 @@ __global__ void __launch_bounds__(512) gc3_interpreter(KParams p) {
               const uint64_t start = wall_clock64();
               uint32_t spins = 0;
               for (;;) {
-                if (pending && load_flag(ptr) >= want) pending = false;
+                if (pending) {
+                  seen = load_flag(ptr);
+                  if (seen >= want) pending = false;
+                }
                 if (!__any(pending)) break;
                 if (!block) { res = 0; break; }
                 if (++spins > 16) __builtin_amdgcn_s_sleep(1);     // poll hard first, politely later
@@ -466,6 +476,9 @@ __global__ void __launch_bounds__(512) gc3_interpreter(KParams p) {
                 }
               }
             }
+            // (only more than 62 dependencies would take the loop above past its first round, in which lane 1
+            // polls the head flag)
+            if (tid == 1 && wait_slot && res == 1 && ndeps <= 62) s_headv[phase & 1] = (uint32_t)(seen - p.run_base);
             if (LL && pops && !block && res == 1) {
               // non-blocking readiness probe: has the first element of the message arrived?
               const uint32_t* first = (const uint32_t*)(fifo_recv + (uint64_t)(recv_seq % p.slots) * slot_bytes);
@@ -479,6 +492,7 @@ __global__ void __launch_bounds__(512) gc3_interpreter(KParams p) {
           ++phase;
           if (res_all < 0) return;     // the run is abandoned; every workgroup leaves the same way
           if (res_all == 0) break;     // not ready: yield to the next fiber
+          if (wait_slot && ndeps <= 62) head_known = uni(s_headv[(phase - 1) & 1]);
         }
 
         // ---- move the tile --------------------------------------------------------------------
@@ -567,6 +581,7 @@ __global__ void __launch_bounds__(512) gc3_interpreter(KParams p) {
           f_s[fi] = s;
           f_send[fi] = send_seq;
           f_recv[fi] = recv_seq;
+          f_head[fi] = head_known;
         }
       }
       if (finished) --live;
