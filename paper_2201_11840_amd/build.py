@@ -1,9 +1,11 @@
 """Build the C-ABI library (libgc3.so) for gfx950 with hipcc, in-tree."""
 from __future__ import annotations
 
+import json
 import os
+import re
 import subprocess
-from typing import Optional, Sequence
+from typing import Dict, List, Optional, Sequence
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
@@ -21,7 +23,7 @@ def build(verbose: bool = False, defines: Sequence[str] = (), out: Optional[str]
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     cmd = [hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-           "-Wall", "-Wno-unused-command-line-argument",
+           "-Wall", "-Wno-unused-command-line-argument", "-Rpass-analysis=kernel-resource-usage",
            "-I", os.path.join(ROOT, "include"), "-I", CSRC,
            "-o", out] + [f"-D{d}" for d in defines] + [os.path.join(CSRC, s) for s in SOURCES]
     if verbose:
@@ -29,9 +31,37 @@ def build(verbose: bool = False, defines: Sequence[str] = (), out: Optional[str]
     res = subprocess.run(cmd, capture_output=True, text=True)
     if res.returncode != 0:
         raise RuntimeError("hipcc failed:\n" + res.stdout + res.stderr)
-    if verbose and res.stderr:
-        print(res.stderr)
+    usage = kernel_resource_usage(res.stderr)
+    with open(os.path.splitext(out)[0] + ".resources.json", "w") as f:
+        json.dump(usage, f, indent=1)
+    other = "\n".join(l for l in res.stderr.splitlines()
+                      if "-Rpass-analysis" not in l and "remark:" not in l and "packed-fp32-ops" not in l)   # host pass: harmless
+    if verbose:
+        if other.strip():
+            print(other)
+        for k in usage:
+            print(f"  {k['name']}: {k['vgprs']} VGPRs, {k['sgprs']} SGPRs, scratch {k['scratch_bytes']} B/lane, "
+                  f"LDS {k['lds_bytes']} B, occupancy {k['occupancy']} waves/SIMD")
     return out
+
+
+def kernel_resource_usage(remarks: str) -> List[Dict]:
+    """The compiler's per-kernel resource report (register counts, scratch, LDS, occupancy) from its
+    -Rpass-analysis=kernel-resource-usage remarks."""
+    out: List[Dict] = []
+    fields = {"VGPRs": "vgprs", "TotalSGPRs": "sgprs", "ScratchSize [bytes/lane]": "scratch_bytes",
+              "LDS Size [bytes/block]": "lds_bytes", "Occupancy [waves/SIMD]": "occupancy"}
+    for line in remarks.splitlines():
+        m = re.search(r"remark: [^:]*:\d+:\d+:\s+(.*?): (\S+) \[-Rpass-analysis", line) or \
+            re.search(r"remark:\s+(?:\S+:\d+:\d+:\s+)?(.*?): (\S+) \[-Rpass-analysis", line)
+        if not m:
+            continue
+        key, val = m.group(1).strip(), m.group(2)
+        if key in ("Function Name", "Name"):
+            out.append({"name": val})
+        elif key in fields and out:
+            out[-1][fields[key]] = int(val)
+    return [k for k in out if "vgprs" in k]
 
 
 if __name__ == "__main__":

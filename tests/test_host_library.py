@@ -257,3 +257,20 @@ def test_selector_argument_checks_without_a_device():
         B.gc3_selector_add(sel, None, 0, 0)
     assert e.value.status == B.GC3_ERR_ARG
     B.gc3_selector_destroy(sel)
+
+
+def test_kernel_resources_of_the_built_library():
+    """The compiler's report for the library that was built: no instantiation of the interpreter may spill to
+    scratch memory or fall under 6 waves per SIMD (6 workgroups of 256 threads per compute unit; the planner
+    aims at 4), which is how a careless change to the kernel shows first."""
+    import json
+    from paper_2201_11840_amd import build
+    path = os.path.splitext(build.LIB_PATH)[0] + ".resources.json"
+    if not os.path.exists(path):
+        pytest.skip("library was built without the resource report")
+    kernels = [k for k in json.load(open(path)) if "gc3_interpreter" in k["name"]]
+    assert len(kernels) == 12                       # 3 data types x dependencies or not x protocol
+    for k in kernels:
+        assert k["scratch_bytes"] == 0, k
+        assert k["occupancy"] >= 6, k
+        assert k["vgprs"] <= 80 and k["lds_bytes"] <= 16384, k
