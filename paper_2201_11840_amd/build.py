@@ -35,7 +35,8 @@ def build(verbose: bool = False, defines: Sequence[str] = (), out: Optional[str]
     with open(os.path.splitext(out)[0] + ".resources.json", "w") as f:
         json.dump(usage, f, indent=1)
     other = "\n".join(l for l in res.stderr.splitlines()
-                      if "-Rpass-analysis" not in l and "remark:" not in l and "packed-fp32-ops" not in l)   # host pass: harmless
+                      if "-Rpass-analysis" not in l and "remark:" not in l and "packed-fp32-ops" not in l   # host pass: harmless
+                      and not re.match(r"\s+\d*\s*\|", l))
     if verbose:
         if other.strip():
             print(other)
