@@ -128,14 +128,15 @@ def _report_base(w, coll, mean_ms, min_ms, wall_ms, gbs):
 
 
 def size_sweep(steps, warmup, tune, cfg):
-    """AllReduce on 8 ranks, fp32, per-rank sizes 4 KiB .. 256 MiB, four schedules of Section 7.1: the time per
+    """AllReduce on 8 ranks, fp32, per-rank sizes 4 KiB .. 256 MiB, five schedules of Section 7.1: the time per
     collective and the per-rank algorithm bandwidth S / time, to show which schedule wins at which size."""
     import torch
     from paper_2201_11840_amd import harness, programs, workloads
     algos = [("ring_x1", lambda: programs.ring_allreduce(8)),
              ("ring_x8", lambda: programs.ring_allreduce(8, instances=8)),
              ("ring_4ch", lambda: programs.multichannel_ring_allreduce(8, 4)),
-             ("allpairs", lambda: programs.allpairs_allreduce(8))]
+             ("allpairs", lambda: programs.allpairs_allreduce(8)),
+             ("allpairs_scratch", lambda: programs.allpairs_allreduce(8, via_scratch=True))]
     rows = []
     for kib in (4, 16, 64, 256, 1024, 4096, 16384, 65536, 262144):
         row = {"bytes_per_rank": kib * 1024}
@@ -170,7 +171,7 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-tune", action="store_true", help="use the planner's plan as is (no gc3_comm_tune)")
     ap.add_argument("--size-sweep", action="store_true",
-                    help="also time four AllReduce schedules on 8 ranks from 4 KiB to 256 MiB per rank (adds about a minute)")
+                    help="also time five AllReduce schedules on 8 ranks from 4 KiB to 256 MiB per rank (adds about a minute)")
     ap.add_argument("--tile-bytes", type=int, default=0)
     ap.add_argument("--team-width", type=int, default=0)
     ap.add_argument("--fifo-slots", type=int, default=0)

@@ -152,8 +152,8 @@ def allpairs_allreduce(R: int, name: Optional[str] = None, via_scratch: bool = F
     broadcast waits for the last of them.
 
     `via_scratch`: the unfused form - the chunk from the k-th peer is received into
-    scratch[k] and a thread block without peers adds the scratch chunks to in[r] one
-    by one with the local `reduce` instruction (same association order)."""
+    scratch[k] and a thread block without peers, once all have arrived, adds the scratch
+    chunks to in[r] one by one with the local `reduce` instruction (same association order)."""
     if R < 2:
         raise ValueError("needs at least 2 ranks")
     prog = Program(name or f"allpairs_allreduce_r{R}" + ("_scratch" if via_scratch else ""), "allreduce", R, R, R,
@@ -168,7 +168,8 @@ def allpairs_allreduce(R: int, name: Optional[str] = None, via_scratch: bool = F
             arrived = [(tb, tb.add("recv", dst=("s", k))) for k, tb in enumerate(tbs)]
             local = prog.tb(r, send=-1, recv=-1, chan=0)
             for k in range(R - 1):
-                prev = (local, local.add("reduce", src=("s", k), dst=("i", r), deps=[arrived[k]]))
+                # one wait for all arrivals (their semaphores are polled side by side), then R-1 local adds
+                prev = (local, local.add("reduce", src=("s", k), dst=("i", r), deps=arrived if k == 0 else ()))
         else:
             for tb in tbs:
                 step = tb.add("rrc", src=("i", r), dst=("i", r), deps=[prev] if prev else ())
