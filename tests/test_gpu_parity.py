@@ -155,6 +155,28 @@ def test_random_compiled_programs(seed):
              small_cfg(fifo_slots=8, team_width=1 + seed % 3), repeats=3)
 
 
+@pytest.mark.parametrize("seed", range(16))
+def test_random_launch_configurations(seed):
+    """Results never depend on the tunables (Section 6.1: b and s are the protocol's business): random team
+    width, slot count, tile, workgroup size, workgroup target and minimum lane size, on programs with shared
+    workgroups, dependencies, aggregation and scratch, with chunk sizes that leave ragged tiles and lanes."""
+    H = _harness()
+    rng = np.random.Generator(np.random.PCG64(9000 + seed))
+    progs = [programs.hierarchical_allreduce(2, 3), programs.hierarchical_allreduce(3, 2, fuse=False),
+             programs.ring_allreduce(5, instances=2), programs.multichannel_ring_allreduce(4, 3),
+             programs.allpairs_allreduce(4, via_scratch=True), programs.allpairs_allreduce(5),
+             programs.twostep_alltoall(2, 3), programs.alltonext(2, 4), programs.ring_allreduce(6, use_rrs=True)]
+    prog = progs[seed % len(progs)]
+    dtype = ("f32", "f16", "bf16")[int(rng.integers(3))]
+    cfg = H.make_config(fifo_slots=int(rng.integers(2, 9)), tile_bytes=int(rng.choice([256, 1024, 4096, 16384, 65536])),
+                        team_width=int(rng.choice([1, 2, 3, 5, 8, 13, 32])), wg_size=int(rng.choice([64, 128, 256, 512])),
+                        target_wgs=int(rng.choice([0, 16, 100, 512])), min_lane_bytes=int(rng.choice([16, 256, 4096, 8192])))
+    unit = 16 // inputs.ITEMSIZE[dtype]
+    chunk_elems = int(rng.choice([1, 3, 17, 250, 1031, 4100])) * unit          # 16 B .. 64 KiB per chunk
+    exact = prog.collective != "allreduce"
+    run_case(prog, dtype, prog.in_chunks * chunk_elems, "normal", 700 + seed, cfg, repeats=2, exact_only=exact)
+
+
 # ---- edge cases ------------------------------------------------------------------------------------
 
 def test_instruction_lists_longer_than_the_workgroup_cache():
