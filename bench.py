@@ -96,7 +96,8 @@ def device_inputs(coll, w, seed):
     torch.cuda.synchronize()
 
 
-TUNE_LAUNCHES_PER_PLAN = 7   # gc3_comm_tune: 2 warm-up + 5 timed runs per plan
+TUNE_LAUNCHES_PER_PLAN = 7   # gc3_comm_tune: 2 warm-up + 5 timed runs per plan ...
+TUNE_EXTRA_LAUNCHES = 6      # ... and 6 more warm-up runs for the first plan
 
 
 def report(w, coll, mean_ms, min_ms, wall_ms, prog=None, launches_before_timed=0):
@@ -217,7 +218,7 @@ def main() -> int:
         before = 0
     coll = harness.Collective(text, w.dtype, w.elems_per_rank, cfg, tune=tune)
     if coll.tune_report is not None:
-        before += coll.tune_report.count * TUNE_LAUNCHES_PER_PLAN
+        before += coll.tune_report.count * TUNE_LAUNCHES_PER_PLAN + TUNE_EXTRA_LAUNCHES
     coll.fill_outputs_with_sentinel()
     coll.upload(ins)
     pristine = [t.clone() for t in coll.inputs] if coll.inplace else None
@@ -268,7 +269,7 @@ def main() -> int:
             c2.fill_outputs_with_sentinel()
             pr = [t.clone() for t in c2.inputs] if c2.inplace else None
             m, mn, wl = time_workload(c2, args.steps, args.warmup, pr)
-            before2 = (c2.tune_report.count * TUNE_LAUNCHES_PER_PLAN if c2.tune_report is not None else 0) + args.warmup
+            before2 = (c2.tune_report.count * TUNE_LAUNCHES_PER_PLAN + TUNE_EXTRA_LAUNCHES if c2.tune_report is not None else 0) + args.warmup
             sweep.append(report(w2, c2, m, mn, wl, prog2, before2))
             c2.close()
             del pr, c2

@@ -191,9 +191,9 @@ typedef struct gc3_tune_report {
  * parallelization the runtime applies).  For the configuration in `base` (may be null) and for team
  * widths 4..64 x workgroup targets {default, 512, 768} - only over fields `base` leaves 0 - it creates
  * a communicator on the current device, binds stand-in buffers of the real sizes (non-zero filler) that it
- * allocates and frees itself, times 5 runs after 2 warm-up runs on `hip_stream`, and writes the
+ * allocates and frees itself, times 5 runs after 2 warm-up runs (8 for the first plan) on `hip_stream`, and writes the
  * chosen configuration to `*best` (ready for gc3_comm_create): the fastest one if it beats `base`,
- * which is timed first (report entry 0), by more than 3 %, else `base`.  `report` may be null.
+ * which is timed first (report entry 0), by more than 2 %, else `base`.  `report` may be null.
  * Synchronises the device.  Plans that do not fit the device are skipped.
  * Errors: GC3_ERR_SIZE (size not a multiple of the chunk count / 16 bytes, or zero), validation errors,
  * GC3_ERR_TIMEOUT or GC3_ERR_HIP from a tuning run, GC3_ERR_ARG. */

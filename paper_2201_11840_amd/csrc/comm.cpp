@@ -406,7 +406,8 @@ int gc3_comm_tune(const gc3_program* prog, const gc3_comm_config* base, size_t e
         uint64_t sb = off[r * 3 + 3] - off[r * 3 + 2];
         rc = gc3_comm_bind(c, r, in, outp, basep + off[r * 3 + 2], sb);
       }
-      const int warm = 2, timed = 5;
+      // the first plan timed also pays for cold code and freshly mapped stand-in buffers: warm it longer
+      const int warm = seen.size() == 1 ? 8 : 2, timed = 5;
       for (int i = 0; i < warm && rc == GC3_OK; ++i) rc = gc3_comm_run(c, elems_per_rank, dtype, GC3_SUM, st);
       if (rc == GC3_OK) {
         HIP_TRY(hipEventRecord(ev.a, st));
@@ -423,8 +424,8 @@ int gc3_comm_tune(const gc3_program* prog, const gc3_comm_config* base, size_t e
       HIP_TRY(hipEventElapsedTime(&ms, ev.a, ev.b));
       double per = (double)ms / timed;
       // the caller's configuration is timed first and is replaced only by a plan that is faster by more than
-      // the run-to-run noise (3 %); after that every strictly faster plan wins
-      const bool better = !have || (first_only ? per < 0.97 * best_ms : per < best_ms);
+      // the run-to-run noise (2 %); after that every strictly faster plan wins
+      const bool better = !have || (first_only ? per < 0.98 * best_ms : per < best_ms);
       if (report && report->count < GC3_TUNE_MAX_TRIED) {
         auto& e = report->tried[report->count];
         e.team_width = c->info.team_width; e.target_wgs = cfg.target_wgs; e.grid = c->info.grid;

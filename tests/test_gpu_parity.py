@@ -359,10 +359,10 @@ def test_tune_measures_plans_and_the_chosen_one_is_correct():
         tried = [rep.tried[i] for i in range(rep.count)]
         assert all(t.ms > 0 and t.grid >= t.active_wgs > 0 for t in tried)
         fastest = min(t.ms for t in tried)
-        if rep.best == 0:                      # the default plan stays unless beaten by more than 3 %
-            assert fastest >= 0.97 * tried[0].ms
+        if rep.best == 0:                      # the default plan stays unless beaten by more than 2 %
+            assert fastest >= 0.98 * tried[0].ms
         else:
-            assert tried[rep.best].ms == fastest < 0.97 * tried[0].ms
+            assert tried[rep.best].ms == fastest < 0.98 * tried[0].ms
         assert len({(t.team_width, t.grid) for t in tried}) == rep.count       # no plan timed twice
         assert (coll.info.team_width, coll.info.grid) == (tried[rep.best].team_width, tried[rep.best].grid)
         coll.upload(ins, outs)
