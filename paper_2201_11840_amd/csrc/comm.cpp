@@ -54,11 +54,10 @@ struct gc3_comm {
   uint64_t spin_limit_ticks = 0;
 
   // device allocations
-  DTb* d_tbs = nullptr;
   DInstr* d_instrs = nullptr;
   DDep* d_deps = nullptr;
-  uint32_t* d_wg_begin = nullptr;
-  uint32_t* d_wg_fibers = nullptr;
+  DWg* d_wgs = nullptr;
+  DFiber* d_fibers = nullptr;
   void** d_bufs = nullptr;
   unsigned char* d_fifo = nullptr;
   unsigned char* d_ll_fifo = nullptr;
@@ -77,7 +76,7 @@ struct gc3_comm {
 
   ~gc3_comm() {
     // best effort; errors on teardown are ignored
-    for (void* q : {(void*)d_tbs, (void*)d_instrs, (void*)d_deps, (void*)d_wg_begin, (void*)d_wg_fibers, (void*)d_bufs,
+    for (void* q : {(void*)d_instrs, (void*)d_deps, (void*)d_wgs, (void*)d_fibers, (void*)d_bufs,
                     (void*)d_fifo, (void*)d_ll_fifo, (void*)d_flags, (void*)d_sems, (void*)d_error})
       if (q) (void)hipFree(q);
   }
@@ -124,11 +123,10 @@ int gc3_comm_create(const gc3_program* prog, const gc3_comm_config* cfg_in, gc3_
   const int W = plan.info.team_width;
   c->flags_bytes = std::max<size_t>(1, (size_t)plan.nconn * W * 2) * kFlagStrideWords * sizeof(uint64_t);
   c->sems_bytes = std::max<size_t>(1, (size_t)plan.ntb * W) * kFlagStrideWords * sizeof(uint64_t);
-  if ((rc = upload(&c->d_tbs, plan.tbs)) != GC3_OK) return rc;
   if ((rc = upload(&c->d_instrs, plan.instrs)) != GC3_OK) return rc;
   if ((rc = upload(&c->d_deps, plan.deps)) != GC3_OK) return rc;
-  if ((rc = upload(&c->d_wg_begin, plan.wg_begin)) != GC3_OK) return rc;
-  if ((rc = upload(&c->d_wg_fibers, plan.wg_fibers)) != GC3_OK) return rc;
+  if ((rc = upload(&c->d_wgs, plan.wgs)) != GC3_OK) return rc;
+  if ((rc = upload(&c->d_fibers, plan.fibers)) != GC3_OK) return rc;
   HIP_TRY(hipMalloc((void**)&c->d_bufs, (size_t)R * 3 * sizeof(void*)));
   HIP_TRY(hipMalloc((void**)&c->d_fifo, plan.info.fifo_bytes));
   if (plan.info.ll_fifo_bytes) {
@@ -201,6 +199,7 @@ static int chunk_bytes_of(const gc3_comm* comm, size_t elems, int dtype, uint64_
   if (elems % (size_t)comm->in_chunks) { set_error("elems_per_rank is not a multiple of the program's chunk count"); return GC3_ERR_SIZE; }
   uint64_t cb = (uint64_t)(elems / comm->in_chunks) * es;
   if (cb % 16) { set_error("chunk size is not a multiple of 16 bytes"); return GC3_ERR_SIZE; }
+  if (cb >> 40) { set_error("chunks of 1 TiB and more are not supported"); return GC3_ERR_SIZE; }
   *out = cb;
   return GC3_OK;
 }
@@ -240,11 +239,10 @@ int gc3_comm_run(gc3_comm* comm, size_t elems_per_rank, gc3_dtype dtype, gc3_red
     comm->bufs_dirty = false;
   }
   KParams p{};
-  p.tbs = comm->d_tbs;
   p.instrs = comm->d_instrs;
   p.deps = comm->d_deps;
-  p.wg_begin = comm->d_wg_begin;
-  p.wg_fibers = comm->d_wg_fibers;
+  p.wgs = comm->d_wgs;
+  p.fibers = comm->d_fibers;
   p.bufs = comm->d_bufs;
   p.fifo = comm->d_fifo;
   p.flags = comm->d_flags;

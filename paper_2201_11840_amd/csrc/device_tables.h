@@ -26,19 +26,35 @@ struct DDep {              // 16 bytes
   uint32_t pad;
 };
 
-struct DTb {               // 32 bytes
+struct DTb {               // 32 bytes (host side: one per IR thread block)
   uint32_t rank;
   uint32_t instr_begin, ninstr;
   int32_t send_conn, recv_conn;  // connection index or -1
   uint32_t pad[3];
 };
 
+// What a workgroup needs to start, laid out so that it is two dependent loads away from the kernel
+// arguments: its own header, then - side by side - its fiber records, the instructions of its bin (the
+// instruction table is ordered by bin, so they are one contiguous range) and its rank's buffer pointers.
+struct DWg {               // 32 bytes, one per (lane, bin) of the plan
+  uint32_t fiber_begin, nfibers;     // range in the fiber table
+  uint32_t instr_begin, ninstr;      // range of the bin's instructions in the instruction table
+  uint32_t rank;                     // all fibers of a workgroup belong to one rank
+  uint32_t pad[3];
+};
+
+struct DFiber {            // 32 bytes: one lane of one IR thread block
+  uint32_t fid;            // global thread-block index * W + lane
+  uint32_t instr_begin, ninstr;
+  int32_t send_conn, recv_conn;  // connection index or -1
+  uint32_t pad[3];
+};
+
 struct KParams {
-  const DTb* tbs;
-  const DInstr* instrs;
+  const DInstr* instrs;    // ordered by bin, then thread block, then step
   const DDep* deps;
-  const uint32_t* wg_begin;   // [grid + 1] range of each workgroup in wg_fibers (empty = idle workgroup)
-  const uint32_t* wg_fibers;  // fiber = global thread-block index * W + lane
+  const DWg* wgs;          // [W * wgs_per_lane], lane-major
+  const DFiber* fibers;
   void* const* bufs;       // [rank*3 + buffer] user buffers
   unsigned char* fifo;     // [(conn*W + lane) * slots + slot] * slot_bytes
   unsigned char* ll_fifo;  // the same for the LL protocol, slots of ll_slot_bytes (data + flag pairs only)

@@ -269,12 +269,18 @@ __device__ __forceinline__ void store_flag(uint64_t* p, uint64_t v) {
   __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-// First byte of lane w's share of a chunk of U 16-byte units split over W lanes.  Shares are cut at
-// 256-byte boundaries when every lane can get at least that much.
-__device__ __forceinline__ uint64_t lane_begin(uint64_t U, uint32_t w, uint32_t W) {
-  if (w >= W) return U << 4;
-  if (U >= 16ull * W) return (((U >> 4) * w) / W) << 8;
-  return ((U * w) / W) << 4;
+// First byte of lane w's share of a chunk of `chunk_bytes` split over W lanes (w = W gives the chunk's end).
+// Shares are cut at 256-byte boundaries when every lane can get at least that much, else at 16-byte
+// boundaries.  32-bit arithmetic: the host admits chunks below 2^40 bytes only, and
+// floor(n * w / W) = (n / W) * w + floor((n % W) * w / W).
+__device__ __forceinline__ uint64_t lane_begin(uint64_t chunk_bytes, uint32_t w, uint32_t W) {
+  if (w >= W) return chunk_bytes;
+  const uint64_t U = chunk_bytes >> 4;
+  if (U >= 16ull * W) {
+    const uint32_t n = (uint32_t)(U >> 4);
+    return ((uint64_t)(n / W) * w + ((n % W) * w) / W) << 8;
+  }
+  return (uint64_t)(((uint32_t)U * w) / W) << 4;
 }
 
 }  // namespace
@@ -300,14 +306,13 @@ __global__ void __launch_bounds__(512) gc3_interpreter(KParams p) {
   __shared__ uint32_t s_headv[2];
   __shared__ uint64_t f_off0[kMaxFibersPerWg], f_share[kMaxFibersPerWg];
   // per fiber: its thread block's record and the three buffer pointers of its rank, fetched once
-  __shared__ uint32_t f_rank[kMaxFibersPerWg], f_ibeg[kMaxFibersPerWg], f_ninstr[kMaxFibersPerWg], f_ilds[kMaxFibersPerWg];
+  __shared__ uint32_t f_ibeg[kMaxFibersPerWg], f_ninstr[kMaxFibersPerWg], f_ilds[kMaxFibersPerWg];
   __shared__ int32_t f_sconn[kMaxFibersPerWg], f_rconn[kMaxFibersPerWg];
-  __shared__ uint64_t f_buf[kMaxFibersPerWg][3];
+  __shared__ uint64_t s_buf[3];
   // the instruction lists of this workgroup's fibers, when they fit (else they are read from global memory
   // every time): an instruction is fetched once per tile, and a fetch is a dependent global access on the
   // critical path of every hop
   __shared__ uint32_t s_instr[kLdsInstrs * 8];
-  __shared__ uint32_t s_ilds_total;
   __shared__ int s_res[2];
 #if GC3_LDS_STAGE
   __shared__ __attribute__((aligned(16))) unsigned char s_stage[kStageBytes];
@@ -316,10 +321,9 @@ __global__ void __launch_bounds__(512) gc3_interpreter(KParams p) {
   // blockIdx = (sub * W_active + lane) * wgs_per_lane + bin: this workgroup takes entries sub, sub + nsplit, ...
   // of the fiber list the plan gives (lane, bin)
   const uint32_t slot = blockIdx.x / p.wgs_per_lane, bin = blockIdx.x % p.wgs_per_lane;
-  const uint32_t wg = (slot % p.W_active) * p.wgs_per_lane + bin, sub = slot / p.W_active, nsplit = p.nsplit;
-  const uint32_t fbeg = p.wg_begin[wg] + sub;
-  const uint32_t nlist = p.wg_begin[wg + 1] - p.wg_begin[wg];
-  const uint32_t nf = nlist > sub ? (nlist - sub + nsplit - 1) / nsplit : 0;
+  const uint32_t sub = slot / p.W_active, nsplit = p.nsplit;
+  const DWg hdr = p.wgs[(slot % p.W_active) * p.wgs_per_lane + bin];
+  const uint32_t nf = hdr.nfibers > sub ? (hdr.nfibers - sub + nsplit - 1) / nsplit : 0;
   if (nf == 0) return;
   if (p.hold) {
     // failure-path test facility: wait (bounded) for a start word that the host never sets
@@ -343,40 +347,30 @@ __global__ void __launch_bounds__(512) gc3_interpreter(KParams p) {
   }
   const uint32_t W = p.W;
   const uint32_t tile = p.tile_bytes;
+  // fiber records, the bin's instructions and the rank's buffer pointers: independent loads, one barrier
   if (tid < nf) {
-    const uint32_t fid = p.wg_fibers[fbeg + tid * nsplit];
-    const uint64_t U = p.chunk_bytes >> 4;
-    const uint64_t o = lane_begin(U, fid % W, p.W_active);
-    f_id[tid] = fid;
+    const DFiber f = p.fibers[hdr.fiber_begin + sub + tid * nsplit];
+    const uint32_t lane = f.fid % W;
+    const uint64_t o = lane_begin(p.chunk_bytes, lane, p.W_active);
+    f_id[tid] = f.fid;
     f_t[tid] = 0;
     f_s[tid] = 0;
     f_send[tid] = 0;
     f_recv[tid] = 0;
     f_head[tid] = 0;
     f_off0[tid] = o;
-    f_share[tid] = lane_begin(U, fid % W + 1, p.W_active) - o;
-    const DTb tb = p.tbs[fid / W];
-    f_rank[tid] = tb.rank;
-    f_ibeg[tid] = tb.instr_begin;
-    f_ninstr[tid] = tb.ninstr;
-    f_sconn[tid] = tb.send_conn;
-    f_rconn[tid] = tb.recv_conn;
-    for (int b = 0; b < 3; ++b) f_buf[tid][b] = (uint64_t)p.bufs[tb.rank * 3 + b];
+    f_share[tid] = lane_begin(p.chunk_bytes, lane + 1, p.W_active) - o;
+    f_ninstr[tid] = f.ninstr;
+    f_ibeg[tid] = f.instr_begin;
+    f_ilds[tid] = f.instr_begin - hdr.instr_begin;
+    f_sconn[tid] = f.send_conn;
+    f_rconn[tid] = f.recv_conn;
   }
-  __syncthreads();
-  if (tid == 0) {
-    uint32_t total = 0;
-    for (uint32_t i = 0; i < nf; ++i) { f_ilds[i] = total; total += f_ninstr[i]; }
-    s_ilds_total = total;
-  }
-  __syncthreads();
-  const bool instr_in_lds = s_ilds_total <= (uint32_t)kLdsInstrs;
+  if (tid >= 32 && tid < 35) s_buf[tid - 32] = (uint64_t)p.bufs[hdr.rank * 3 + (tid - 32)];
+  const bool instr_in_lds = hdr.ninstr <= (uint32_t)kLdsInstrs;
   if (instr_in_lds) {
-    const uint32_t* gi = (const uint32_t*)p.instrs;
-    for (uint32_t i = 0; i < nf; ++i) {
-      const uint32_t words = f_ninstr[i] * 8, from = f_ibeg[i] * 8, to = f_ilds[i] * 8;
-      for (uint32_t k = tid; k < words; k += nthreads) s_instr[to + k] = gi[from + k];
-    }
+    const uint32_t* gi = (const uint32_t*)(p.instrs + hdr.instr_begin);
+    for (uint32_t k = tid; k < hdr.ninstr * 8; k += nthreads) s_instr[k] = gi[k];
   }
   uint32_t live = nf, phase = 0;
   uint64_t last_progress = wall_clock64();
@@ -390,7 +384,7 @@ __global__ void __launch_bounds__(512) gc3_interpreter(KParams p) {
       const uint32_t fid = uni(f_id[fi]);
       const uint32_t tbi = fid / W, lane = fid % W;
       DTb tb;
-      tb.rank = uni(f_rank[fi]);
+      tb.rank = hdr.rank;
       tb.instr_begin = uni(f_ibeg[fi]);
       tb.ninstr = uni(f_ninstr[fi]);
       tb.send_conn = (int32_t)uni((uint32_t)f_sconn[fi]);
@@ -497,8 +491,8 @@ __global__ void __launch_bounds__(512) gc3_interpreter(KParams p) {
 
         // ---- move the tile --------------------------------------------------------------------
         const uint64_t coff = off0 + toff;   // byte offset inside each chunk
-        unsigned char* const srcb = ins.srcbuf < 3 ? (unsigned char*)uni64(f_buf[fi][ins.srcbuf]) + (uint64_t)ins.srcidx * p.chunk_bytes + coff : nullptr;
-        unsigned char* const dstb = ins.dstbuf < 3 ? (unsigned char*)uni64(f_buf[fi][ins.dstbuf]) + (uint64_t)ins.dstidx * p.chunk_bytes + coff : nullptr;
+        unsigned char* const srcb = ins.srcbuf < 3 ? (unsigned char*)uni64(s_buf[ins.srcbuf]) + (uint64_t)ins.srcidx * p.chunk_bytes + coff : nullptr;
+        unsigned char* const dstb = ins.dstbuf < 3 ? (unsigned char*)uni64(s_buf[ins.dstbuf]) + (uint64_t)ins.dstidx * p.chunk_bytes + coff : nullptr;
         unsigned char* const rslot = pops ? fifo_recv + (uint64_t)(recv_seq % p.slots) * slot_bytes : nullptr;
         unsigned char* const sslot = pushes ? fifo_send + (uint64_t)(send_seq % p.slots) * slot_bytes : nullptr;
         bool data_ok = true;

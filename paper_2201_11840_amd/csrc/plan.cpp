@@ -208,23 +208,45 @@ int make_plan(const gc3_program& prog, const gc3_comm_config& cfg, int cus, long
   // round-robin over the 8 dies (XCDs), so every prefix is spread evenly.  (Placing connected thread
   // blocks on one die was measured and makes no difference: FIFO payload and flags bypass the
   // per-die L2 by design, so nothing is shared through it.)
-  std::vector<std::vector<uint32_t>> wg_lists;   // per workgroup: its fibers
+  // The instruction table is reordered by bin (then thread block, then step), so that the instructions a
+  // workgroup needs are one contiguous range it can fetch without first reading its thread blocks' records.
+  {
+    std::vector<DInstr> ordered;
+    ordered.reserve(instrs.size());
+    for (auto& bin : bins)
+      for (int g : bin) {
+        const uint32_t from = tbs[g].instr_begin;
+        tbs[g].instr_begin = (uint32_t)ordered.size();
+        ordered.insert(ordered.end(), instrs.begin() + from, instrs.begin() + from + tbs[g].ninstr);
+      }
+    instrs.swap(ordered);
+  }
+  std::vector<DWg>& wgs = plan.wgs;
+  std::vector<DFiber>& fibers = plan.fibers;
+  wgs.clear();
+  fibers.clear();
+  int max_fibers = 0;
   for (int w = 0; w < W; ++w)
     for (size_t b = 0; b < bins.size(); ++b) {
-      wg_lists.emplace_back();
-      for (int g : bins[b]) wg_lists.back().push_back((uint32_t)(g * W + w));
+      DWg h{};
+      h.fiber_begin = (uint32_t)fibers.size();
+      h.nfibers = (uint32_t)bins[b].size();
+      h.instr_begin = bins[b].empty() ? 0u : tbs[bins[b].front()].instr_begin;
+      for (int g : bins[b]) {
+        DFiber f{};
+        f.fid = (uint32_t)(g * W + w);
+        f.instr_begin = tbs[g].instr_begin;
+        f.ninstr = tbs[g].ninstr;
+        f.send_conn = tbs[g].send_conn;
+        f.recv_conn = tbs[g].recv_conn;
+        fibers.push_back(f);
+        h.ninstr += tbs[g].ninstr;
+        h.rank = tbs[g].rank;
+      }
+      wgs.push_back(h);
+      max_fibers = std::max(max_fibers, (int)bins[b].size());
     }
-  std::vector<uint32_t>& wg_begin = plan.wg_begin;
-  std::vector<uint32_t>& wg_fibers = plan.wg_fibers;
-  wg_begin.assign(1, 0);
-  wg_fibers.clear();
-  int max_fibers = 0;
-  for (auto& l : wg_lists) {
-    wg_fibers.insert(wg_fibers.end(), l.begin(), l.end());
-    wg_begin.push_back((uint32_t)wg_fibers.size());
-    max_fibers = std::max(max_fibers, (int)l.size());
-  }
-  const long grid = (long)wg_lists.size();
+  const long grid = (long)wgs.size();
 
 
   // Largest tile (= what a FIFO slot holds per chunk): 64 KiB unless given; halved (not below 16 KiB)

@@ -14,8 +14,8 @@ struct Plan {
   std::vector<DTb> tbs;
   std::vector<DInstr> instrs;
   std::vector<DDep> deps;
-  std::vector<uint32_t> wg_begin;  // [grid + 1]
-  std::vector<uint32_t> wg_fibers;
+  std::vector<DWg> wgs;            // [grid], lane-major
+  std::vector<DFiber> fibers;
   int nconn = 0, ntb = 0, max_count = 1;
   int max_pushes = 0;              // most send-type instructions in one thread block (messages per tile)
   uint64_t algorithmic_chunks = 0;
