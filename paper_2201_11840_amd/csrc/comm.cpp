@@ -374,69 +374,86 @@ int gc3_comm_tune(const gc3_program* prog, const gc3_comm_config* base, size_t e
   HIP_TRY(hipEventCreate(&ev.b));
   hipStream_t st = (hipStream_t)hip_stream;
 
-  static const int widths[] = {0, 4, 8, 16, 32, 64};
-  static const int targets[] = {0, 512, 768};
-  std::vector<std::pair<int, int>> seen;   // (team width, grid) of plans already timed
+  std::vector<std::tuple<int, int, int>> seen;   // (team width, grid, slot tile) of plans already timed
   double best_ms = 0;
   bool have = false, first_only = false;   // first_only: the best so far is still the caller's configuration
   int last_err = GC3_OK;
   std::string last_msg;
+  int best_tile = 0;
+  // Times one configuration; returns GC3_OK also when the plan was skipped (does not fit, seen before).
+  auto try_config = [&](const gc3_comm_config& cfg) -> int {
+    gc3_comm* c = nullptr;
+    int rc = gc3_comm_create(prog, &cfg, &c);
+    if (rc != GC3_OK) { last_err = rc; last_msg = gc3_last_error(); return GC3_OK; }
+    struct CommGuard { gc3_comm* c; ~CommGuard() { gc3_comm_destroy(c); } } cg{c};
+    std::tuple<int, int, int> key(c->info.team_width, c->info.grid, c->info.tile_bytes);
+    if (std::find(seen.begin(), seen.end(), key) != seen.end()) return GC3_OK;
+    seen.push_back(key);
+    unsigned char* basep = (unsigned char*)block.p;
+    for (int r = 0; r < pi.ranks && rc == GC3_OK; ++r) {
+      void* in = basep + off[r * 3];
+      void* outp = pi.inplace ? in : (void*)(basep + off[r * 3 + 1]);
+      uint64_t sb = off[r * 3 + 3] - off[r * 3 + 2];
+      rc = gc3_comm_bind(c, r, in, outp, basep + off[r * 3 + 2], sb);
+    }
+    // the first plan timed also pays for cold code and freshly mapped stand-in buffers: warm it longer
+    const int warm = seen.size() == 1 ? 8 : 2, timed = 5;
+    for (int i = 0; i < warm && rc == GC3_OK; ++i) rc = gc3_comm_run(c, elems_per_rank, dtype, GC3_SUM, st);
+    if (rc == GC3_OK) {
+      HIP_TRY(hipEventRecord(ev.a, st));
+      for (int i = 0; i < timed && rc == GC3_OK; ++i) rc = gc3_comm_run(c, elems_per_rank, dtype, GC3_SUM, st);
+      HIP_TRY(hipEventRecord(ev.b, st));
+    }
+    if (rc == GC3_OK) rc = gc3_comm_status(c);   // synchronises
+    if (rc != GC3_OK) {
+      last_err = rc; last_msg = gc3_last_error();
+      if (rc == GC3_ERR_TIMEOUT || rc == GC3_ERR_HIP) { set_error("tuning run failed: " + last_msg); return rc; }
+      return GC3_OK;
+    }
+    float ms = 0;
+    HIP_TRY(hipEventElapsedTime(&ms, ev.a, ev.b));
+    const double per = (double)ms / timed;
+    // the caller's configuration is timed first and is replaced only by a plan that is faster by more than
+    // the run-to-run noise (2 %); after that every strictly faster plan wins
+    const bool better = !have || (first_only ? per < 0.98 * best_ms : per < best_ms);
+    if (report && report->count < GC3_TUNE_MAX_TRIED) {
+      auto& e = report->tried[report->count];
+      e.team_width = c->info.team_width; e.target_wgs = cfg.target_wgs; e.grid = c->info.grid;
+      e.active_wgs = c->info.active_wgs; e.tile_bytes = c->info.tile_bytes; e.ms = per;
+      if (better) report->best = report->count;
+      ++report->count;
+    }
+    if (better) {
+      first_only = !have;
+      have = true; best_ms = per;
+      *best = cfg;
+      best_tile = c->info.tile_bytes;
+    }
+    return GC3_OK;
+  };
+  // pass 1: team width x workgroup target, the caller's configuration as given first
+  static const int widths[] = {0, 4, 8, 16, 32, 64};
+  static const int targets[] = {0, 512, 768};
   for (int w : widths)
     for (int t : targets) {
       gc3_comm_config cfg = cfg0;
-      if (w == 0 && t == 0) { /* the caller's configuration as given comes first */ }
-      else {
+      if (w != 0 || t != 0) {
         if ((cfg0.team_width && w) || (cfg0.target_wgs && t)) continue;   // fixed by the caller
         if (w) cfg.team_width = w;
         if (t) cfg.target_wgs = t;
       }
-      gc3_comm* c = nullptr;
-      rc = gc3_comm_create(prog, &cfg, &c);
-      if (rc != GC3_OK) { last_err = rc; last_msg = gc3_last_error(); continue; }
-      struct CommGuard { gc3_comm* c; ~CommGuard() { gc3_comm_destroy(c); } } cg{c};
-      std::pair<int, int> key(c->info.team_width, c->info.grid);
-      if (std::find(seen.begin(), seen.end(), key) != seen.end()) continue;
-      seen.push_back(key);
-      unsigned char* basep = (unsigned char*)block.p;
-      for (int r = 0; r < pi.ranks && rc == GC3_OK; ++r) {
-        void* in = basep + off[r * 3];
-        void* outp = pi.inplace ? in : (void*)(basep + off[r * 3 + 1]);
-        uint64_t sb = off[r * 3 + 3] - off[r * 3 + 2];
-        rc = gc3_comm_bind(c, r, in, outp, basep + off[r * 3 + 2], sb);
-      }
-      // the first plan timed also pays for cold code and freshly mapped stand-in buffers: warm it longer
-      const int warm = seen.size() == 1 ? 8 : 2, timed = 5;
-      for (int i = 0; i < warm && rc == GC3_OK; ++i) rc = gc3_comm_run(c, elems_per_rank, dtype, GC3_SUM, st);
-      if (rc == GC3_OK) {
-        HIP_TRY(hipEventRecord(ev.a, st));
-        for (int i = 0; i < timed && rc == GC3_OK; ++i) rc = gc3_comm_run(c, elems_per_rank, dtype, GC3_SUM, st);
-        HIP_TRY(hipEventRecord(ev.b, st));
-      }
-      if (rc == GC3_OK) rc = gc3_comm_status(c);   // synchronises
-      if (rc != GC3_OK) {
-        last_err = rc; last_msg = gc3_last_error();
-        if (rc == GC3_ERR_TIMEOUT || rc == GC3_ERR_HIP) { set_error("tuning run failed: " + last_msg); return rc; }
-        continue;
-      }
-      float ms = 0;
-      HIP_TRY(hipEventElapsedTime(&ms, ev.a, ev.b));
-      double per = (double)ms / timed;
-      // the caller's configuration is timed first and is replaced only by a plan that is faster by more than
-      // the run-to-run noise (2 %); after that every strictly faster plan wins
-      const bool better = !have || (first_only ? per < 0.98 * best_ms : per < best_ms);
-      if (report && report->count < GC3_TUNE_MAX_TRIED) {
-        auto& e = report->tried[report->count];
-        e.team_width = c->info.team_width; e.target_wgs = cfg.target_wgs; e.grid = c->info.grid;
-        e.active_wgs = c->info.active_wgs; e.ms = per;
-        if (better) report->best = report->count;
-        ++report->count;
-      }
-      if (better) {
-        first_only = !have;
-        have = true; best_ms = per;
-        *best = cfg;
-      }
+      if ((rc = try_config(cfg)) != GC3_OK) return rc;
     }
+  // pass 2: the slot tile of the winner (it bounds the tile of a run and sets the FIFO footprint)
+  if (have && cfg0.tile_bytes == 0) {
+    const gc3_comm_config winner = *best;
+    for (int tile : {16384, 32768, 65536}) {
+      if (tile == best_tile) continue;
+      gc3_comm_config cfg = winner;
+      cfg.tile_bytes = tile;
+      if ((rc = try_config(cfg)) != GC3_OK) return rc;
+    }
+  }
   if (!have) {
     set_error("no configuration could be timed: " + last_msg);
     return last_err != GC3_OK ? last_err : GC3_ERR_ARG;
