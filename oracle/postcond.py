@@ -7,6 +7,10 @@ buffer, the input chunk or reduction chunk that must end there.
     AllToAll  (Section 7.3):  chunk i of rank j ends on rank i at index j.
     AllToNext (Section 7.4):  rank i's buffer ends on rank i+1; the last rank
         sends nothing, so rank 0's output is never written.
+    ReduceScatter / AllGather (the two halves of an AllReduce, Section 2):  with k
+        output (input) chunks per rank, output chunk j of rank r is the reduction of
+        chunk r*k + j of all ranks / output chunk q*k + j of every rank is chunk j
+        of rank q.
 Written as brute-force loops over ranks and chunks, independent of the interpreter.
 """
 from __future__ import annotations
@@ -34,6 +38,10 @@ def symbolic_expected(collective: str, ranks: int, in_chunks: int, out_chunks: i
                 row.append(Counter({(src, r * per + k): 1}))
             elif collective == "alltonext":
                 row.append(None if r == 0 else Counter({(r - 1, j): 1}))
+            elif collective == "reducescatter":
+                row.append(Counter({(q, r * out_chunks + j): 1 for q in range(ranks)}))
+            elif collective == "allgather":
+                row.append(Counter({(j // in_chunks, j % in_chunks): 1}))
             else:
                 raise ValueError(f"no postcondition known for {collective}")
         exp.append(row)
@@ -76,3 +84,17 @@ def alltonext_expected(inputs: Sequence[np.ndarray], outputs_before: Sequence[np
     for i in range(1, len(inputs)):
         outs.append(inputs[i - 1].copy())
     return outs
+
+
+def reducescatter_sum_f64(inputs: Sequence[np.ndarray], dtype: str) -> List[np.ndarray]:
+    """out[r] = the r-th of R equal parts of the element-wise sum over ranks (float64)."""
+    total = allreduce_sum_f64(inputs, dtype)
+    R = len(inputs)
+    part = total.size // R
+    return [total[r * part:(r + 1) * part].copy() for r in range(R)]
+
+
+def allgather_expected(inputs: Sequence[np.ndarray]) -> List[np.ndarray]:
+    """Every rank's output is the concatenation of all ranks' inputs in rank order."""
+    cat = np.concatenate(list(inputs))
+    return [cat.copy() for _ in inputs]

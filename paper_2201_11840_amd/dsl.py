@@ -122,6 +122,8 @@ class GC3Program:
                 elif self.collective == "allgather":
                     per = self.out_chunks // R
                     want = Counter({(j // per, j % per): 1})
+                elif self.collective == "reducescatter":
+                    want = Counter({(q, r * self.out_chunks + j): 1 for q in range(R)})
                 elif self.collective == "custom":
                     continue
                 else:

@@ -42,6 +42,28 @@ def ring_allreduce(R: int, instances: int = 1, **opts) -> Program:
     return compile_program(p, **opts)
 
 
+def ring_reduce_scatter(R: int, instances: int = 1, **opts) -> Program:
+    """Section 2's ReduceScatter helper as a collective: ring reduction inside the input buffer (which is
+    overwritten), then the owned chunk is copied to the output."""
+    with GC3Program(f"dsl_ring_reducescatter_r{R}_x{instances}", "reducescatter", R, R, 1) as p:
+        with parallelize(instances):
+            reduce_scatter(list(range(R)), 0, 1)
+            for r in range(R):
+                chunk(r, "input", r).copy(r, "output", 0)
+    return compile_program(p, **opts)
+
+
+def ring_allgather(R: int, instances: int = 1, **opts) -> Program:
+    """Section 2's AllGather helper as a collective: every rank's chunk goes once round the ring."""
+    with GC3Program(f"dsl_ring_allgather_r{R}_x{instances}", "allgather", R, 1, R) as p:
+        with parallelize(instances):
+            for q in range(R):
+                c = chunk(q, "input", 0).copy(q, "output", q)
+                for hop in range(1, R):
+                    c = c.copy((q + hop) % R, "output", q)
+    return compile_program(p, **opts)
+
+
 def hierarchical_allreduce(N: int, G: int, intra_parallel: bool = True, **opts) -> Program:
     """Sections 2 and 5.1: intra-group ReduceScatter on channel 0 (parallelized by N), cross-group
     ReduceScatter and AllGather on channel 1, intra-group AllGather on channel 2 (parallelized by N)."""

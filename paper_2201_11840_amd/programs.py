@@ -104,6 +104,47 @@ def ring_allreduce(R: int, instances: int = 1, fuse: bool = True, use_rrs: bool 
     return prog
 
 
+def ring_reduce_scatter(R: int, instances: int = 1, name: Optional[str] = None) -> Program:
+    """The ring ReduceScatter helper of Section 2 as a collective of its own, out of place: the input has
+    R*k chunks, the output k; output chunk j of rank r is the sum over all ranks of input chunk r*k + j.
+    The group with ring number q starts on rank q+1 and is summed on its way round to rank q.  The
+    intermediate hops use `rrs` (nothing is stored locally, Section 4.2) and the last hop an `rrc` into
+    the output, so the input buffers stay as they were."""
+    if R < 2:
+        raise ValueError("ring needs at least 2 ranks")
+    k = instances
+    prog = Program(name or f"ring_reducescatter_r{R}_x{k}", "reducescatter", R, R * k, k, inplace=False)
+    for j in range(k):
+        for r in range(R):
+            tb = prog.tb(r, send=(r + 1) % R, recv=(r - 1) % R, chan=j)
+            ref = lambda q: ("i", (q % R) * k + j)
+            tb.add("send", src=ref(r - 1))
+            for s in range(1, R - 1):
+                tb.add("rrs", src=ref(r - 1 - s))
+            tb.add("rrc", src=ref(r), dst=("o", j))
+    return prog
+
+
+def ring_allgather(R: int, instances: int = 1, name: Optional[str] = None) -> Program:
+    """The ring AllGather helper of Section 2 as a collective of its own, out of place: the input has k
+    chunks, the output R*k; output chunk q*k + j of every rank is input chunk j of rank q.  Every rank
+    copies its own chunks into place and passes each group on for R-1 hops."""
+    if R < 2:
+        raise ValueError("ring needs at least 2 ranks")
+    k = instances
+    prog = Program(name or f"ring_allgather_r{R}_x{k}", "allgather", R, k, R * k, inplace=False)
+    for j in range(k):
+        for r in range(R):
+            tb = prog.tb(r, send=(r + 1) % R, recv=(r - 1) % R, chan=j)
+            out = lambda q: ("o", (q % R) * k + j)
+            tb.add("send", src=("i", j))
+            tb.add("copy", src=("i", j), dst=out(r))
+            for s in range(1, R - 1):
+                tb.add("rcs", dst=out(r - s))
+            tb.add("recv", dst=out(r + 1))
+    return prog
+
+
 def multichannel_ring_allreduce(R: int, channels: int, name: Optional[str] = None) -> Program:
     """One logical ring spread over several channels (Section 7.1.1: "distributes a
     single logical ring across multiple channels by varying the channel of copy

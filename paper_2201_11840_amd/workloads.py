@@ -65,7 +65,8 @@ def all_workloads() -> List[Workload]:
 def next_row_workloads() -> List[Workload]:
     """Programs beyond the five benchmark configurations: the rrs fusion (Section 4.2), All Pairs
     AllReduce (Section 7.1.2), one logical ring spread over several channels in the paper's
-    32 KB - 3 MB regime (Section 7.1.1), and Two-Step AllToAll (Section 7.3)."""
+    32 KB - 3 MB regime (Section 7.1.1), Two-Step AllToAll (Section 7.3), and the ring ReduceScatter /
+    AllGather helpers of Section 2 as collectives of their own (64 MiB per rank on the wide side)."""
     return [
         Workload("ring_allreduce_rrs_r8_x8_f32_64MiB", lambda: programs.ring_allreduce(8, instances=8, use_rrs=True),
                  "f32", 64 * MiB, "uniform", 61840),
@@ -78,6 +79,10 @@ def next_row_workloads() -> List[Workload]:
                  "f32", 2 * MiB, "uniform", 63842),
         Workload("ring_allreduce_r8_f32_2MiB", lambda: programs.ring_allreduce(8), "f32", 2 * MiB, "uniform", 63843),
         Workload("twostep_alltoall_3x8_f16_48MiB", lambda: programs.twostep_alltoall(3, 8), "f16", 48 * MiB, "normal", 64840),
+        Workload("ring_reducescatter_r8_x8_f32_64MiB", lambda: programs.ring_reduce_scatter(8, instances=8),
+                 "f32", 64 * MiB, "uniform", 65840),
+        Workload("ring_allgather_r8_x8_f32_8MiB", lambda: programs.ring_allgather(8, instances=8),
+                 "f32", 8 * MiB, "uniform", 66840),
     ]
 
 

@@ -15,7 +15,8 @@ def compiled():
     out = []
     for R in (2, 3, 4, 8):
         out += [D.ring_allreduce(R), D.ring_allreduce(R, fuse=False), D.ring_allreduce(R, use_rrs=True),
-                D.allpairs_allreduce(R), D.allpairs_allreduce(R, via_scratch=True), D.direct_alltoall(R)]
+                D.allpairs_allreduce(R), D.allpairs_allreduce(R, via_scratch=True), D.direct_alltoall(R),
+                D.ring_reduce_scatter(R), D.ring_allgather(R, instances=2)]
     out += [D.ring_allreduce(8, instances=8), D.ring_allreduce(3, instances=2)]
     for N, G in ((2, 2), (2, 3), (3, 2), (2, 8)):
         out += [D.hierarchical_allreduce(N, G), D.hierarchical_allreduce(N, G, intra_parallel=False),

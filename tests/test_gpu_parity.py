@@ -37,7 +37,7 @@ def compare(got, want, dtype, exact_only=False):
 
 def run_case(prog, dtype, elems, dist="normal", seed=1234, cfg=None, repeats=1, exact_only=False):
     """Run `prog` on the GPU and in the oracle on the same seeded inputs; compare every output element
-    of every rank (and the inputs of out-of-place programs, which must be untouched).  With an explicit
+    of every rank (and the inputs of out-of-place programs, which most programs leave untouched).  With an explicit
     configuration both protocols (payload + flag, and LL) are exercised unless it fixes one."""
     H = _harness()
     text = prog.to_text()
@@ -65,8 +65,8 @@ def run_case(prog, dtype, elems, dist="normal", seed=1234, cfg=None, repeats=1, 
                     compare(got_out[r], (want_in if p.inplace else want_out)[r], dtype, exact_only)
                 if not p.inplace:
                     got_in = coll.download("in")
-                    for r in range(p.ranks):
-                        assert got_in[r].tobytes() == ins[r].tobytes()
+                    for r in range(p.ranks):               # untouched, or changed exactly as the oracle's were
+                        assert got_in[r].tobytes() == want_in[r].tobytes()
         finally:
             coll.close()
             if proto is not None:
@@ -102,6 +102,20 @@ def test_allreduce_variants(dtype):
     run_case(programs.allpairs_allreduce(4, via_scratch=True), dtype, 4 * 1000 * m, "normal", 5, small_cfg())
     run_case(programs.allpairs_allreduce(8, via_scratch=True), dtype, 8 * 1000 * m, "uniform", 6, small_cfg(team_width=2))
     run_case(programs.allpairs_allreduce(8, via_scratch=True), dtype, 8 * 65536 * m, "uniform", 7)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
+def test_reducescatter_and_allgather(dtype):
+    # the two ring helpers of Section 2 as collectives of their own (rrs chain ending in an rrc; copy + rcs chain)
+    m = 1 if dtype == "f32" else 2
+    for R, k in ((2, 1), (5, 2), (8, 8)):
+        run_case(programs.ring_reduce_scatter(R, instances=k), dtype, R * k * 500 * m, "normal", 31, small_cfg())
+        run_case(programs.ring_allgather(R, instances=k), dtype, k * 700 * m, "normal", 32, small_cfg(), exact_only=True)
+    run_case(programs.ring_reduce_scatter(8, instances=8), dtype, (4 << 20) // inputs.ITEMSIZE[dtype], "uniform", 33)
+    run_case(programs.ring_allgather(8, instances=8), dtype, (512 << 10) // inputs.ITEMSIZE[dtype], "uniform", 34, exact_only=True)
+    from paper_2201_11840_amd import dsl_programs as D
+    run_case(D.ring_reduce_scatter(4, instances=2), dtype, 8 * 600 * m, "normal", 35, small_cfg())
+    run_case(D.ring_allgather(5, instances=2), dtype, 2 * 600 * m, "normal", 36, small_cfg(), exact_only=True)
 
 
 @pytest.mark.parametrize("N,G", [(2, 2), (2, 3), (3, 2), (2, 8), (3, 8)])

@@ -36,7 +36,8 @@ def generated():
     out = [programs.ring_allreduce(R, instances=k, fuse=f) for R in (2, 3, 8) for k in (1, 3) for f in (True, False)]
     out += [programs.ring_allreduce(5, use_rrs=True), programs.multichannel_ring_allreduce(5, 2),
             programs.allpairs_allreduce(4), programs.allpairs_allreduce(5, via_scratch=True),
-            programs.direct_alltoall(1), programs.direct_alltoall(8)]
+            programs.direct_alltoall(1), programs.direct_alltoall(8),
+            programs.ring_reduce_scatter(8, instances=8), programs.ring_allgather(5, instances=2)]
     out += [programs.hierarchical_allreduce(N, G) for N, G in ((2, 2), (2, 3), (3, 2), (2, 8), (3, 8))]
     out += [programs.alltonext(N, G) for N, G in ((1, 1), (1, 4), (4, 1), (3, 8))]
     out += [programs.twostep_alltoall(N, G) for N, G in ((1, 4), (4, 1), (2, 3), (3, 8))]

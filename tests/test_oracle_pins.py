@@ -33,7 +33,9 @@ def all_programs():
         out += [programs.ring_allreduce(R), programs.ring_allreduce(R, fuse=False),
                 programs.ring_allreduce(R, use_rrs=True), programs.ring_allreduce(R, instances=3),
                 programs.multichannel_ring_allreduce(R, 2), programs.allpairs_allreduce(R),
-                programs.allpairs_allreduce(R, via_scratch=True), programs.direct_alltoall(R)]
+                programs.allpairs_allreduce(R, via_scratch=True), programs.direct_alltoall(R),
+                programs.ring_reduce_scatter(R), programs.ring_reduce_scatter(R, instances=2),
+                programs.ring_allgather(R), programs.ring_allgather(R, instances=3)]
     for N, G in GRIDS:
         out += [programs.hierarchical_allreduce(N, G), programs.hierarchical_allreduce(N, G, fuse=False),
                 programs.alltonext(N, G), programs.twostep_alltoall(N, G)]
@@ -217,6 +219,33 @@ def test_alltoall_bytewise(R, dtype):
         for r in range(R):
             assert outs[r].tobytes() == want[r].tobytes()
             assert ins[r].tobytes() == keep[r].tobytes()
+
+
+@pytest.mark.parametrize("R,k", [(2, 1), (4, 1), (5, 2), (8, 8)])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_reducescatter_and_allgather_against_their_definitions(R, k, dtype):
+    # ReduceScatter on integer-valued data: exactly the r-th part of the plain sum; inputs left untouched
+    elems = R * k * 24
+    ins = inputs.make_inputs(R, elems, dtype, "int8", 77)
+    keep = [a.copy() for a in ins]
+    outs = inputs.sentinel_outputs(R, elems // R, dtype)
+    oracle.run_program(parse(programs.ring_reduce_scatter(R, instances=k)), ins, outs, dtype, slots=2)
+    want = postcond.reducescatter_sum_f64(keep, dtype)
+    for r in range(R):
+        assert np.array_equal(numeric.to_float64(outs[r], dtype), want[r])
+        assert ins[r].tobytes() == keep[r].tobytes()
+    # the two halves compose to an AllReduce: gathering the scattered sums gives the sum everywhere
+    gathered = inputs.sentinel_outputs(R, elems, dtype)
+    oracle.run_program(parse(programs.ring_allgather(R, instances=k)), outs, gathered, dtype, slots=2)
+    total = postcond.allreduce_sum_f64(keep, dtype)
+    for r in range(R):
+        assert np.array_equal(numeric.to_float64(gathered[r], dtype), total)
+    # AllGather of arbitrary bit patterns is bytewise the concatenation
+    ins = inputs.make_inputs(R, k * 40, dtype, "normal", 78)
+    outs = inputs.sentinel_outputs(R, R * k * 40, dtype)
+    oracle.run_program(parse(programs.ring_allgather(R, instances=k)), ins, outs, dtype, slots=2)
+    for got, w in zip(outs, postcond.allgather_expected(ins)):
+        assert got.tobytes() == w.tobytes()
 
 
 @pytest.mark.parametrize("N,G", [(1, 1), (1, 4), (4, 1), (2, 2), (3, 8)])
