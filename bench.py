@@ -110,7 +110,7 @@ def report(w, coll, mean_ms, min_ms, wall_ms, prog=None, launches_before_timed=0
     rep = coll.tune_report
     if rep is not None:
         extra["tuned"] = {"team_width": coll.cfg.team_width, "target_wgs": coll.cfg.target_wgs,
-                          "tile_bytes": coll.cfg.tile_bytes,
+                          "tile_bytes": coll.cfg.tile_bytes, "wg_size": coll.cfg.wg_size,
                           "plans_timed": rep.count,
                           "untuned_plan_ms_in_tuner": round(rep.tried[0].ms, 5),
                           "chosen_plan_ms_in_tuner": round(rep.tried[rep.best].ms, 5)}

@@ -179,7 +179,7 @@ typedef struct gc3_tune_entry {
   int32_t grid;            /* workgroups of the plan */
   int32_t active_wgs;      /* of them, workgroups that hold work */
   int32_t tile_bytes;      /* slot tile of the plan */
-  int32_t reserved;
+  int32_t wg_size;         /* threads per workgroup */
   double ms;               /* mean duration of one run */
 } gc3_tune_entry;
 typedef struct gc3_tune_report {
@@ -192,7 +192,7 @@ typedef struct gc3_tune_report {
  * parallelization of every algorithm is tuned for the system and the buffer size; this does it for the
  * parallelization the runtime applies).  For the configuration in `base` (may be null) and for team
  * widths 4..64 x workgroup targets {default, 512, 768}, then for the fastest of them the slot tiles 16, 32
- * and 64 KiB - only over fields `base` leaves 0 - it creates
+ * and 64 KiB, then workgroups of 128 threads - only over fields `base` leaves 0 - it creates
  * a communicator on the current device, binds stand-in buffers of the real sizes (non-zero filler) that it
  * allocates and frees itself, times 5 runs after 2 warm-up runs (8 for the first plan) on `hip_stream`, and writes the
  * chosen configuration to `*best` (ready for gc3_comm_create): the fastest one if it beats `base`,

@@ -72,7 +72,7 @@ GC3_TUNE_MAX_TRIED = 24
 
 class TuneEntry(C.Structure):
     _fields_ = [("team_width", C.c_int32), ("target_wgs", C.c_int32), ("grid", C.c_int32),
-                ("active_wgs", C.c_int32), ("tile_bytes", C.c_int32), ("reserved", C.c_int32), ("ms", C.c_double)]
+                ("active_wgs", C.c_int32), ("tile_bytes", C.c_int32), ("wg_size", C.c_int32), ("ms", C.c_double)]
 
 
 class TuneReport(C.Structure):

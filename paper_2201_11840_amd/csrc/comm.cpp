@@ -419,7 +419,7 @@ int gc3_comm_tune(const gc3_program* prog, const gc3_comm_config* base, size_t e
     if (report && report->count < GC3_TUNE_MAX_TRIED) {
       auto& e = report->tried[report->count];
       e.team_width = c->info.team_width; e.target_wgs = cfg.target_wgs; e.grid = c->info.grid;
-      e.active_wgs = c->info.active_wgs; e.tile_bytes = c->info.tile_bytes; e.ms = per;
+      e.active_wgs = c->info.active_wgs; e.tile_bytes = c->info.tile_bytes; e.wg_size = c->info.wg_size; e.ms = per;
       if (better) report->best = report->count;
       ++report->count;
     }
@@ -453,6 +453,14 @@ int gc3_comm_tune(const gc3_program* prog, const gc3_comm_config* base, size_t e
       cfg.tile_bytes = tile;
       if ((rc = try_config(cfg)) != GC3_OK) return rc;
     }
+  }
+  // pass 3: smaller workgroups (less to synchronise per instruction; pays on latency-bound sizes)
+  if (have && cfg0.wg_size == 0) {
+    gc3_comm_config cfg = *best;
+    cfg.wg_size = 128;
+    seen.clear();        // a plan of another workgroup size is a different plan even if W, grid and tile agree
+    seen.emplace_back(-1, -1, -1);   // (keeps the longer warm-up for the very first plan only)
+    if ((rc = try_config(cfg)) != GC3_OK) return rc;
   }
   if (!have) {
     set_error("no configuration could be timed: " + last_msg);

@@ -377,9 +377,10 @@ def test_tune_measures_plans_and_the_chosen_one_is_correct():
             assert fastest >= 0.98 * tried[0].ms
         else:
             assert tried[rep.best].ms == fastest < 0.98 * tried[0].ms
-        assert len({(t.team_width, t.grid, t.tile_bytes) for t in tried}) == rep.count       # no plan timed twice
-        assert (coll.info.team_width, coll.info.grid, coll.info.tile_bytes) == \
-            (tried[rep.best].team_width, tried[rep.best].grid, tried[rep.best].tile_bytes)
+        assert len({(t.team_width, t.grid, t.tile_bytes, t.wg_size) for t in tried}) == rep.count   # no plan timed twice
+        b = tried[rep.best]
+        assert (coll.info.team_width, coll.info.grid, coll.info.tile_bytes, coll.info.wg_size) == \
+            (b.team_width, b.grid, b.tile_bytes, b.wg_size)
         coll.upload(ins, outs)
         coll.run()
         coll.status()
