@@ -1,14 +1,16 @@
 // The GC3-IR interpreter kernel for gfx950 (Section 6.2 of the paper, figure "GC3 interpreter").
 //
-// One workgroup executes one lane of one IR thread block: it walks that thread block's
-// instruction list once per tile (outer loop = chunk tiling, inner loop = instructions), waits
-// for the instruction's cross-thread-block dependencies and FIFO slots, moves one tile of each of
-// the instruction's chunks with 128-bit accesses, then publishes FIFO flags and its semaphore.
+// A workgroup executes one or a few FIBERS.  A fiber is one lane of one IR thread block: it walks
+// that thread block's instruction list once per tile (outer loop = chunk tiling, inner loop =
+// instructions), waits for the instruction's cross-thread-block dependencies and FIFO slots, moves
+// one tile of each of the instruction's chunks with 128-bit accesses, then publishes FIFO flags and
+// its semaphore.  Lightly loaded thread blocks of one rank share a workgroup, which visits its
+// fibers round-robin (see the comment at the kernel).
 //
-// A thread block is run by a team of W workgroups; lane w owns the w-th 1/W of every chunk and
-// has FIFO slots, flags and a semaphore of its own, so lanes never synchronise with each other.
-// All instructions are element-wise, hence this is Section 5.1's parallelize(W) applied by the
-// runtime: values and reduction order are those of the program.
+// A thread block is split into W lanes; lane w owns the w-th 1/W of every chunk and has FIFO slots,
+// flags and a semaphore of its own, so lanes never synchronise with each other.  All instructions
+// are element-wise, hence this is Section 5.1's parallelize(W) applied by the runtime: values and
+// reduction order are those of the program.
 //
 // Flag protocol (Section 6.1, remote buffers with s slots).  All flags are 64-bit and only grow:
 // value = run_base + n, where run_base = run number << 32.
@@ -31,8 +33,6 @@
 namespace gc3 {
 
 namespace {
-
-
 
 typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
