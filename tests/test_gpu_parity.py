@@ -191,6 +191,16 @@ def test_random_launch_configurations(seed):
     run_case(prog, dtype, prog.in_chunks * chunk_elems, "normal", 700 + seed, cfg, repeats=2, exact_only=exact)
 
 
+def test_many_ranks_and_thread_blocks():
+    # up to 64 virtual ranks and 1106 thread blocks, default plans (workgroups multiplex up to 16 thread blocks)
+    for prog, dt in [(programs.hierarchical_allreduce(4, 8), "bf16"), (programs.hierarchical_allreduce(8, 4), "f32"),
+                     (programs.twostep_alltoall(4, 8), "f16"), (programs.alltonext(8, 8), "f16"),
+                     (programs.ring_allreduce(32, instances=2), "f32"), (programs.allpairs_allreduce(16), "f32"),
+                     (programs.allpairs_allreduce(16, via_scratch=True), "bf16"), (programs.direct_alltoall(32), "f16")]:
+        exact = prog.collective in ("alltoall", "alltonext")
+        run_case(prog, dt, prog.in_chunks * 4096 // inputs.ITEMSIZE[dt], "normal", 5, None, exact_only=exact)
+
+
 # ---- edge cases ------------------------------------------------------------------------------------
 
 def test_instruction_lists_longer_than_the_workgroup_cache():
