@@ -463,11 +463,16 @@ def test_headline_under_every_plan_the_tuner_may_choose():
     want = [gather(a) for a in ins]
     oracle.run_program(p, want, None, w.dtype, slots=2)
     seen = set()
-    for W in (0, 4, 8, 16, 32, 64):
-        for tgt in (0, 512, 768):
-            coll = H.Collective(text, w.dtype, w.elems_per_rank, H.make_config(team_width=W, target_wgs=tgt))
+    candidates = [dict(team_width=W, target_wgs=tgt) for W in (0, 4, 8, 16, 32, 64) for tgt in (0, 512, 768)]
+    # the tuner's later passes: slot tile and workgroup size of the winner
+    candidates += [dict(tile_bytes=16384), dict(tile_bytes=32768), dict(wg_size=128),
+                   dict(target_wgs=512, tile_bytes=32768), dict(target_wgs=512, wg_size=128),
+                   dict(team_width=32, tile_bytes=16384, wg_size=128)]
+    for kw in candidates:
+        if True:
+            coll = H.Collective(text, w.dtype, w.elems_per_rank, H.make_config(**kw))
             try:
-                key = (coll.info.team_width, coll.info.grid)
+                key = (coll.info.team_width, coll.info.grid, coll.info.tile_bytes, coll.info.wg_size)
                 if key in seen:
                     continue
                 seen.add(key)
@@ -478,9 +483,9 @@ def test_headline_under_every_plan_the_tuner_may_choose():
             finally:
                 coll.close()
             for r in range(p.ranks):
-                assert gather(got[r]).tobytes() == want[r].tobytes(), f"plan W={key[0]} grid={key[1]} rank {r}"
+                assert gather(got[r]).tobytes() == want[r].tobytes(), f"plan {key} rank {r}"
                 assert got[r].tobytes() == got[0].tobytes()
-    assert len(seen) >= 8
+    assert len(seen) >= 14
 
 
 def test_config1_ring_allreduce_r4():
