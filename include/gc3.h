@@ -88,7 +88,8 @@ typedef struct gc3_comm_config {
                               Section 5.1's parallelize(W)).  Lightly loaded thread blocks of one
                               rank may share a workgroup.  0 = choose W and the sharing so that the
                               heaviest workgroup is lightest */
-  int32_t wg_size;         /* threads per workgroup: 64, 128, 256 or 512; default 256 */
+  int32_t wg_size;         /* threads per workgroup: 64, 128, 256 or 512; default 256 (a run whose lanes get
+                              at most 8 KiB of a chunk launches 128 of them) */
   int32_t reserved0;       /* must be 0 */
   int32_t target_wgs;      /* workgroups the schedule aims at (never more than can be resident);
                               0 = four per compute unit */
