@@ -35,7 +35,7 @@ HEADLINE = "ring_allreduce_r8_x8_f32_64MiB"
 # HBM-side traffic per launch (bytes): rocprofv3 --pmc FETCH_SIZE and --pmc WRITE_SIZE (two runs), each
 # scaled by the same counter's reading for this script's own 64 MiB restore copy (factors 1.9989 and
 # 1.0000); the traffic does not depend on the plan.  Workloads not listed were not measured (null).
-MEASURED_TRAFFIC = {"ring_allreduce_r8_x8_f32_64MiB": 3365010773, "hier_allreduce_2x8_bf16_64MiB": 7473969376,
+MEASURED_TRAFFIC = {"ring_allreduce_r8_x8_f32_64MiB": 3365023295, "hier_allreduce_2x8_bf16_64MiB": 7473969376,
                     "alltonext_3x8_f16_32MiB": 3443780562}
 
 
