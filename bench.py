@@ -278,7 +278,8 @@ def main() -> int:
 
     gbs = alg_bytes / (mean_ms * 1e-3) / 1e9
     out = {
-        "metric": "aggregate HBM GB/s (algorithmic bytes / kernel time) executing AllReduce/AllToAll GC3-IR",
+        "metric": "aggregate HBM GB/s (and % of peak) executing AllReduce/AllToAll GC3-IR",
+        "metric_definition": "algorithmic bytes of one run / mean kernel time; % of peak in frac_of_hbm_peak and roofline.frac",
         "value": round(gbs, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(mean_ms, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": {"f32": "f32", "f16": "f16", "bf16": "bf16"}[table[args.workload].dtype], "data": "synthetic",
