@@ -46,6 +46,23 @@ def build(verbose: bool = False, defines: Sequence[str] = (), out: Optional[str]
     return out
 
 
+EXAMPLE_SRC = os.path.join(HERE, "examples", "allreduce_c_abi.cpp")
+EXAMPLE_BIN = os.path.join(LIB_DIR, "allreduce_c_abi")
+
+
+def build_example(verbose: bool = False) -> str:
+    """Compile the stand-alone C++ example against the header and link it with the built library."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    cmd = [hipcc, "--offload-arch=gfx950", "-O2", "-std=c++17", "-Wall", "-Wno-unused-command-line-argument",
+           "-I", os.path.join(ROOT, "include"), EXAMPLE_SRC, "-L", LIB_DIR, "-lgc3", "-Wl,-rpath,$ORIGIN", "-o", EXAMPLE_BIN]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    if res.returncode != 0:
+        raise RuntimeError("hipcc failed on the example:\n" + res.stdout + res.stderr)
+    return EXAMPLE_BIN
+
+
 def kernel_resource_usage(remarks: str) -> List[Dict]:
     """The compiler's per-kernel resource report (register counts, scratch, LDS, occupancy) from its
     -Rpass-analysis=kernel-resource-usage remarks."""
@@ -67,3 +84,4 @@ def kernel_resource_usage(remarks: str) -> List[Dict]:
 
 if __name__ == "__main__":
     print(build(verbose=True))
+    print(build_example(verbose=True))

@@ -665,3 +665,21 @@ def test_selector_picks_the_program_by_size():
         B.gc3_selector_destroy(bounded)
     finally:
         sel.close()
+
+
+def test_c_abi_from_a_stand_alone_program(tmp_path):
+    """The library used without Python: a C++ program loads IR written by the compiler's command line, tunes,
+    binds hipMalloc'ed buffers, runs and checks an AllReduce of integer-valued data."""
+    import os
+    import subprocess
+    from paper_2201_11840_amd import build, gc3c
+    if not os.path.exists(build.EXAMPLE_BIN):
+        pytest.fail("the example binary is missing: run the build first")
+    for argv, elems in ((["ring_allreduce", "--ranks", "8", "--instances", "2"], 16 * 65536),
+                        (["hierarchical_allreduce", "--nodes", "2", "--gpus", "4", "--hand"], 8 * 4096),
+                        (["allpairs_allreduce", "--ranks", "4"], 4 * 1000)):
+        ir = tmp_path / "prog.gc3ir"
+        assert gc3c.main(argv + ["-o", str(ir)]) == 0
+        res = subprocess.run([build.EXAMPLE_BIN, str(ir), str(elems)], capture_output=True, text=True, timeout=120)
+        assert res.returncode == 0, res.stdout + res.stderr
+        assert ": OK (0 wrong)" in res.stdout

@@ -275,3 +275,27 @@ def test_kernel_resources_of_the_built_library():
         assert k["scratch_bytes"] == 0, k
         assert k["occupancy"] >= 6, k
         assert k["vgprs"] <= 80 and k["lds_bytes"] <= 16384, k
+
+
+def test_compiler_command_line_writes_loadable_programs(tmp_path):
+    from paper_2201_11840_amd import gc3c
+    for argv in (["ring_allreduce", "--ranks", "4", "--instances", "2"], ["ring_allreduce", "--ranks", "4", "--hand"],
+                 ["allpairs_allreduce", "--ranks", "5"], ["hierarchical_allreduce", "--nodes", "2", "--gpus", "3"],
+                 ["direct_alltoall", "--ranks", "3", "--hand"], ["twostep_alltoall", "--nodes", "2", "--gpus", "2"],
+                 ["alltonext", "--nodes", "2", "--gpus", "3"], ["ring_reduce_scatter", "--ranks", "4"],
+                 ["ring_allgather", "--ranks", "3", "--instances", "2", "--hand"]):
+        out = tmp_path / "p.gc3ir"
+        assert gc3c.main(argv + ["-o", str(out)]) == 0
+        prog = B.gc3_program_load(out.read_text())
+        B.gc3_program_validate(prog, 2)
+        B.gc3_program_free(prog)
+
+
+def test_c_abi_example_is_built_and_rejects_bad_usage():
+    # the stand-alone C++ program is compiled against include/gc3.h and linked with the library by build()
+    import subprocess
+    from paper_2201_11840_amd import build
+    if not os.path.exists(build.EXAMPLE_BIN):
+        pytest.skip("example was not built")
+    res = subprocess.run([build.EXAMPLE_BIN], capture_output=True, text=True)
+    assert res.returncode == 1 and "usage" in res.stderr
