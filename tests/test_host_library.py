@@ -299,3 +299,14 @@ def test_c_abi_example_is_built_and_rejects_bad_usage():
         pytest.skip("example was not built")
     res = subprocess.run([build.EXAMPLE_BIN], capture_output=True, text=True)
     assert res.returncode == 1 and "usage" in res.stderr
+
+
+def test_header_is_plain_c(tmp_path):
+    # the boundary is a C ABI: the header has to compile as C99 with nothing but the standard headers
+    import subprocess
+    src = tmp_path / "use_header.c"
+    src.write_text('#include "gc3.h"\nint main(void) { gc3_comm_config c = {0}; gc3_tune_report r; (void)r; return c.fifo_slots + (int)sizeof(gc3_comm_info) * 0; }\n')
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    res = subprocess.run(["gcc", "-std=c99", "-pedantic", "-Wall", "-Werror", "-fsyntax-only", "-I", os.path.join(root, "include"), str(src)],
+                         capture_output=True, text=True)
+    assert res.returncode == 0, res.stderr
