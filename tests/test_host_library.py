@@ -310,3 +310,27 @@ def test_header_is_plain_c(tmp_path):
     res = subprocess.run(["gcc", "-std=c99", "-pedantic", "-Wall", "-Werror", "-fsyntax-only", "-I", os.path.join(root, "include"), str(src)],
                          capture_output=True, text=True)
     assert res.returncode == 0, res.stderr
+
+
+def test_loader_validator_and_planner_survive_mutated_programs(tmp_path):
+    """The host part of the library (no device code) built with AddressSanitizer and UBSan and fed 20000 randomly
+    damaged programs: every outcome is fine except a crash or a sanitizer report."""
+    import subprocess
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    csrc = os.path.join(root, "paper_2201_11840_amd", "csrc")
+    exe = tmp_path / "fuzz_host"
+    cmd = ["g++", "-std=c++17", "-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=all",
+           "-I", os.path.join(root, "include"), "-I", csrc, os.path.join(root, "tests", "fuzz_host.cpp"),
+           os.path.join(csrc, "program.cpp"), os.path.join(csrc, "plan.cpp"), "-o", str(exe)]
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    assert res.returncode == 0, res.stderr
+    files = []
+    for i, prog in enumerate([programs.ring_allreduce(4, instances=2), programs.hierarchical_allreduce(2, 3),
+                              programs.allpairs_allreduce(4, via_scratch=True), programs.twostep_alltoall(2, 2),
+                              programs.alltonext(2, 3)]):
+        f = tmp_path / f"seed{i}.gc3ir"
+        f.write_text(prog.to_text())
+        files.append(str(f))
+    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=1:abort_on_error=0", LD_PRELOAD="")
+    res = subprocess.run([str(exe), "20000"] + files, capture_output=True, text=True, env=env, timeout=600)
+    assert res.returncode == 0, res.stdout + res.stderr[-4000:]
