@@ -94,24 +94,29 @@ def compile_program(prog: GC3Program, fuse: bool = True, use_rrs: bool = False) 
         nodes.append(nd)
         return nd
 
-    def edge(nd: Node, pred: int, kind: str) -> None:
+    # processing edges per location: (producer, consumer) -> location -> kinds.  An instruction with count > 1
+    # covers several chunks, and a later instruction may touch only some of them.
+    edge_locs: Dict[Tuple[int, int], Dict[Tuple[int, str, int], Set[str]]] = {}
+
+    def edge(nd: Node, pred: int, kind: str, loc: Tuple[int, str, int]) -> None:
         if pred != nd.id:
             nd.preds.setdefault(pred, set()).add(kind)
+            edge_locs.setdefault((pred, nd.id), {}).setdefault(loc, set()).add(kind)
 
     def reads(nd: Node, rank, buf, idx, cnt) -> None:
         for k in range(cnt):
             loc = (rank, buf, idx + k)
             if loc in last_writer:
-                edge(nd, last_writer[loc], "raw")
+                edge(nd, last_writer[loc], "raw", loc)
             readers.setdefault(loc, set()).add(nd.id)
 
     def writes(nd: Node, rank, buf, idx, cnt) -> None:
         for k in range(cnt):
             loc = (rank, buf, idx + k)
             if loc in last_writer:
-                edge(nd, last_writer[loc], "waw")
+                edge(nd, last_writer[loc], "waw", loc)
             for rd in readers.get(loc, ()):
-                edge(nd, rd, "war")
+                edge(nd, rd, "war", loc)
             last_writer[loc] = nd.id
             readers[loc] = set()
 
@@ -182,14 +187,26 @@ def compile_program(prog: GC3Program, fuse: bool = True, use_rrs: bool = False) 
                     if x.id != r_node.id:
                         x.preds.setdefault(r_node.id, set()).update(kinds)
         if use_rrs:
-            users: Dict[int, Set[str]] = {}
-            for x in nodes:
-                if x.alive:
-                    for p, kinds in x.preds.items():
-                        users.setdefault(p, set()).update(kinds)
+            # The local store of an rrcs may be dropped when, for EVERY chunk it covers, the reduced value is
+            # overwritten later and not read before that.  Decided per location: with count > 1 a later write
+            # may cover only part of the range, and the rest must keep the reduced value.
+            consumers: Dict[int, List[int]] = {}
+            for (producer, consumer) in edge_locs:
+                consumers.setdefault(producer, []).append(consumer)
             for n in nodes:
-                # the reduced value is never read locally and is overwritten later: no local store needed
-                if n.alive and n.opcode == "rrcs" and "raw" not in users.get(n.id, set()) and "waw" in users.get(n.id, set()):
+                if not (n.alive and n.opcode == "rrcs"):
+                    continue
+                droppable = True
+                for k in range(n.count):
+                    loc = (n.rank, n.dst[0], n.dst[1] + k)
+                    kinds: Set[str] = set()
+                    for x in consumers.get(n.id, ()):
+                        if nodes[x].alive:
+                            kinds |= edge_locs[(n.id, x)].get(loc, set())
+                    if "raw" in kinds or "waw" not in kinds:
+                        droppable = False
+                        break
+                if droppable:
                     n.opcode, n.dst = "rrs", None
 
     alive = [n for n in nodes if n.alive]

@@ -184,3 +184,33 @@ def test_random_programs_keep_the_traced_semantics(seed):
                 for j, want in enumerate(p.content[r]["s"]):
                     if want is not None and "use_rrs" not in opts:
                         assert bufs[r]["s"][j] == want, (seed, opts, r, j)
+
+
+def test_rrs_rewrite_is_decided_per_chunk_of_an_aggregated_instruction():
+    # A count = 2 reduction travels 0 -> 1 -> 2; afterwards only the FIRST of rank 1's two chunks is overwritten.
+    # The fused instruction on rank 1 must keep its local store (rrcs): dropping it (rrs) would leave the second
+    # chunk with its pre-reduction content (Section 4.2 fusion applied to Section 5.1 aggregated instructions).
+    with GC3Program("partial_overwrite", "custom", 3, 2, 2, inplace=True) as p:
+        c = chunk(1, "input", 0, 2).reduce(chunk(0, "input", 0, 2))
+        chunk(2, "input", 0, 2).reduce(c)
+        chunk(0, "input", 1, 1).copy(1, "input", 0)
+    for opts in (dict(use_rrs=True), dict()):
+        ir = compile_program(p, **opts)
+        assert not any(o.opcode == "rrs" for r in ir.tbs for t in r for o in t.ops)
+        op = oracle.parse_program(ir.to_text())
+        for seed in range(3):
+            bufs, _ = oracle.run_symbolic(op, slots=8, order="random", seed=seed)
+            for r in range(3):
+                assert bufs[r]["i"] == p.content[r]["i"], (opts, r)
+    # the whole range overwritten later and never read in between: the store is dropped
+    with GC3Program("full_overwrite", "custom", 3, 2, 2, inplace=True) as p:
+        c = chunk(1, "input", 0, 2).reduce(chunk(0, "input", 0, 2))
+        chunk(2, "input", 0, 2).reduce(c)
+        chunk(0, "input", 1, 1).copy(1, "input", 0)
+        chunk(0, "input", 0, 1).copy(1, "input", 1)
+    ir = compile_program(p, use_rrs=True)
+    assert sum(o.opcode == "rrs" for r in ir.tbs for t in r for o in t.ops) == 1
+    op = oracle.parse_program(ir.to_text())
+    bufs, _ = oracle.run_symbolic(op, slots=8, order="random", seed=0)
+    for r in range(3):
+        assert bufs[r]["i"] == p.content[r]["i"]
