@@ -1,7 +1,7 @@
 """Element-wise reduction of the oracle: the sum, in the buffer's own data type.
 
-The paper's reduction is "a point-wise reduction (e.g. addition)" (Section 3.1)
-applied by `reduce`, `rrc`, `rrcs`, `rrs` (Section 4.2).  It names no precision;
+The paper's reduction is element-wise and addition is the one operator it names (Section 3.1);
+`reduce`, `rrc`, `rrcs` and `rrs` apply it (Section 4.2).  It names no precision;
 the reading taken here is one correctly rounded add per hop in the buffer's
 type: IEEE binary32 add for f32; for the 16-bit types both operands are widened
 to binary32 (exact), added there, and rounded to nearest-even back to 16 bits,
