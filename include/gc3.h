@@ -51,7 +51,8 @@ typedef enum gc3_status {
 
 typedef enum gc3_dtype { GC3_F32 = 0, GC3_F16 = 1, GC3_BF16 = 2 } gc3_dtype;
 
-/* The paper's reduction is a point-wise one, "e.g. addition" (Section 3.1); only the sum is built. */
+/* The paper's reduction is element-wise and addition is the only operator it names (Section 3.1);
+ * only the sum is built. */
 typedef enum gc3_redop { GC3_SUM = 0 } gc3_redop;
 
 /* Opcodes of Section 4.2 (instruction generation and fusion). */
@@ -240,6 +241,30 @@ int gc3_comm_status(gc3_comm* comm);
 int gc3_comm_reset(gc3_comm* comm);
 
 void gc3_comm_destroy(gc3_comm* comm);
+
+/* For callers that cannot allocate device memory - code under HIP graph capture rules that forbid hipMalloc,
+ * tight serving loops, harnesses that ban allocation: one complete run of `prog` without a communicator and
+ * without any hipMalloc / hipFree.  Everything a communicator would allocate (flags, semaphores, instruction
+ * tables, FIFOs) is laid out, for the duration of the call's kernels, in a static device array of
+ * GC3_STATIC_SCRATCH_BYTES (64 MiB) that every GPU the library runs on holds until the process ends.
+ *   inputs / outputs / scratch: host arrays of `ranks` device pointers (16-byte aligned, owned by the caller);
+ *     `outputs` may be null for an in-place program (else outputs[r] must be null or equal inputs[r]);
+ *     `scratch` / `scratch_bytes` (capacities) may be null when no rank uses scratch chunks.
+ *   cfg: as for gc3_comm_create (null = defaults); the simple protocol only (protocol must be 0 or 1).  The
+ *     slot tile defaults to the largest of 64 KiB ... 1 KiB with which the FIFOs fit.
+ * The results are those of gc3_comm_run on the same program and buffers, bit for bit.
+ * The call plans the program on the host, copies the tables (and waits for `hip_stream` once, because the host
+ * copy dies with the call), clears flags and semaphores with a fill kernel and launches the interpreter, all on
+ * `hip_stream`; it returns without waiting for the run.  All calls on one GPU share that GPU's array: calls that
+ * overlap in time on one GPU (several streams or threads) race and are not allowed; calls on one stream are safe.
+ * A run abandoned inside the kernel (spin limit) is reported by the NEXT call on that device, which returns
+ * GC3_ERR_TIMEOUT without running.
+ * Errors: GC3_ERR_SIZE when the program's state does not fit the static array (or the element count / scratch
+ * capacity is unacceptable, as for gc3_comm_run), validation errors, GC3_ERR_RESIDENCY, GC3_ERR_ARG, GC3_ERR_HIP. */
+#define GC3_STATIC_SCRATCH_BYTES (64u << 20)
+int gc3_run_static(const gc3_program* prog, const gc3_comm_config* cfg, void* const* inputs, void* const* outputs,
+                   void* const* scratch, const size_t* scratch_bytes, size_t elems_per_rank, gc3_dtype dtype,
+                   gc3_redop op, void* hip_stream);
 
 /* ---- selection by buffer size (Section 6, introduction) ---- */
 

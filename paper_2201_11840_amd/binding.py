@@ -33,7 +33,7 @@ DTYPE_CODE = {"f32": GC3_F32, "f16": GC3_F16, "bf16": GC3_BF16}
 EXPORTS = ("gc3_last_error", "gc3_program_load", "gc3_program_free", "gc3_program_validate",
            "gc3_program_info_get", "gc3_program_scratch_chunks", "gc3_program_plan", "gc3_comm_create", "gc3_comm_info_get",
            "gc3_comm_bind", "gc3_comm_run", "gc3_comm_algorithmic_bytes", "gc3_comm_status",
-           "gc3_comm_reset", "gc3_comm_destroy", "gc3_comm_tune",
+           "gc3_comm_reset", "gc3_comm_destroy", "gc3_comm_tune", "gc3_run_static",
            "gc3_selector_create", "gc3_selector_add", "gc3_selector_run", "gc3_selector_destroy")
 
 
@@ -117,6 +117,8 @@ def lib() -> C.CDLL:
         L.gc3_comm_destroy.restype = None
         L.gc3_comm_tune.argtypes = [C.c_void_p, C.POINTER(CommConfig), C.c_size_t, C.c_int, C.c_void_p,
                                     C.POINTER(CommConfig), C.POINTER(TuneReport)]
+        L.gc3_run_static.argtypes = [C.c_void_p, C.POINTER(CommConfig), C.POINTER(C.c_void_p), C.POINTER(C.c_void_p),
+                                     C.POINTER(C.c_void_p), C.POINTER(C.c_size_t), C.c_size_t, C.c_int, C.c_int, C.c_void_p]
         L.gc3_selector_create.argtypes = [C.POINTER(C.c_void_p)]
         L.gc3_selector_add.argtypes = [C.c_void_p, C.c_void_p, C.c_uint64, C.c_uint64]
         L.gc3_selector_run.argtypes = [C.c_void_p, C.c_size_t, C.c_int, C.c_int, C.c_void_p, C.POINTER(C.c_int)]
@@ -216,6 +218,17 @@ def gc3_comm_tune(prog: C.c_void_p, base: Optional[CommConfig], elems_per_rank: 
     _check(lib().gc3_comm_tune(prog, C.byref(base) if base is not None else None, elems_per_rank, dtype,
                                C.c_void_p(stream), C.byref(best), C.byref(report)))
     return best, report
+
+
+def gc3_run_static(prog: C.c_void_p, cfg: Optional[CommConfig], inputs, outputs, scratch, scratch_bytes,
+                   elems_per_rank: int, dtype: int, op: int = GC3_SUM, stream: int = 0) -> None:
+    """inputs / outputs / scratch: sequences of device addresses (ints; None entries = null), outputs and scratch
+    may be None; scratch_bytes: sequence of capacities or None."""
+    n = len(inputs)
+    ptrs = lambda seq: None if seq is None else (C.c_void_p * n)(*[C.c_void_p(a or 0) for a in seq])
+    sizes = None if scratch_bytes is None else (C.c_size_t * n)(*scratch_bytes)
+    _check(lib().gc3_run_static(prog, C.byref(cfg) if cfg is not None else None, ptrs(inputs), ptrs(outputs),
+                                ptrs(scratch), sizes, elems_per_rank, dtype, op, C.c_void_p(stream)))
 
 
 def gc3_selector_create() -> C.c_void_p:

@@ -7,6 +7,7 @@
 #include <cmath>
 #include <cstring>
 #include <map>
+#include <mutex>
 #include <numeric>
 #include <string>
 #include <tuple>
@@ -19,6 +20,8 @@
 namespace gc3 {
 int launch_interpreter(int dtype, bool coherent_user, bool ll, unsigned grid, unsigned block, void* stream, const KParams& p);
 int interpreter_occupancy(unsigned block, int* out);
+int static_scratch_ptr(void** out);
+int launch_fill_zero(void* ptr, size_t bytes, void* stream);
 }  // namespace gc3
 
 using namespace gc3;
@@ -90,6 +93,58 @@ int upload(T** dptr, const std::vector<T>& host) {
   HIP_TRY(hipMalloc((void**)dptr, bytes));
   if (!host.empty()) HIP_TRY(hipMemcpy(*dptr, host.data(), host.size() * sizeof(T), hipMemcpyHostToDevice));
   return GC3_OK;
+}
+
+// What one run launches, as far as it depends on the chunk size only: active lanes, tile, protocol, grid.
+struct Launch {
+  KParams p{};
+  unsigned grid = 0, block = 0;
+  bool ll = false;
+  uint64_t lane_share = 0;   // largest share a lane has of a chunk, bytes
+};
+
+void shape_run(const gc3_comm_info& info, uint64_t cb, uint64_t min_lane_bytes, uint64_t ll_max_lane_bytes, Launch& L) {
+  KParams& p = L.p;
+  p.chunk_bytes = cb;
+  p.W = (uint32_t)info.team_width;
+  // small chunks are not worth splitting over all lanes: every active lane gets at least min_lane_bytes
+  p.W_active = (uint32_t)std::max<uint64_t>(1, std::min<uint64_t>(p.W, cb / min_lane_bytes));
+  p.slots = (uint32_t)info.fifo_slots;
+  p.slot_bytes = (uint32_t)info.slot_bytes;
+  // Shares are computed exactly as the kernel does.
+  uint64_t lane_share = 0;
+  {
+    const uint64_t U = cb >> 4, Wa = p.W_active;
+    auto begin = [&](uint64_t w) -> uint64_t {
+      if (w >= Wa) return U << 4;
+      if (U >= 16 * Wa) return (((U >> 4) * w) / Wa) << 8;
+      return ((U * w) / Wa) << 4;
+    };
+    for (uint64_t w = 0; w < Wa; ++w) lane_share = std::max(lane_share, begin(w + 1) - begin(w));
+  }
+  L.lane_share = lane_share;
+  // Tile of this run: about half of the largest lane share (two tiles per chunk keep sender and receiver
+  // overlapped), at least 16 KiB, at most the tile the FIFO slots were sized for.
+  {
+    uint64_t t = ((lane_share + 1) / 2 + 255) & ~255ull;
+    t = std::max<uint64_t>(t, 16384);
+    p.tile_bytes = (uint32_t)std::min<uint64_t>(t, (uint64_t)info.tile_bytes);
+  }
+  // Protocol of this run (Section 6.1): LL when forced, or in auto mode when the largest share a lane
+  // has of a chunk is small.
+  L.ll = info.protocol == 2 || (info.protocol == 3 && lane_share <= ll_max_lane_bytes);
+  if (L.ll) p.tile_bytes = (uint32_t)ll_max_lane_bytes;
+  // Lane-major grid: the workgroups of the active lanes are a prefix.  When only some lanes own bytes, the
+  // workgroups of the others take over part of the work: the fiber list of every (lane, bin) is dealt
+  // round-robin to nsplit workgroups, so that on small buffers thread blocks that share a workgroup in the
+  // plan run side by side instead.  Never more workgroups than the plan's (resident) grid.
+  p.wgs_per_lane = (uint32_t)info.wgs_per_lane;
+  p.nsplit = std::max<uint32_t>(1, std::min<uint32_t>(p.W / p.W_active, (uint32_t)info.max_fibers_per_wg));
+  L.grid = p.W_active * p.nsplit * p.wgs_per_lane;
+  // a lane share of a few KiB is one sweep for two wavefronts: fewer threads to synchronise per instruction
+  // (measured 2-3 % faster up to 8 KiB per lane, slower above)
+  L.block = (unsigned)info.wg_size;
+  if (L.block > 128 && lane_share <= 8192) L.block = 128;
 }
 
 }  // namespace
@@ -238,7 +293,8 @@ int gc3_comm_run(gc3_comm* comm, size_t elems_per_rank, gc3_dtype dtype, gc3_red
     HIP_TRY(hipStreamSynchronize(st));
     comm->bufs_dirty = false;
   }
-  KParams p{};
+  Launch L;
+  KParams& p = L.p;
   p.instrs = comm->d_instrs;
   p.deps = comm->d_deps;
   p.wgs = comm->d_wgs;
@@ -250,57 +306,21 @@ int gc3_comm_run(gc3_comm* comm, size_t elems_per_rank, gc3_dtype dtype, gc3_red
   p.error = comm->d_error;
   p.hold = comm->debug_hold ? comm->d_error + 32 : nullptr;   // a word of the zeroed error block nobody writes
   p.run_base = (++comm->run_number) << 32;
-  p.chunk_bytes = cb;
   p.spin_limit_ticks = comm->spin_limit_ticks;
-  p.W = (uint32_t)comm->info.team_width;
-  // small chunks are not worth splitting over all lanes: every active lane gets at least min_lane_bytes
-  p.W_active = (uint32_t)std::max<uint64_t>(1, std::min<uint64_t>(p.W, cb / comm->min_lane_bytes));
-  p.slots = (uint32_t)comm->info.fifo_slots;
-  p.tile_bytes = (uint32_t)comm->info.tile_bytes;
-  p.slot_bytes = (uint32_t)comm->info.slot_bytes;
-  // Protocol of this run (Section 6.1): LL when forced, or in auto mode when the largest share a lane
-  // has of a chunk is small.  Shares are computed exactly as the kernel does.
-  uint64_t lane_share = 0;
-  {
-    const uint64_t U = cb >> 4, Wa = p.W_active;
-    auto begin = [&](uint64_t w) -> uint64_t {
-      if (w >= Wa) return U << 4;
-      if (U >= 16 * Wa) return (((U >> 4) * w) / Wa) << 8;
-      return ((U * w) / Wa) << 4;
-    };
-    for (uint64_t w = 0; w < Wa; ++w) lane_share = std::max(lane_share, begin(w + 1) - begin(w));
-  }
-  // Tile of this run: about half of the largest lane share (two tiles per chunk keep sender and receiver
-  // overlapped), at least 16 KiB, at most the tile the FIFO slots were sized for.
-  {
-    uint64_t t = ((lane_share + 1) / 2 + 255) & ~255ull;
-    t = std::max<uint64_t>(t, 16384);
-    p.tile_bytes = (uint32_t)std::min<uint64_t>(t, (uint64_t)comm->info.tile_bytes);
-  }
-  const bool ll = comm->info.protocol == 2 || (comm->info.protocol == 3 && lane_share <= comm->ll_max_lane_bytes);
+  shape_run(comm->info, cb, comm->min_lane_bytes, comm->ll_max_lane_bytes, L);
   p.ll_fifo = comm->d_ll_fifo;
   p.ll_slot_bytes = comm->ll_slot_bytes;
-  if (ll) {
-    p.tile_bytes = (uint32_t)comm->ll_max_lane_bytes;
+  if (L.ll) {
     // message numbers of this run: [ll_next + 1, ll_next + messages]; their low 32 bits are the flags and
     // must never be 0 (the value untouched slot memory holds), so a range never crosses a multiple of 2^32
-    const uint64_t tiles = (lane_share + p.tile_bytes - 1) / p.tile_bytes;
+    const uint64_t tiles = (L.lane_share + p.tile_bytes - 1) / p.tile_bytes;
     const uint64_t messages = (uint64_t)comm->max_pushes * tiles + 1;
     if (((comm->ll_next + messages) >> 32) != (comm->ll_next >> 32)) comm->ll_next = ((comm->ll_next >> 32) + 1) << 32;
     p.ll_base = (uint32_t)comm->ll_next;
     comm->ll_next += messages;
   }
-  // Lane-major grid: the workgroups of the active lanes are a prefix.  When only some lanes own bytes, the
-  // workgroups of the others take over part of the work: the fiber list of every (lane, bin) is dealt
-  // round-robin to nsplit workgroups, so that on small buffers thread blocks that share a workgroup in the
-  // plan run side by side instead.  Never more workgroups than the plan's (resident) grid.
-  p.wgs_per_lane = (uint32_t)comm->info.wgs_per_lane;
-  p.nsplit = std::max<uint32_t>(1, std::min<uint32_t>(p.W / p.W_active, (uint32_t)comm->info.max_fibers_per_wg));
-  const unsigned grid = p.W_active * p.nsplit * p.wgs_per_lane;
-  // a lane share of a few KiB is one sweep for two wavefronts: fewer threads to synchronise per instruction
-  // (measured 2-3 % faster up to 8 KiB per lane, slower above)
-  unsigned block = (unsigned)comm->info.wg_size;
-  if (block > 128 && lane_share <= 8192) block = 128;
+  const bool ll = L.ll;
+  const unsigned grid = L.grid, block = L.block;
   int e = launch_interpreter((int)dtype, comm->has_deps, ll, grid, block, hip_stream, p);
   if (e != 0) return hip_fail((hipError_t)e, "interpreter launch");
   return GC3_OK;
@@ -474,6 +494,166 @@ int gc3_comm_tune(const gc3_program* prog, const gc3_comm_config* base, size_t e
 }
 
 }  // extern "C"
+
+// ---- one run for callers that cannot allocate device memory ---------------------------------------------------
+
+namespace {
+// What gc3_run_static needs to know of a device, looked up once per device.
+struct StaticDevice {
+  bool ready = false;
+  void* scratch = nullptr;      // this device's copy of the static array
+  int cus = 0;
+  int occupancy[4] = {0, 0, 0, 0};   // workgroups per compute unit for 64, 128, 256, 512 threads
+};
+constexpr int kMaxStaticDevices = 64;
+StaticDevice g_static[kMaxStaticDevices];
+std::mutex g_static_lock;
+
+int static_device(int dev, const StaticDevice** out) {
+  if (dev < 0 || dev >= kMaxStaticDevices) { set_error("device index out of range"); return GC3_ERR_ARG; }
+  std::lock_guard<std::mutex> hold(g_static_lock);
+  StaticDevice& d = g_static[dev];
+  if (!d.ready) {
+    void* ptr = nullptr;
+    int e = static_scratch_ptr(&ptr);
+    if (e != 0) return hip_fail((hipError_t)e, "hipGetSymbolAddress(static scratch)");
+    int cus = 0;
+    HIP_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+    int k = 0;
+    for (unsigned block : {64u, 128u, 256u, 512u}) {
+      e = interpreter_occupancy(block, &d.occupancy[k++]);
+      if (e != 0) return hip_fail((hipError_t)e, "hipOccupancyMaxActiveBlocksPerMultiprocessor");
+    }
+    d.scratch = ptr;
+    d.cus = cus;
+    d.ready = true;
+  }
+  *out = &d;
+  return GC3_OK;
+}
+
+uint64_t align256(uint64_t v) { return (v + 255) & ~255ull; }
+}  // namespace
+
+extern "C" int gc3_run_static(const gc3_program* prog, const gc3_comm_config* cfg_in, void* const* inputs,
+                              void* const* outputs, void* const* scratch_bufs, const size_t* scratch_bytes,
+                              size_t elems_per_rank, gc3_dtype dtype, gc3_redop op, void* hip_stream) {
+  if (!prog || !inputs) { set_error("null argument"); return GC3_ERR_ARG; }
+  if (op != GC3_SUM) { set_error("unknown reduction"); return GC3_ERR_ARG; }
+  const int es = dtype_size(dtype);
+  if (!es) { set_error("unknown dtype"); return GC3_ERR_ARG; }
+  gc3_comm_config cfg{};
+  std::string msg;
+  int rc = resolve_config(cfg_in, cfg, msg);
+  if (rc != GC3_OK) { set_error(msg); return rc; }
+  if (cfg.protocol > 1) { set_error("gc3_run_static runs the simple protocol only"); return GC3_ERR_ARG; }
+  cfg.protocol = 1;
+  const int R = prog->ranks;
+  if (prog->in_chunks <= 0 || elems_per_rank % (size_t)prog->in_chunks) {
+    set_error("elems_per_rank is not a multiple of the program's chunk count");
+    return GC3_ERR_SIZE;
+  }
+  const uint64_t cb = (uint64_t)(elems_per_rank / prog->in_chunks) * es;
+  if (cb % 16) { set_error("chunk size is not a multiple of 16 bytes"); return GC3_ERR_SIZE; }
+  if (cb >> 40) { set_error("chunks of 1 TiB and more are not supported"); return GC3_ERR_SIZE; }
+  if (!prog->inplace && !outputs) { set_error("out-of-place program needs output buffers"); return GC3_ERR_ARG; }
+  std::vector<void*> bufs((size_t)R * 3, nullptr);
+  for (int r = 0; r < R; ++r) {
+    void* in = inputs[r];
+    void* out = prog->inplace ? in : outputs[r];
+    if (prog->inplace && outputs && outputs[r] && outputs[r] != in) {
+      set_error("in-place program: output must alias input");
+      return GC3_ERR_ARG;
+    }
+    const int sc = prog->rank[r].scratch_chunks;
+    void* sb = (sc > 0 && scratch_bufs) ? scratch_bufs[r] : nullptr;
+    if (!in || !out || (!prog->inplace && out == in)) { set_error("rank " + std::to_string(r) + ": bad input / output buffer"); return GC3_ERR_ARG; }
+    if (sc > 0 && (!sb || !scratch_bytes)) { set_error("rank " + std::to_string(r) + " uses scratch chunks but has no scratch buffer"); return GC3_ERR_ARG; }
+    if (sc > 0 && (uint64_t)sc * cb > scratch_bytes[r]) { set_error("rank " + std::to_string(r) + ": scratch buffer too small for this size"); return GC3_ERR_SIZE; }
+    for (void* q : {in, out, sb})
+      if ((uintptr_t)q % 16) { set_error("buffers must be 16-byte aligned"); return GC3_ERR_ARG; }
+    bufs[(size_t)r * 3 + 0] = in;
+    bufs[(size_t)r * 3 + 1] = out;
+    bufs[(size_t)r * 3 + 2] = sb;
+  }
+
+  int dev = -1;
+  HIP_TRY(hipGetDevice(&dev));
+  const StaticDevice* sd = nullptr;
+  if ((rc = static_device(dev, &sd)) != GC3_OK) return rc;
+  const int occ = sd->occupancy[cfg.wg_size == 64 ? 0 : cfg.wg_size == 128 ? 1 : cfg.wg_size == 256 ? 2 : 3];
+
+  // Plan with the FIFOs bounded by what the static array can hold; tables, flags and semaphores are small and
+  // get a fixed reserve that is checked exactly below.
+  Plan plan;
+  const uint64_t reserve = 8ull << 20;
+  rc = make_plan(*prog, cfg, sd->cus, (long)occ * sd->cus, plan, msg, kStaticScratchBytes - reserve);
+  if (rc != GC3_OK) { set_error("gc3_run_static: " + msg); return rc; }
+  if (elems_per_rank == 0 || plan.info.grid == 0) return GC3_OK;
+
+  // Layout: [error block | flags | semaphores] (cleared every call) [pointer table | instructions |
+  // dependencies | workgroup headers | fibers] (copied every call) [FIFOs].
+  const int W = plan.info.team_width;
+  const uint64_t flags_bytes = std::max<uint64_t>(1, (uint64_t)plan.nconn * W * 2) * kFlagStrideWords * sizeof(uint64_t);
+  const uint64_t sems_bytes = std::max<uint64_t>(1, (uint64_t)plan.ntb * W) * kFlagStrideWords * sizeof(uint64_t);
+  const uint64_t off_flags = 256, off_sems = off_flags + flags_bytes, off_tables = align256(off_sems + sems_bytes);
+  const uint64_t t_bufs = 0;
+  const uint64_t t_instrs = align256(t_bufs + bufs.size() * sizeof(void*));
+  const uint64_t t_deps = align256(t_instrs + plan.instrs.size() * sizeof(DInstr));
+  const uint64_t t_wgs = align256(t_deps + plan.deps.size() * sizeof(DDep));
+  const uint64_t t_fibers = align256(t_wgs + plan.wgs.size() * sizeof(DWg));
+  const uint64_t tables_bytes = align256(t_fibers + plan.fibers.size() * sizeof(DFiber));
+  const uint64_t off_fifo = off_tables + tables_bytes;
+  const uint64_t need = off_fifo + plan.info.fifo_bytes;
+  if (need > kStaticScratchBytes) {
+    set_error("gc3_run_static: this program needs " + std::to_string(need) + " bytes of device state, the static array holds " +
+              std::to_string((uint64_t)kStaticScratchBytes) + " (use a communicator instead)");
+    return GC3_ERR_SIZE;
+  }
+  std::vector<unsigned char> tables(tables_bytes, 0);
+  std::memcpy(tables.data() + t_bufs, bufs.data(), bufs.size() * sizeof(void*));
+  if (!plan.instrs.empty()) std::memcpy(tables.data() + t_instrs, plan.instrs.data(), plan.instrs.size() * sizeof(DInstr));
+  if (!plan.deps.empty()) std::memcpy(tables.data() + t_deps, plan.deps.data(), plan.deps.size() * sizeof(DDep));
+  if (!plan.wgs.empty()) std::memcpy(tables.data() + t_wgs, plan.wgs.data(), plan.wgs.size() * sizeof(DWg));
+  if (!plan.fibers.empty()) std::memcpy(tables.data() + t_fibers, plan.fibers.data(), plan.fibers.size() * sizeof(DFiber));
+
+  // `base` is the device address obtained from hipGetSymbolAddress: the array's name is never used here.
+  unsigned char* const base = (unsigned char*)sd->scratch;
+  hipStream_t st = (hipStream_t)hip_stream;
+  // the error word the previous call on this device left, then this call's tables; the host copies of both
+  // die with this call, so the stream is drained before going on
+  uint32_t previous_error = 0;
+  HIP_TRY(hipMemcpyAsync(&previous_error, base, sizeof(previous_error), hipMemcpyDeviceToHost, st));
+  HIP_TRY(hipMemcpyAsync(base + off_tables, tables.data(), tables_bytes, hipMemcpyHostToDevice, st));
+  HIP_TRY(hipStreamSynchronize(st));
+  // flags, semaphores and the error word of whatever ran here before must start at zero
+  int e = launch_fill_zero(base, off_tables, hip_stream);
+  if (e != 0) return hip_fail((hipError_t)e, "fill launch");
+  if (previous_error != 0) {
+    set_error("the previous gc3_run_static on this device was abandoned (a wait exceeded the spin limit); its outputs are "
+              "incomplete and this call did not run");
+    return -(int)previous_error;
+  }
+
+  Launch L;
+  KParams& p = L.p;
+  p.bufs = (void* const*)(base + off_tables + t_bufs);
+  p.instrs = (const DInstr*)(base + off_tables + t_instrs);
+  p.deps = (const DDep*)(base + off_tables + t_deps);
+  p.wgs = (const DWg*)(base + off_tables + t_wgs);
+  p.fibers = (const DFiber*)(base + off_tables + t_fibers);
+  p.fifo = base + off_fifo;
+  p.flags = (uint64_t*)(base + off_flags);
+  p.sems = (uint64_t*)(base + off_sems);
+  p.error = (uint32_t*)base;
+  p.hold = cfg.debug_hold ? (const uint32_t*)(base + 128) : nullptr;
+  p.run_base = 1ull << 32;                 // flags were just cleared: every call is run number one
+  p.spin_limit_ticks = cfg.spin_limit_us * 100ull;
+  shape_run(plan.info, cb, (uint64_t)cfg.min_lane_bytes, (uint64_t)cfg.ll_max_lane_bytes, L);
+  e = launch_interpreter((int)dtype, !plan.deps.empty(), false, L.grid, L.block, hip_stream, p);
+  if (e != 0) return hip_fail((hipError_t)e, "interpreter launch");
+  return GC3_OK;
+}
 
 // ---- selection by buffer size (Section 6, introduction) -----------------------------------------------
 

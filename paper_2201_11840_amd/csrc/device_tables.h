@@ -9,6 +9,9 @@ namespace gc3 {
 constexpr int kMaxFibersPerWg = 32;  // lanes of IR thread blocks one workgroup may multiplex
 constexpr int kFlagStrideWords = 16;  // one 64-bit flag per 128-byte line
 constexpr int kLdsInstrs = 192;       // instructions (of all its fibers together) a workgroup keeps in LDS
+// Size of the per-GPU static array that serves callers who cannot allocate device memory: flags, semaphores,
+// instruction tables and FIFOs of one run must fit.
+constexpr unsigned long long kStaticScratchBytes = 64ull << 20;
 
 struct DInstr {            // 32 bytes
   uint32_t op;             // gc3_opcode

@@ -27,6 +27,8 @@
 // workgroup barrier, then device-scope loads of the payload.
 #include <hip/hip_runtime.h>
 
+#include <mutex>
+
 #include "device_tables.h"
 #include "gc3.h"
 
@@ -643,6 +645,54 @@ int interpreter_occupancy(unsigned block, int* out) {
   }
   *out = best;
   return 0;
+}
+
+}  // namespace gc3
+
+// ---- device memory for callers that cannot allocate ---------------------------------------------------------
+// One array per GPU the library runs on, held until the process ends.  In host code the array's name is only a
+// stand-in for the symbol, not a device address: its address on the current device comes from
+// hipGetSymbolAddress, once per device, and only that pointer is ever handed to kernels and copies.
+static __device__ __align__(256) unsigned char scratch[gc3::kStaticScratchBytes];
+
+namespace gc3 {
+
+namespace {
+constexpr int kMaxDevices = 64;
+void* g_scratch_ptr[kMaxDevices];   // per device, set once under the lock
+std::mutex g_scratch_lock;
+
+__global__ void __launch_bounds__(256) gc3_fill_zero(u32x4* dst, uint32_t nvec) {
+  const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < nvec) dst[i] = u32x4{0, 0, 0, 0};
+}
+}  // namespace
+
+// Address of the current device's copy of the static scratch array (resolved on the first call per device).
+int static_scratch_ptr(void** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return (int)e;
+  if (dev < 0 || dev >= kMaxDevices) return (int)hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> hold(g_scratch_lock);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    e = hipGetSymbolAddress((void**)&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return (int)e;
+    if (!ptr) return (int)hipErrorInvalidSymbol;
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return 0;
+}
+
+// Zero [ptr, ptr + bytes) with a kernel on `stream` (bytes a multiple of 16, ptr 16-byte aligned): a fill
+// kernel, not a memset node, so that the call may be recorded into a graph.
+int launch_fill_zero(void* ptr, size_t bytes, void* stream) {
+  const uint32_t nvec = (uint32_t)(bytes >> 4);
+  if (nvec == 0) return 0;
+  hipLaunchKernelGGL(gc3_fill_zero, dim3((nvec + 255) / 256), dim3(256), 0, (hipStream_t)stream, (u32x4*)ptr, nvec);
+  return (int)hipGetLastError();
 }
 
 }  // namespace gc3

@@ -46,7 +46,8 @@ int resolve_config(const gc3_comm_config* cfg_in, gc3_comm_config& cfg, std::str
   return GC3_OK;
 }
 
-int make_plan(const gc3_program& prog, const gc3_comm_config& cfg, int cus, long resident, Plan& plan, std::string& msg) {
+int make_plan(const gc3_program& prog, const gc3_comm_config& cfg, int cus, long resident, Plan& plan, std::string& msg,
+              uint64_t fifo_limit) {
   if (cus < 1 || resident < 1) { msg = "device size must be positive"; return GC3_ERR_ARG; }
   int rc = validate(prog, cfg.fifo_slots, msg);
   if (rc != GC3_OK) return rc;
@@ -255,18 +256,27 @@ int make_plan(const gc3_program& prog, const gc3_comm_config& cfg, int cus, long
   int tile_bytes = cfg.tile_bytes;
   if (tile_bytes == 0) {
     tile_bytes = 65536;
-    while (tile_bytes > 16384 && (uint64_t)nconn * W * cfg.fifo_slots * max_count * (uint64_t)tile_bytes > (256ull << 20))
+    const uint64_t soft = fifo_limit ? fifo_limit : (256ull << 20);
+    const int floor_bytes = fifo_limit ? 1024 : 16384;
+    while (tile_bytes > floor_bytes && (uint64_t)nconn * W * cfg.fifo_slots * max_count * (uint64_t)tile_bytes > soft)
       tile_bytes /= 2;
   }
   plan.cfg.tile_bytes = tile_bytes;
   const uint64_t slot_bytes = (uint64_t)max_count * (uint64_t)tile_bytes;
   const uint64_t fifo_bytes = std::max<uint64_t>(16, (uint64_t)nconn * W * cfg.fifo_slots * slot_bytes);
   if (slot_bytes > (1ull << 30) || fifo_bytes > (64ull << 30)) { msg = "FIFO memory too large"; return GC3_ERR_SIZE; }
+  if (fifo_limit && fifo_bytes > fifo_limit) {
+    msg = "the connections' FIFOs need " + std::to_string(fifo_bytes) + " bytes, " + std::to_string(fifo_limit) + " are available";
+    return GC3_ERR_SIZE;
+  }
   int protocol = cfg.protocol;
   if (protocol == 0) protocol = prog.protocol == "simple" ? 1 : (prog.protocol == "ll" || prog.protocol == "ll128") ? 2 : 3;
   const uint64_t ll_slot_bytes = 2ull * max_count * (uint64_t)cfg.ll_max_lane_bytes;
   const uint64_t ll_fifo_bytes = protocol == 1 ? 0 : std::max<uint64_t>(16, (uint64_t)nconn * W * cfg.fifo_slots * ll_slot_bytes);
-  if (ll_fifo_bytes > (64ull << 30)) { msg = "LL FIFO memory too large"; return GC3_ERR_SIZE; }
+  if (protocol != 1 && (ll_slot_bytes > (1ull << 30) || ll_fifo_bytes > (64ull << 30))) {
+    msg = "LL FIFO memory too large";
+    return GC3_ERR_SIZE;
+  }
   int max_pushes = 0;
   for (int r = 0; r < R; ++r)
     for (auto& tb : prog.rank[r].tbs) {

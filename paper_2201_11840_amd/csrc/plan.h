@@ -26,7 +26,10 @@ struct Plan {
 int resolve_config(const gc3_comm_config* cfg_in, gc3_comm_config& cfg, std::string& msg);
 
 // Validate `prog` and plan it for a device with `cus` compute units that can hold `resident`
-// workgroups of cfg.wg_size threads at once.
-int make_plan(const gc3_program& prog, const gc3_comm_config& cfg, int cus, long resident, Plan& plan, std::string& msg);
+// workgroups of cfg.wg_size threads at once.  `fifo_limit` = 0: the slot tile defaults to 64 KiB, halved (not
+// below 16 KiB) while all FIFOs exceed 256 MiB.  `fifo_limit` > 0: a hard bound on the FIFO memory; the default
+// tile is halved (not below 1 KiB) until the FIFOs fit, and a plan that still does not fit is GC3_ERR_SIZE.
+int make_plan(const gc3_program& prog, const gc3_comm_config& cfg, int cus, long resident, Plan& plan, std::string& msg,
+              uint64_t fifo_limit = 0);
 
 }  // namespace gc3
