@@ -21,6 +21,13 @@
  *    released with the matching free / destroy call.
  *  - Calls on one gc3_comm must not overlap in time (from several threads or streams): the
  *    FIFOs, flags and semaphores of a communicator are shared by its runs.
+ *  - Runs of DIFFERENT communicators may be launched on different streams.  All workgroups of a run
+ *    wait on each other, so every grid in flight has to be resident at once (Section 6.2); the
+ *    library keeps a per-device ledger of the runs it launched and makes a new run's stream wait
+ *    for earlier runs on other streams when they would not fit the device together (see
+ *    gc3_residency_plan for the rule).  The ledger sees only launches made through gc3_comm_run
+ *    outside stream capture: kernels of other libraries that fill the device for longer than the
+ *    spin limit, and replays of captured launches, are the caller's to keep apart.
  */
 #ifndef GC3_H
 #define GC3_H
@@ -90,8 +97,13 @@ typedef struct gc3_comm_config {
                               rank may share a workgroup.  0 = choose W and the sharing so that the
                               heaviest workgroup is lightest */
   int32_t wg_size;         /* threads per workgroup: 64, 128, 256 or 512; default 256 (a run whose lanes get
-                              at most 8 KiB of a chunk launches 128 of them) */
-  int32_t reserved0;       /* must be 0 */
+                              at most 8 KiB of a chunk launches 128 of them).  With 64, runs in which every
+                              workgroup executes a single thread-block lane use the wavefront-level
+                              interpreter: no workgroup barrier and no LDS state on the path of a hop */
+  int32_t lds_stage;       /* 1 = the receiving instructions (recv, rrc, rcs, rrcs, rrs) bring the FIFO payload into LDS
+                              with direct-to-LDS 128-bit loads and read it back from there, so loads in flight
+                              hold no registers; 0 (default) = through registers.  Same results; on MI355X the
+                              register path is as fast or faster, the option exists for measurement */
   int32_t target_wgs;      /* workgroups the schedule aims at (never more than can be resident);
                               0 = four per compute unit */
   uint64_t spin_limit_us;  /* longest a workgroup waits on one flag before the run is abandoned
@@ -157,6 +169,8 @@ void gc3_program_free(gc3_program* prog);
  * message.  Errors: GC3_ERR_INVALID_PROGRAM, GC3_ERR_DEADLOCK, GC3_ERR_ARG. */
 int gc3_program_validate(const gc3_program* prog, int fifo_slots, char* err, size_t errlen);
 
+/* Shape of a parsed program (Section 3.1: number of ranks and chunks per buffer are fixed by the program, the
+ * buffer size is not; Section 5: thread blocks, connections, instructions).  Errors: GC3_ERR_ARG. */
 int gc3_program_info_get(const gc3_program* prog, gc3_program_info* out);
 
 /* Scratch chunks rank `rank` needs (Section 3.2: deduced from the highest index used). */
@@ -171,6 +185,8 @@ int gc3_program_scratch_chunks(const gc3_program* prog, int rank, int* out);
  * Errors: validation errors, GC3_ERR_RESIDENCY, GC3_ERR_HIP, GC3_ERR_ARG. */
 int gc3_comm_create(const gc3_program* prog, const gc3_comm_config* cfg, gc3_comm** out);
 
+/* The plan in use: team width, grid, tile and slot sizes, FIFO memory (Section 6.1: b and s are properties of the
+ * connection set-up).  Errors: GC3_ERR_ARG. */
 int gc3_comm_info_get(const gc3_comm* comm, gc3_comm_info* out);
 
 /* What gc3_comm_tune tried. */
@@ -215,32 +231,82 @@ int gc3_program_plan(const gc3_program* prog, const gc3_comm_config* cfg, int co
 /* Bind the three named buffers of one rank (Section 3.1): device pointers, 16-byte aligned,
  * owned by the caller and alive for every later run.  For an in-place program `output` must be
  * null or equal `input`.  `scratch` may be null iff the rank uses no scratch chunk;
- * `scratch_bytes` is its capacity, checked against the run's chunk size.
- * Errors: GC3_ERR_ARG. */
+ * `scratch_bytes` is its capacity, checked against the run's chunk size.  The device-side pointer table is
+ * updated before the call returns (a small synchronous copy, after waiting for this communicator's last run),
+ * so binding is set-up work: not for use under stream capture.
+ * Errors: GC3_ERR_ARG, GC3_ERR_HIP. */
 int gc3_comm_bind(gc3_comm* comm, int rank, void* input, void* output, void* scratch, size_t scratch_bytes);
 
-/* Run the collective once, asynchronously on `hip_stream` (a hipStream_t, null = default stream).
- * `elems_per_rank` is the element count of every rank's INPUT buffer; a chunk is
+/* What gc3_comm_run launches for one size (host only). */
+typedef struct gc3_launch_info {
+  int32_t grid;           /* workgroups (0 = nothing is launched) */
+  int32_t wg_size;        /* threads per workgroup of this run */
+  int32_t active_lanes;   /* lanes that own bytes: min(team width, chunk bytes / min_lane_bytes), at least 1 */
+  int32_t split;          /* workgroups that share the fiber list of one (lane, bin) of the plan */
+  int32_t tile_bytes;     /* bytes of one chunk a fiber moves per tile in this run */
+  int32_t kernel;         /* 0 general interpreter, 1 LL protocol, 2 FIFO payload staged through LDS,
+                             3 wavefront-level interpreter (one wavefront, one thread-block lane per workgroup) */
+  uint64_t lane_bytes;    /* largest share a lane has of one chunk */
+} gc3_launch_info;
+
+/* The launch gc3_comm_run would make for `elems_per_rank` elements of `dtype`: how the runtime's own
+ * parallelization (Section 5.1 applied by the runtime) and tiling (Section 6.2) turn out for this chunk size.
+ * Touches no device.  Errors: GC3_ERR_SIZE, GC3_ERR_ARG. */
+int gc3_comm_launch_info(const gc3_comm* comm, size_t elems_per_rank, gc3_dtype dtype, gc3_launch_info* out);
+
+/* Run the collective once, asynchronously on `hip_stream` (a hipStream_t, null = default stream): one launch
+ * of the interpreter kernel (Section 6.2), in which every thread block executes its instruction list tile by
+ * tile.  `elems_per_rank` is the element count of every rank's INPUT buffer; a chunk is
  * elems_per_rank / in_chunks elements (Section 3.1: the chunk size is known only at run time),
  * the output buffer holds out_chunks chunks.  The chunk must be a whole number of elements and
  * of 16-byte units.  elems_per_rank = 0 is a no-op.  Errors: GC3_ERR_UNBOUND, GC3_ERR_SIZE,
  * GC3_ERR_POISONED, GC3_ERR_HIP, GC3_ERR_ARG.  A GC3_ERR_TIMEOUT inside the kernel is reported by
- * gc3_comm_status.  Not for use under stream capture: the run number is a kernel argument (a captured
- * launch must not be replayed) and the first run after a bind copies the pointer table and waits for the stream. */
+ * gc3_comm_status.
+ * Stream capture: the kernel's arguments depend only on the communicator, the size and the data type (the run
+ * counters live in device memory), the call copies nothing and waits for nothing, so under the simple protocol
+ * it may be recorded into a HIP graph and replayed any number of times, also interleaved with eager runs of the
+ * same communicator (never overlapping them).  A run under the LL protocol is refused while capturing
+ * (GC3_ERR_ARG).  A communicator serves 2^32 - 1 runs between resets. */
 int gc3_comm_run(gc3_comm* comm, size_t elems_per_rank, gc3_dtype dtype, gc3_redop op, void* hip_stream);
 
-/* Bytes the method loads and stores through global memory in one run of this size:
- * algorithmic_chunks x chunk bytes. */
+/* Bytes the method itself loads and stores through global memory in one run of this size: the sum over all
+ * instructions of count x chunk bytes x (send 2, recv 2, copy 2, reduce 3, rrc 3, rcs 3, rrcs 4, rrs 3) -
+ * every instruction of Section 4.2 reads each of its operands once and writes each of its results once;
+ * flags, semaphores and instruction fetches are not counted.  This is the numerator of the throughput the
+ * benchmark reports.  Errors: GC3_ERR_SIZE, GC3_ERR_ARG. */
 int gc3_comm_algorithmic_bytes(const gc3_comm* comm, size_t elems_per_rank, gc3_dtype dtype, uint64_t* out);
 
-/* Wait for the device and report whether any run since the last reset failed
- * (GC3_ERR_TIMEOUT; the communicator is then poisoned) or GC3_OK. */
+/* Wait for this communicator's last run launched outside stream capture (its completion event; no other stream
+ * of the process is stalled) and report whether any run since the last reset was abandoned because a wait
+ * inside the kernel - for a semaphore, a message or a free slot, Section 6.2 - exceeded the spin limit
+ * (GC3_ERR_TIMEOUT; the communicator is then poisoned) or GC3_OK.  After replaying a captured run, synchronise
+ * the stream it ran on first.  Errors: GC3_ERR_TIMEOUT, GC3_ERR_HIP, GC3_ERR_ARG. */
 int gc3_comm_status(gc3_comm* comm);
 
-/* Clear all flags, semaphores and the error state (synchronises the device). */
+/* Clear all flags, semaphores, run counters and the error state, as after the initial set-up of Section 6.2
+ * (synchronises the device).  Errors: GC3_ERR_HIP, GC3_ERR_ARG. */
 int gc3_comm_reset(gc3_comm* comm);
 
+/* Wait for the communicator's last run launched outside capture and release its connections (FIFOs, flags),
+ * semaphores and tables (the teardown of what Section 6.2's initial set-up created). */
 void gc3_comm_destroy(gc3_comm* comm);
+
+/* One run in flight, as the per-device ledger sees it. */
+typedef struct gc3_inflight {
+  uint64_t stream;    /* identity of the stream it was launched on */
+  int32_t wgs;        /* workgroups of the run */
+  int32_t capacity;   /* workgroups of that size the device holds at once */
+} gc3_inflight;
+
+/* The rule gc3_comm_run applies before a launch, as a host-only function (no device is touched): given the runs
+ * in flight on a device, oldest first, and a new run of `wgs` workgroups (device capacity `capacity`) on
+ * `stream`, set wait_on[i] = 1 for the runs the new run's stream must wait for and 0 for the others.  A run's
+ * share of the device is wgs / capacity; runs on `stream` itself never overlap the new one; the oldest runs on
+ * other streams are waited for until the shares of the rest plus the new run's are at most the whole device
+ * (Section 6.2: all thread blocks of a program must be able to run concurrently).
+ * Returns the number of runs to wait for (>= 0), or GC3_ERR_ARG. */
+int gc3_residency_plan(const gc3_inflight* inflight, int n, uint64_t stream, int32_t wgs, int32_t capacity,
+                       int32_t* wait_on);
 
 /* For callers that cannot allocate device memory - code under HIP graph capture rules that forbid hipMalloc,
  * tight serving loops, harnesses that ban allocation: one complete run of `prog` without a communicator and

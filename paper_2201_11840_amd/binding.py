@@ -32,8 +32,8 @@ DTYPE_CODE = {"f32": GC3_F32, "f16": GC3_F16, "bf16": GC3_BF16}
 
 EXPORTS = ("gc3_last_error", "gc3_program_load", "gc3_program_free", "gc3_program_validate",
            "gc3_program_info_get", "gc3_program_scratch_chunks", "gc3_program_plan", "gc3_comm_create", "gc3_comm_info_get",
-           "gc3_comm_bind", "gc3_comm_run", "gc3_comm_algorithmic_bytes", "gc3_comm_status",
-           "gc3_comm_reset", "gc3_comm_destroy", "gc3_comm_tune", "gc3_run_static",
+           "gc3_comm_bind", "gc3_comm_launch_info", "gc3_comm_run", "gc3_comm_algorithmic_bytes", "gc3_comm_status",
+           "gc3_comm_reset", "gc3_comm_destroy", "gc3_comm_tune", "gc3_run_static", "gc3_residency_plan",
            "gc3_selector_create", "gc3_selector_add", "gc3_selector_run", "gc3_selector_destroy")
 
 
@@ -46,16 +46,16 @@ class ProgramInfo(C.Structure):
 
 class CommConfig(C.Structure):
     _fields_ = [("fifo_slots", C.c_int32), ("tile_bytes", C.c_int32), ("team_width", C.c_int32),
-                ("wg_size", C.c_int32), ("reserved0", C.c_int32), ("target_wgs", C.c_int32),
+                ("wg_size", C.c_int32), ("lds_stage", C.c_int32), ("target_wgs", C.c_int32),
                 ("spin_limit_us", C.c_uint64), ("debug_hold", C.c_int32), ("min_lane_bytes", C.c_int32),
                 ("protocol", C.c_int32), ("ll_max_lane_bytes", C.c_int32)]
 
 
 def make_config(fifo_slots: int = 0, tile_bytes: int = 0, team_width: int = 0, wg_size: int = 0,
                 spin_limit_us: int = 0, target_wgs: int = 0, debug_hold: int = 0,
-                min_lane_bytes: int = 0, protocol: int = 0, ll_max_lane_bytes: int = 0) -> CommConfig:
+                min_lane_bytes: int = 0, protocol: int = 0, ll_max_lane_bytes: int = 0, lds_stage: int = 0) -> CommConfig:
     """A gc3_comm_config; zero fields select the library's defaults."""
-    return CommConfig(fifo_slots, tile_bytes, team_width, wg_size, 0, target_wgs, spin_limit_us,
+    return CommConfig(fifo_slots, tile_bytes, team_width, wg_size, lds_stage, target_wgs, spin_limit_us,
                       debug_hold, min_lane_bytes, protocol, ll_max_lane_bytes)
 
 
@@ -68,6 +68,18 @@ class CommInfo(C.Structure):
 
 
 GC3_TUNE_MAX_TRIED = 24
+
+
+class LaunchInfo(C.Structure):
+    _fields_ = [("grid", C.c_int32), ("wg_size", C.c_int32), ("active_lanes", C.c_int32), ("split", C.c_int32),
+                ("tile_bytes", C.c_int32), ("kernel", C.c_int32), ("lane_bytes", C.c_uint64)]
+
+
+KERNEL_GENERAL, KERNEL_LL, KERNEL_STAGED, KERNEL_WAVE = 0, 1, 2, 3
+
+
+class InFlight(C.Structure):
+    _fields_ = [("stream", C.c_uint64), ("wgs", C.c_int32), ("capacity", C.c_int32)]
 
 
 class TuneEntry(C.Structure):
@@ -109,6 +121,7 @@ def lib() -> C.CDLL:
         L.gc3_comm_create.argtypes = [C.c_void_p, C.POINTER(CommConfig), C.POINTER(C.c_void_p)]
         L.gc3_comm_info_get.argtypes = [C.c_void_p, C.POINTER(CommInfo)]
         L.gc3_comm_bind.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t]
+        L.gc3_comm_launch_info.argtypes = [C.c_void_p, C.c_size_t, C.c_int, C.POINTER(LaunchInfo)]
         L.gc3_comm_run.argtypes = [C.c_void_p, C.c_size_t, C.c_int, C.c_int, C.c_void_p]
         L.gc3_comm_algorithmic_bytes.argtypes = [C.c_void_p, C.c_size_t, C.c_int, C.POINTER(C.c_uint64)]
         L.gc3_comm_status.argtypes = [C.c_void_p]
@@ -119,6 +132,7 @@ def lib() -> C.CDLL:
                                     C.POINTER(CommConfig), C.POINTER(TuneReport)]
         L.gc3_run_static.argtypes = [C.c_void_p, C.POINTER(CommConfig), C.POINTER(C.c_void_p), C.POINTER(C.c_void_p),
                                      C.POINTER(C.c_void_p), C.POINTER(C.c_size_t), C.c_size_t, C.c_int, C.c_int, C.c_void_p]
+        L.gc3_residency_plan.argtypes = [C.POINTER(InFlight), C.c_int, C.c_uint64, C.c_int32, C.c_int32, C.POINTER(C.c_int32)]
         L.gc3_selector_create.argtypes = [C.POINTER(C.c_void_p)]
         L.gc3_selector_add.argtypes = [C.c_void_p, C.c_void_p, C.c_uint64, C.c_uint64]
         L.gc3_selector_run.argtypes = [C.c_void_p, C.c_size_t, C.c_int, C.c_int, C.c_void_p, C.POINTER(C.c_int)]
@@ -190,6 +204,12 @@ def gc3_comm_bind(comm: C.c_void_p, rank: int, input_ptr: int, output_ptr: Optio
                                C.c_void_p(scratch_ptr or 0), scratch_bytes))
 
 
+def gc3_comm_launch_info(comm: C.c_void_p, elems_per_rank: int, dtype: int) -> LaunchInfo:
+    info = LaunchInfo()
+    _check(lib().gc3_comm_launch_info(comm, elems_per_rank, dtype, C.byref(info)))
+    return info
+
+
 def gc3_comm_run(comm: C.c_void_p, elems_per_rank: int, dtype: int, op: int = GC3_SUM, stream: int = 0) -> None:
     _check(lib().gc3_comm_run(comm, elems_per_rank, dtype, op, C.c_void_p(stream)))
 
@@ -229,6 +249,17 @@ def gc3_run_static(prog: C.c_void_p, cfg: Optional[CommConfig], inputs, outputs,
     sizes = None if scratch_bytes is None else (C.c_size_t * n)(*scratch_bytes)
     _check(lib().gc3_run_static(prog, C.byref(cfg) if cfg is not None else None, ptrs(inputs), ptrs(outputs),
                                 ptrs(scratch), sizes, elems_per_rank, dtype, op, C.c_void_p(stream)))
+
+
+def gc3_residency_plan(inflight, stream: int, wgs: int, capacity: int):
+    """inflight: sequence of (stream, wgs, capacity), oldest first.  Returns the list of 0/1 marks."""
+    n = len(inflight)
+    arr = (InFlight * max(n, 1))(*[InFlight(*e) for e in inflight])
+    marks = (C.c_int32 * max(n, 1))()
+    rc = lib().gc3_residency_plan(arr, n, stream, wgs, capacity, marks)
+    if rc < 0:
+        raise Gc3Error(rc, gc3_last_error())
+    return list(marks)[:n]
 
 
 def gc3_selector_create() -> C.c_void_p:

@@ -12,7 +12,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB_DIR = os.path.join(HERE, "lib")
 LIB_PATH = os.path.join(LIB_DIR, "libgc3.so")
-SOURCES = ["program.cpp", "plan.cpp", "comm.cpp", "interp_kernel.hip"]
+SOURCES = ["program.cpp", "plan.cpp", "residency.cpp", "comm.cpp", "interp_kernel.hip"]
 
 
 def build(verbose: bool = False, defines: Sequence[str] = (), out: Optional[str] = None) -> str:

@@ -16,10 +16,11 @@
 #include "device_tables.h"
 #include "plan.h"
 #include "program.h"
+#include "residency.h"
 
 namespace gc3 {
-int launch_interpreter(int dtype, bool coherent_user, bool ll, unsigned grid, unsigned block, void* stream, const KParams& p);
-int interpreter_occupancy(unsigned block, int* out);
+int launch_interpreter(int dtype, bool coherent_user, int mode, unsigned grid, unsigned block, void* stream, const KParams& p);
+int interpreter_occupancy(unsigned block, bool staged, int* out);
 int static_scratch_ptr(void** out);
 int launch_fill_zero(void* ptr, size_t bytes, void* stream);
 }  // namespace gc3
@@ -46,6 +47,7 @@ struct gc3_comm {
   bool inplace = false;
   bool has_deps = false;    // some instruction waits on another thread block's semaphore
   bool debug_hold = false;  // failure-path test facility
+  bool lds_stage = false;   // FIFO payload of the receiving instructions goes through LDS
   uint64_t min_lane_bytes = 8192;
   uint64_t ll_max_lane_bytes = 8192;
   uint32_t ll_slot_bytes = 0;
@@ -73,15 +75,18 @@ struct gc3_comm {
   std::vector<void*> bufs;            // [rank*3 + buffer]
   std::vector<size_t> scratch_bytes;  // capacity bound per rank
   std::vector<char> bound;
-  bool bufs_dirty = true;
   bool poisoned = false;
-  uint64_t run_number = 0;
+  hipEvent_t done = nullptr;          // recorded after every launch outside stream capture
+  bool done_recorded = false;
+  hipStream_t aux = nullptr;          // non-blocking stream for the status read-back (stalls no other stream)
 
   ~gc3_comm() {
     // best effort; errors on teardown are ignored
     for (void* q : {(void*)d_instrs, (void*)d_deps, (void*)d_wgs, (void*)d_fibers, (void*)d_bufs,
                     (void*)d_fifo, (void*)d_ll_fifo, (void*)d_flags, (void*)d_sems, (void*)d_error})
       if (q) (void)hipFree(q);
+    if (done) (void)hipEventDestroy(done);
+    if (aux) (void)hipStreamDestroy(aux);
   }
 };
 
@@ -95,15 +100,60 @@ int upload(T** dptr, const std::vector<T>& host) {
   return GC3_OK;
 }
 
+// ---- per-device ledger of runs in flight (see residency.h) -------------------------------------------------
+struct LedgerEntry {
+  const gc3_comm* owner;
+  hipStream_t stream;
+  int32_t wgs, capacity;
+  hipEvent_t done;       // the owner's event, recorded after the run
+};
+constexpr int kMaxLedgerDevices = 64;
+std::vector<LedgerEntry> g_ledger[kMaxLedgerDevices];
+std::mutex g_ledger_lock;
+
+void ledger_forget(const gc3_comm* c, int device) {
+  if (device < 0 || device >= kMaxLedgerDevices) return;
+  std::lock_guard<std::mutex> hold(g_ledger_lock);
+  auto& v = g_ledger[device];
+  v.erase(std::remove_if(v.begin(), v.end(), [&](const LedgerEntry& e) { return e.owner == c; }), v.end());
+}
+
+// Before a launch of `wgs` workgroups on `st` (the caller holds g_ledger_lock from here until it has recorded
+// the run's event and entered the run with ledger_enter): drop finished runs and make `st` wait for the runs on
+// other streams that could not be resident beside this one.
+int ledger_make_room(const gc3_comm* c, int device, hipStream_t st, int32_t wgs, int32_t capacity) {
+  if (device < 0 || device >= kMaxLedgerDevices) return GC3_OK;
+  auto& v = g_ledger[device];
+  // this communicator's earlier run is ordered before the new one by the caller (runs of one communicator
+  // must not overlap); other owners' runs that have completed no longer occupy the device
+  v.erase(std::remove_if(v.begin(), v.end(), [&](const LedgerEntry& e) {
+            return e.owner == c || hipEventQuery(e.done) == hipSuccess;
+          }), v.end());
+  std::vector<InFlightRun> runs;
+  for (const LedgerEntry& e : v) runs.push_back({(uint64_t)(uintptr_t)e.stream, e.wgs, e.capacity});
+  std::vector<char> wait_on;
+  if (residency_waits(runs, (uint64_t)(uintptr_t)st, wgs, capacity, wait_on) > 0)
+    for (size_t i = 0; i < v.size(); ++i)
+      if (wait_on[i]) HIP_TRY(hipStreamWaitEvent(st, v[i].done, 0));
+  return GC3_OK;
+}
+
+void ledger_enter(const gc3_comm* c, int device, hipStream_t st, int32_t wgs, int32_t capacity, hipEvent_t done) {
+  if (device < 0 || device >= kMaxLedgerDevices) return;
+  g_ledger[device].push_back({c, st, wgs, capacity, done});
+}
+
 // What one run launches, as far as it depends on the chunk size only: active lanes, tile, protocol, grid.
 struct Launch {
   KParams p{};
   unsigned grid = 0, block = 0;
   bool ll = false;
+  int mode = 0;              // kernel variant: 0 general, 1 LL, 2 payload staged through LDS, 3 wavefront-level
   uint64_t lane_share = 0;   // largest share a lane has of a chunk, bytes
 };
 
-void shape_run(const gc3_comm_info& info, uint64_t cb, uint64_t min_lane_bytes, uint64_t ll_max_lane_bytes, Launch& L) {
+void shape_run(const gc3_comm_info& info, uint64_t cb, uint64_t min_lane_bytes, uint64_t ll_max_lane_bytes, bool lds_stage,
+               Launch& L) {
   KParams& p = L.p;
   p.chunk_bytes = cb;
   p.W = (uint32_t)info.team_width;
@@ -145,6 +195,12 @@ void shape_run(const gc3_comm_info& info, uint64_t cb, uint64_t min_lane_bytes, 
   // (measured 2-3 % faster up to 8 KiB per lane, slower above)
   L.block = (unsigned)info.wg_size;
   if (L.block > 128 && lane_share <= 8192) L.block = 128;
+  // Instantiation: LL, or payload staged through LDS, or - for workgroups of one wavefront that each run one
+  // fiber - the wavefront-level interpreter, or the general one.
+  L.mode = 0;
+  if (L.ll) L.mode = 1;
+  else if (lds_stage) L.mode = 2;
+  else if (L.block == 64 && (uint32_t)info.max_fibers_per_wg <= p.nsplit) L.mode = 3;
 }
 
 }  // namespace
@@ -166,7 +222,7 @@ int gc3_comm_create(const gc3_program* prog, const gc3_comm_config* cfg_in, gc3_
   HIP_TRY(hipGetDeviceProperties(&prop, c->device));
   int occ = 0;
   {
-    int e = interpreter_occupancy((unsigned)cfg.wg_size, &occ);
+    int e = interpreter_occupancy((unsigned)cfg.wg_size, cfg.lds_stage != 0, &occ);
     if (e != 0) return hip_fail((hipError_t)e, "hipOccupancyMaxActiveBlocksPerMultiprocessor");
   }
   // all workgroups wait on each other, so the whole grid has to be resident at once (Section 6.2)
@@ -196,6 +252,8 @@ int gc3_comm_create(const gc3_program* prog, const gc3_comm_config* cfg_in, gc3_
   HIP_TRY(hipMemset(c->d_sems, 0, c->sems_bytes));
   HIP_TRY(hipMemset(c->d_error, 0, 256));
   HIP_TRY(hipDeviceSynchronize());
+  HIP_TRY(hipEventCreateWithFlags(&c->done, hipEventDisableTiming));
+  HIP_TRY(hipStreamCreateWithFlags(&c->aux, hipStreamNonBlocking));
 
   c->ranks = R;
   c->in_chunks = prog->in_chunks;
@@ -204,6 +262,7 @@ int gc3_comm_create(const gc3_program* prog, const gc3_comm_config* cfg_in, gc3_
   c->algorithmic_chunks = plan.algorithmic_chunks;
   c->has_deps = !plan.deps.empty();
   c->debug_hold = cfg.debug_hold != 0;
+  c->lds_stage = cfg.lds_stage != 0;
   c->min_lane_bytes = (uint64_t)cfg.min_lane_bytes;
   c->ll_max_lane_bytes = (uint64_t)cfg.ll_max_lane_bytes;
   c->ll_slot_bytes = (uint32_t)(2ull * plan.max_count * (uint64_t)cfg.ll_max_lane_bytes);
@@ -239,12 +298,17 @@ int gc3_comm_bind(gc3_comm* comm, int rank, void* input, void* output, void* scr
   if (comm->scratch_chunks[rank] > 0 && !scratch) { set_error("rank uses scratch chunks but scratch is null"); return GC3_ERR_ARG; }
   for (void* p : {input, output, scratch})
     if ((uintptr_t)p % 16) { set_error("buffers must be 16-byte aligned"); return GC3_ERR_ARG; }
+  // The device-side pointer table is updated here, synchronously, so that a run has nothing to copy and
+  // its kernel arguments never change; an earlier run of this communicator still reads the table, so it is
+  // waited for first.
+  if (comm->done_recorded) HIP_TRY(hipEventSynchronize(comm->done));
+  void* triple[3] = {input, output, scratch};
+  HIP_TRY(hipMemcpy(comm->d_bufs + (size_t)rank * 3, triple, sizeof(triple), hipMemcpyHostToDevice));
   comm->bufs[(size_t)rank * 3 + 0] = input;
   comm->bufs[(size_t)rank * 3 + 1] = output;
   comm->bufs[(size_t)rank * 3 + 2] = scratch;
   comm->scratch_bytes[rank] = scratch ? scratch_bytes : 0;
   comm->bound[rank] = 1;
-  comm->bufs_dirty = true;
   return GC3_OK;
 }
 
@@ -268,6 +332,24 @@ int gc3_comm_algorithmic_bytes(const gc3_comm* comm, size_t elems_per_rank, gc3_
   return GC3_OK;
 }
 
+int gc3_comm_launch_info(const gc3_comm* comm, size_t elems_per_rank, gc3_dtype dtype, gc3_launch_info* out) {
+  if (!comm || !out) { set_error("null argument"); return GC3_ERR_ARG; }
+  uint64_t cb = 0;
+  int rc = chunk_bytes_of(comm, elems_per_rank, dtype, &cb);
+  if (rc != GC3_OK) return rc;
+  Launch L;
+  shape_run(comm->info, cb, comm->min_lane_bytes, comm->ll_max_lane_bytes, comm->lds_stage, L);
+  *out = gc3_launch_info{};
+  out->grid = (elems_per_rank == 0 || comm->info.grid == 0) ? 0 : (int32_t)L.grid;
+  out->wg_size = (int32_t)L.block;
+  out->active_lanes = (int32_t)L.p.W_active;
+  out->split = (int32_t)L.p.nsplit;
+  out->tile_bytes = (int32_t)L.p.tile_bytes;
+  out->kernel = L.mode;
+  out->lane_bytes = L.lane_share;
+  return GC3_OK;
+}
+
 int gc3_comm_run(gc3_comm* comm, size_t elems_per_rank, gc3_dtype dtype, gc3_redop op, void* hip_stream) {
   if (!comm) { set_error("null communicator"); return GC3_ERR_ARG; }
   if (op != GC3_SUM) { set_error("unknown reduction"); return GC3_ERR_ARG; }
@@ -287,12 +369,9 @@ int gc3_comm_run(gc3_comm* comm, size_t elems_per_rank, gc3_dtype dtype, gc3_red
   HIP_TRY(hipGetDevice(&dev));
   if (dev != comm->device) { set_error("communicator belongs to another device"); return GC3_ERR_ARG; }
   hipStream_t st = (hipStream_t)hip_stream;
-  if (comm->bufs_dirty) {
-    HIP_TRY(hipMemcpyAsync(comm->d_bufs, comm->bufs.data(), comm->bufs.size() * sizeof(void*), hipMemcpyHostToDevice, st));
-    // the host table may change right after this call returns: make the copy complete first
-    HIP_TRY(hipStreamSynchronize(st));
-    comm->bufs_dirty = false;
-  }
+  hipStreamCaptureStatus capture = hipStreamCaptureStatusNone;
+  HIP_TRY(hipStreamIsCapturing(st, &capture));
+  const bool capturing = capture != hipStreamCaptureStatusNone;
   Launch L;
   KParams& p = L.p;
   p.instrs = comm->d_instrs;
@@ -305,12 +384,16 @@ int gc3_comm_run(gc3_comm* comm, size_t elems_per_rank, gc3_dtype dtype, gc3_red
   p.sems = comm->d_sems;
   p.error = comm->d_error;
   p.hold = comm->debug_hold ? comm->d_error + 32 : nullptr;   // a word of the zeroed error block nobody writes
-  p.run_base = (++comm->run_number) << 32;
   p.spin_limit_ticks = comm->spin_limit_ticks;
-  shape_run(comm->info, cb, comm->min_lane_bytes, comm->ll_max_lane_bytes, L);
+  shape_run(comm->info, cb, comm->min_lane_bytes, comm->ll_max_lane_bytes, comm->lds_stage, L);
   p.ll_fifo = comm->d_ll_fifo;
   p.ll_slot_bytes = comm->ll_slot_bytes;
   if (L.ll) {
+    if (capturing) {
+      set_error("a run under the LL protocol cannot be captured: its message numbers are kernel arguments that change "
+                "from run to run");
+      return GC3_ERR_ARG;
+    }
     // message numbers of this run: [ll_next + 1, ll_next + messages]; their low 32 bits are the flags and
     // must never be 0 (the value untouched slot memory holds), so a range never crosses a multiple of 2^32
     const uint64_t tiles = (L.lane_share + p.tile_bytes - 1) / p.tile_bytes;
@@ -319,18 +402,33 @@ int gc3_comm_run(gc3_comm* comm, size_t elems_per_rank, gc3_dtype dtype, gc3_red
     p.ll_base = (uint32_t)comm->ll_next;
     comm->ll_next += messages;
   }
-  const bool ll = L.ll;
-  const unsigned grid = L.grid, block = L.block;
-  int e = launch_interpreter((int)dtype, comm->has_deps, ll, grid, block, hip_stream, p);
+  // Outside capture the run enters the device's ledger: its stream first waits for runs of other communicators
+  // on other streams beside which this grid could not be resident.  A captured launch is replayed at times
+  // the library does not see: keeping such launches apart from other communicators' runs is the caller's job.
+  std::unique_lock<std::mutex> ledger(g_ledger_lock, std::defer_lock);
+  if (!capturing) {
+    ledger.lock();
+    rc = ledger_make_room(comm, comm->device, st, (int32_t)L.grid, comm->info.max_resident_wgs);
+    if (rc != GC3_OK) return rc;
+  }
+  int e = launch_interpreter((int)dtype, comm->has_deps, L.mode, L.grid, L.block, hip_stream, p);
   if (e != 0) return hip_fail((hipError_t)e, "interpreter launch");
+  if (!capturing) {
+    HIP_TRY(hipEventRecord(comm->done, st));
+    comm->done_recorded = true;
+    ledger_enter(comm, comm->device, st, (int32_t)L.grid, comm->info.max_resident_wgs, comm->done);
+  }
   return GC3_OK;
 }
 
 int gc3_comm_status(gc3_comm* comm) {
   if (!comm) { set_error("null communicator"); return GC3_ERR_ARG; }
-  HIP_TRY(hipDeviceSynchronize());
+  // wait for this communicator's last run only, and read the error word on a stream of its own: no other
+  // stream of the process is stalled
+  if (comm->done_recorded) HIP_TRY(hipEventSynchronize(comm->done));
   uint32_t err = 0;
-  HIP_TRY(hipMemcpy(&err, comm->d_error, sizeof(err), hipMemcpyDeviceToHost));
+  HIP_TRY(hipMemcpyAsync(&err, comm->d_error, sizeof(err), hipMemcpyDeviceToHost, comm->aux));
+  HIP_TRY(hipStreamSynchronize(comm->aux));
   if (err != 0) {
     comm->poisoned = true;
     set_error("a workgroup waited longer than the spin limit (run abandoned)");
@@ -352,7 +450,10 @@ int gc3_comm_reset(gc3_comm* comm) {
 
 void gc3_comm_destroy(gc3_comm* comm) {
   if (!comm) return;
-  (void)hipDeviceSynchronize();
+  // the last run launched through the library must have left the device before its state is freed (a run
+  // replayed from a captured graph is the caller's to wait for)
+  if (comm->done_recorded) (void)hipEventSynchronize(comm->done);
+  ledger_forget(comm, comm->device);
   delete comm;
 }
 
@@ -503,7 +604,7 @@ struct StaticDevice {
   bool ready = false;
   void* scratch = nullptr;      // this device's copy of the static array
   int cus = 0;
-  int occupancy[4] = {0, 0, 0, 0};   // workgroups per compute unit for 64, 128, 256, 512 threads
+  int occupancy[2][4] = {};     // [LDS-staged or not][64, 128, 256, 512 threads]: workgroups per compute unit
 };
 constexpr int kMaxStaticDevices = 64;
 StaticDevice g_static[kMaxStaticDevices];
@@ -519,10 +620,12 @@ int static_device(int dev, const StaticDevice** out) {
     if (e != 0) return hip_fail((hipError_t)e, "hipGetSymbolAddress(static scratch)");
     int cus = 0;
     HIP_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
-    int k = 0;
-    for (unsigned block : {64u, 128u, 256u, 512u}) {
-      e = interpreter_occupancy(block, &d.occupancy[k++]);
-      if (e != 0) return hip_fail((hipError_t)e, "hipOccupancyMaxActiveBlocksPerMultiprocessor");
+    for (int staged = 0; staged < 2; ++staged) {
+      int k = 0;
+      for (unsigned block : {64u, 128u, 256u, 512u}) {
+        e = interpreter_occupancy(block, staged != 0, &d.occupancy[staged][k++]);
+        if (e != 0) return hip_fail((hipError_t)e, "hipOccupancyMaxActiveBlocksPerMultiprocessor");
+      }
     }
     d.scratch = ptr;
     d.cus = cus;
@@ -581,7 +684,7 @@ extern "C" int gc3_run_static(const gc3_program* prog, const gc3_comm_config* cf
   HIP_TRY(hipGetDevice(&dev));
   const StaticDevice* sd = nullptr;
   if ((rc = static_device(dev, &sd)) != GC3_OK) return rc;
-  const int occ = sd->occupancy[cfg.wg_size == 64 ? 0 : cfg.wg_size == 128 ? 1 : cfg.wg_size == 256 ? 2 : 3];
+  const int occ = sd->occupancy[cfg.lds_stage ? 1 : 0][cfg.wg_size == 64 ? 0 : cfg.wg_size == 128 ? 1 : cfg.wg_size == 256 ? 2 : 3];
 
   // Plan with the FIFOs bounded by what the static array can hold; tables, flags and semaphores are small and
   // get a fixed reserve that is checked exactly below.
@@ -647,10 +750,10 @@ extern "C" int gc3_run_static(const gc3_program* prog, const gc3_comm_config* cf
   p.sems = (uint64_t*)(base + off_sems);
   p.error = (uint32_t*)base;
   p.hold = cfg.debug_hold ? (const uint32_t*)(base + 128) : nullptr;
-  p.run_base = 1ull << 32;                 // flags were just cleared: every call is run number one
   p.spin_limit_ticks = cfg.spin_limit_us * 100ull;
-  shape_run(plan.info, cb, (uint64_t)cfg.min_lane_bytes, (uint64_t)cfg.ll_max_lane_bytes, L);
-  e = launch_interpreter((int)dtype, !plan.deps.empty(), false, L.grid, L.block, hip_stream, p);
+  shape_run(plan.info, cb, (uint64_t)cfg.min_lane_bytes, (uint64_t)cfg.ll_max_lane_bytes, cfg.lds_stage != 0, L);
+  // (epochs were cleared with the flags: every call is the first run)
+  e = launch_interpreter((int)dtype, !plan.deps.empty(), L.mode, L.grid, L.block, hip_stream, p);
   if (e != 0) return hip_fail((hipError_t)e, "interpreter launch");
   return GC3_OK;
 }

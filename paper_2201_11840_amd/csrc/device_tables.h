@@ -62,10 +62,10 @@ struct KParams {
   unsigned char* fifo;     // [(conn*W + lane) * slots + slot] * slot_bytes
   unsigned char* ll_fifo;  // the same for the LL protocol, slots of ll_slot_bytes (data + flag pairs only)
   uint64_t* flags;         // [((conn*W + lane)*2 + {0 tail, 1 head}) * kFlagStrideWords]
-  uint64_t* sems;          // [(tb*W + lane) * kFlagStrideWords]
+  uint64_t* sems;          // [(tb*W + lane) * kFlagStrideWords]: word 0 the semaphore, word 1 the fiber's epoch
+                           // (runs it has completed); flag values of a run lie above (epoch + 1) << 32
   uint32_t* error;         // 0 = fine, else a gc3_status (negated) set by the first failing workgroup
   const uint32_t* hold;    // null, or a start word every workgroup waits for (failure-path tests)
-  uint64_t run_base;       // run number << 32; all flag values of this run lie above it
   uint64_t chunk_bytes;
   uint64_t spin_limit_ticks;  // of the 100 MHz wall clock
   uint32_t W, slots, tile_bytes, slot_bytes;

@@ -13,7 +13,11 @@
 // reduction order are those of the program.
 //
 // Flag protocol (Section 6.1, remote buffers with s slots).  All flags are 64-bit and only grow:
-// value = run_base + n, where run_base = run number << 32.
+// value = run_base + n, where run_base = (epoch + 1) << 32 and the epoch of a fiber is the number of runs it
+// has completed, kept in device memory next to its semaphore (a fiber reads it when it starts and stores
+// epoch + 1 when it is done).  The fibers of one lane take part in exactly the same runs, so both ends of a
+// connection and both ends of a dependency agree on the epoch without the host passing a run number: the
+// kernel's arguments are the same for every run of one size, which lets a launch be captured in a graph.
 //   tail[conn, lane]  written by the sender:   messages published in this run
 //   head[conn, lane]  written by the receiver: messages consumed in this run
 //   sem[tb, lane]     written by the thread block: tile * ninstr + step + 1 of the latest
@@ -87,39 +91,11 @@ __device__ __forceinline__ u32x4 add_vec(u32x4 a, u32x4 b) {
 // chunks another one wrote in the same run (template parameter COH).  With these policies no bulk L2
 // write-back / invalidate (agent-scope fence) is needed anywhere in the kernel.
 constexpr int kPolNt = 2, kPolSc1 = 16;   // (bit 0 would be sc0)
-#ifndef GC3_POL_SLOT_LD
-#define GC3_POL_SLOT_LD (kPolSc1)
-#endif
-#ifndef GC3_POL_SLOT_ST
-#define GC3_POL_SLOT_ST (kPolSc1)
-#endif
-#ifndef GC3_POL_USER_LD
-#define GC3_POL_USER_LD (kPolNt)
-#endif
-#ifndef GC3_POL_USER_ST
-#define GC3_POL_USER_ST (kPolSc1)
-#endif
-#ifndef GC3_POL_USER_LD_COH
-#define GC3_POL_USER_LD_COH (kPolSc1 | kPolNt)
-#endif
-#ifndef GC3_POL_USER_ST_COH
-#define GC3_POL_USER_ST_COH (kPolSc1 | kPolNt)
-#endif
-// 1 = conservative build for A/B measurements: every wait ends with an agent-scope acquire fence and
-// every publish starts with an agent-scope release fence (bulk L2 invalidate / write-back).
-#ifndef GC3_CONSERVATIVE_FENCES
-#define GC3_CONSERVATIVE_FENCES 0
-#endif
-#ifndef GC3_UNROLL
-#define GC3_UNROLL 4
-#endif
-// 1 = stage the FIFO payload of the receiving instructions through LDS with direct-to-LDS buffer loads
-// (no VGPRs held by loads in flight).  Measured on MI355X it does not beat the register path (the
-// interpreter is bound by the fabric, not by registers), so it is off; kept for A/B measurements.
-#ifndef GC3_LDS_STAGE
-#define GC3_LDS_STAGE 0
-#endif
-constexpr uint32_t kStageBytes = 32768;   // LDS staging area per workgroup
+constexpr int kSlotLd = kPolSc1, kSlotSt = kPolSc1;
+constexpr int kUserLd = kPolNt, kUserSt = kPolSc1;
+constexpr int kUserLdCoh = kPolSc1 | kPolNt, kUserStCoh = kPolSc1 | kPolNt;
+constexpr int kUnroll = 4;                // 128-bit loads per stream in flight before the adds and stores
+constexpr uint32_t kStageBytes = 16384;   // LDS staging area per workgroup (staged variant only): one sweep of 256 threads
 
 typedef __amdgpu_buffer_rsrc_t rsrc_t;
 
@@ -135,21 +111,21 @@ __device__ __forceinline__ rsrc_t make_rsrc(const void* base, uint32_t bytes) {
 template <bool IN1, bool OUT1, int DT, int P_IN0, int P_IN1, int P_OUT0, int P_OUT1>
 __device__ __forceinline__ void move_tile(rsrc_t in0, rsrc_t in1, rsrc_t out0, rsrc_t out1,
                                           uint32_t nvec, uint32_t tid, uint32_t nthreads) {
-  const uint32_t step = nthreads * GC3_UNROLL;
+  const uint32_t step = nthreads * kUnroll;
   for (uint32_t base = tid; base < nvec; base += step) {
-    u32x4 a[GC3_UNROLL], b[GC3_UNROLL];
+    u32x4 a[kUnroll], b[kUnroll];
 #pragma unroll
-    for (int u = 0; u < GC3_UNROLL; ++u)
+    for (int u = 0; u < kUnroll; ++u)
       a[u] = __builtin_amdgcn_raw_buffer_load_b128(in0, (base + u * nthreads) << 4, 0, P_IN0);
     if (IN1) {
 #pragma unroll
-      for (int u = 0; u < GC3_UNROLL; ++u)
+      for (int u = 0; u < kUnroll; ++u)
         b[u] = __builtin_amdgcn_raw_buffer_load_b128(in1, (base + u * nthreads) << 4, 0, P_IN1);
 #pragma unroll
-      for (int u = 0; u < GC3_UNROLL; ++u) a[u] = add_vec<DT>(a[u], b[u]);
+      for (int u = 0; u < kUnroll; ++u) a[u] = add_vec<DT>(a[u], b[u]);
     }
 #pragma unroll
-    for (int u = 0; u < GC3_UNROLL; ++u) {
+    for (int u = 0; u < kUnroll; ++u) {
       __builtin_amdgcn_raw_buffer_store_b128(a[u], out0, (base + u * nthreads) << 4, 0, P_OUT0);
       if (OUT1) __builtin_amdgcn_raw_buffer_store_b128(a[u], out1, (base + u * nthreads) << 4, 0, P_OUT1);
     }
@@ -171,23 +147,23 @@ __device__ __forceinline__ void move_tile_staged(rsrc_t in0, rsrc_t in1, rsrc_t 
     for (uint32_t k = 0; k < n; k += nthreads)
       __builtin_amdgcn_raw_ptr_buffer_load_lds(in0, (lds_void*)(stage + ((k + wave_first) << 4)), 16,
                                                (r0 + k + tid) << 4, 0, 0, P_IN0);
-    const uint32_t step = nthreads * GC3_UNROLL;
+    const uint32_t step = nthreads * kUnroll;
     for (uint32_t base = tid; base < n; base += step) {
-      u32x4 a[GC3_UNROLL], b[GC3_UNROLL];
+      u32x4 a[kUnroll], b[kUnroll];
       if (IN1) {
 #pragma unroll
-        for (int u = 0; u < GC3_UNROLL; ++u)
+        for (int u = 0; u < kUnroll; ++u)
           b[u] = __builtin_amdgcn_raw_buffer_load_b128(in1, (r0 + base + u * nthreads) << 4, 0, P_IN1);
       }
       __builtin_amdgcn_s_waitcnt(0);                           // staged loads (and in1) have landed
 #pragma unroll
-      for (int u = 0; u < GC3_UNROLL; ++u) {
+      for (int u = 0; u < kUnroll; ++u) {
         const uint32_t i = base + u * nthreads;
         a[u] = i < n ? *(const u32x4*)(stage + (i << 4)) : u32x4{0, 0, 0, 0};
         if (IN1) a[u] = add_vec<DT>(a[u], b[u]);
       }
 #pragma unroll
-      for (int u = 0; u < GC3_UNROLL; ++u) {
+      for (int u = 0; u < kUnroll; ++u) {
         __builtin_amdgcn_raw_buffer_store_b128(a[u], out0, (r0 + base + u * nthreads) << 4, 0, P_OUT0);
         if (OUT1) __builtin_amdgcn_raw_buffer_store_b128(a[u], out1, (r0 + base + u * nthreads) << 4, 0, P_OUT1);
       }
@@ -292,19 +268,153 @@ constexpr uint32_t kFiberDone = 0xffffffffu;
 __device__ __forceinline__ uint32_t uni(uint32_t v) { return __builtin_amdgcn_readfirstlane(v); }
 __device__ __forceinline__ uint64_t uni64(uint64_t v) { return ((uint64_t)uni((uint32_t)(v >> 32)) << 32) | uni((uint32_t)v); }
 
+namespace {
+
+// Protocol / payload path of an interpreter instantiation.
+constexpr int kSimple = 0;   // payload, completion wait, separate flag; payload moves through registers
+constexpr int kLL = 1;       // every 8 bytes carry 4 bytes of data and a 4-byte flag
+constexpr int kStaged = 2;   // simple protocol, FIFO payload of the receiving instructions staged through LDS
+
+__device__ __forceinline__ uint64_t* flag_of(const KParams& p, int32_t conn, uint32_t lane, uint32_t which) {
+  return p.flags + ((uint64_t)((uint32_t)conn * p.W + lane) * 2 + which) * kFlagStrideWords;
+}
+__device__ __forceinline__ uint64_t* sem_of(const KParams& p, uint32_t tb, uint32_t lane) {
+  return p.sems + (uint64_t)(tb * p.W + lane) * kFlagStrideWords;
+}
+
+// Failure-path test facility: wait (bounded by the spin limit) for a start word that the host never sets.
+// Called by one thread; returns false when the run is abandoned.
+__device__ __forceinline__ bool hold_wait(const KParams& p) {
+  const uint64_t start = wall_clock64();
+  while (__hip_atomic_load(p.hold, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0) {
+    __builtin_amdgcn_s_sleep(8);
+    if (__hip_atomic_load(p.error, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) return false;
+    if (wall_clock64() - start > p.spin_limit_ticks) {
+      atomicCAS(p.error, 0u, (uint32_t)(-GC3_ERR_TIMEOUT));
+      return false;
+    }
+  }
+  return true;
+}
+
+// The waits of one instruction, taken by the lanes of ONE wavefront (all 64 call this): lane 0 polls the tail
+// flag of the receive connection (tail_recv, may be null), lane 1 the head flag of the send connection
+// (head_send, may be null), lanes 2.. one dependency's semaphore each, in rounds of 64 when an instruction has
+// more than 62 dependencies.  block: spin (bounded by the spin limit) until every flag has reached its value;
+// otherwise a single look.  Returns 1 = ready, 0 = not ready, -1 = the run is abandoned.  `seen` is the last
+// value this lane loaded (lane 1: the head flag, meaningful when ndeps <= 62).
+__device__ __forceinline__ int poll_flags(const KParams& p, uint32_t lane_id, bool block,
+                                          const uint64_t* tail_recv, uint64_t want_tail,
+                                          const uint64_t* head_send, uint64_t want_head,
+                                          uint32_t dep_begin, uint32_t ndeps, uint32_t lane,
+                                          uint64_t run_base, uint32_t t, uint64_t& seen) {
+  int res = 1;
+  seen = 0;
+  const uint32_t total = 2 + ndeps;
+  for (uint32_t it0 = 0; it0 < total && res == 1; it0 += 64) {
+    const uint32_t it = it0 + lane_id;
+    const uint64_t* ptr = nullptr;
+    uint64_t want = 0;
+    if (it == 0) {
+      ptr = tail_recv; want = want_tail;
+    } else if (it == 1) {
+      ptr = head_send; want = want_head;
+    } else if (it < total) {
+      const DDep d = p.deps[dep_begin + it - 2];
+      ptr = sem_of(p, d.tb, lane);
+      want = run_base + (uint64_t)t * d.ninstr + d.step + 1;
+    }
+    bool pending = ptr != nullptr;
+    const uint64_t start = wall_clock64();
+    uint32_t spins = 0;
+    for (;;) {
+      if (pending) {
+        seen = load_flag(ptr);
+        if (seen >= want) pending = false;
+      }
+      if (!__any(pending)) break;
+      if (!block) { res = 0; break; }
+      if (++spins > 16) __builtin_amdgcn_s_sleep(1);     // poll hard first, politely later
+      if ((spins & 255u) == 0) {
+        if (__hip_atomic_load(p.error, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) { res = -1; break; }
+        if (wall_clock64() - start > p.spin_limit_ticks) {
+          atomicCAS(p.error, 0u, (uint32_t)(-GC3_ERR_TIMEOUT));
+          res = -1;
+          break;
+        }
+      }
+    }
+  }
+  return res;
+}
+
+// One tile of one instruction under the simple protocol: `count` pieces of `len` bytes, piece j at
+// srcb / dstb + j * chunk_bytes in the user buffers and packed back to back in the FIFO slots.
+template <int DT, bool COH, bool STAGE>
+__device__ __forceinline__ void move_simple(uint32_t op, uint32_t count, unsigned char* srcb, unsigned char* dstb,
+                                            unsigned char* rslot, unsigned char* sslot, uint32_t len,
+                                            uint64_t chunk_bytes, uint32_t tid, uint32_t nthreads, unsigned char* stage) {
+  constexpr int UL = COH ? kUserLdCoh : kUserLd, US = COH ? kUserStCoh : kUserSt;
+  constexpr int SL = kSlotLd, SS = kSlotSt;
+  const uint32_t nvec = len >> 4;
+  for (uint32_t j = 0; j < count; ++j) {
+    const rsrc_t src = make_rsrc(srcb + (uint64_t)j * chunk_bytes, srcb ? len : 0);
+    const rsrc_t dst = make_rsrc(dstb + (uint64_t)j * chunk_bytes, dstb ? len : 0);
+    const rsrc_t rs = make_rsrc(rslot + (uint64_t)j * len, rslot ? len : 0);
+    const rsrc_t ss = make_rsrc(sslot + (uint64_t)j * len, sslot ? len : 0);
+    switch (op) {
+      case GC3_OP_SEND:   move_tile<false, false, DT, UL, 0, SS, 0>(src, src, ss, ss, nvec, tid, nthreads); break;
+      case GC3_OP_COPY:   move_tile<false, false, DT, UL, 0, US, 0>(src, src, dst, dst, nvec, tid, nthreads); break;
+      case GC3_OP_REDUCE: move_tile<true, false, DT, UL, UL, US, 0>(dst, src, dst, dst, nvec, tid, nthreads); break;
+      default:
+        if (STAGE) {
+          switch (op) {
+            case GC3_OP_RECV: move_tile_staged<false, false, DT, SL, 0, US, 0>(rs, rs, dst, dst, nvec, tid, nthreads, stage); break;
+            case GC3_OP_RRC:  move_tile_staged<true, false, DT, SL, UL, US, 0>(rs, src, dst, dst, nvec, tid, nthreads, stage); break;
+            case GC3_OP_RCS:  move_tile_staged<false, true, DT, SL, 0, US, SS>(rs, rs, dst, ss, nvec, tid, nthreads, stage); break;
+            case GC3_OP_RRCS: move_tile_staged<true, true, DT, SL, UL, US, SS>(rs, src, dst, ss, nvec, tid, nthreads, stage); break;
+            case GC3_OP_RRS:  move_tile_staged<true, false, DT, SL, UL, SS, 0>(rs, src, ss, ss, nvec, tid, nthreads, stage); break;
+            default: break;
+          }
+        } else {
+          switch (op) {
+            case GC3_OP_RECV: move_tile<false, false, DT, SL, 0, US, 0>(rs, rs, dst, dst, nvec, tid, nthreads); break;
+            case GC3_OP_RRC:  move_tile<true, false, DT, SL, UL, US, 0>(rs, src, dst, dst, nvec, tid, nthreads); break;
+            case GC3_OP_RCS:  move_tile<false, true, DT, SL, 0, US, SS>(rs, rs, dst, ss, nvec, tid, nthreads); break;
+            case GC3_OP_RRCS: move_tile<true, true, DT, SL, UL, US, SS>(rs, src, dst, ss, nvec, tid, nthreads); break;
+            case GC3_OP_RRS:  move_tile<true, false, DT, SL, UL, SS, 0>(rs, src, ss, ss, nvec, tid, nthreads); break;
+            default: break;
+          }
+        }
+    }
+  }
+}
+
+__device__ __forceinline__ bool op_pops(uint32_t op) {
+  return op == GC3_OP_RECV || op == GC3_OP_RRC || op == GC3_OP_RCS || op == GC3_OP_RRCS || op == GC3_OP_RRS;
+}
+__device__ __forceinline__ bool op_pushes(uint32_t op) {
+  return op == GC3_OP_SEND || op == GC3_OP_RCS || op == GC3_OP_RRCS || op == GC3_OP_RRS;
+}
+
+}  // namespace
+
 // A workgroup runs a short list of FIBERS.  A fiber is one lane of one IR thread block: its own
 // tile counter, step counter and FIFO sequence numbers.  The workgroup visits its unfinished
 // fibers round-robin and advances each as far as its waits allow; while more than one fiber is
 // unfinished a wait is a single poll (a fiber that is not ready yields to the next one, so thread
 // blocks sharing a workgroup can never block each other), and the last unfinished fiber waits by
 // spinning.  One fiber per workgroup is the paper's one-thread-block-per-block execution.
-template <int DT, bool COH, bool LL>
+template <int DT, bool COH, int MODE>
 __global__ void __launch_bounds__(512) gc3_interpreter(KParams p) {
+  constexpr bool LL = MODE == kLL;
+  constexpr bool STAGE = MODE == kStaged;
   __shared__ uint32_t f_id[kMaxFibersPerWg], f_t[kMaxFibersPerWg], f_s[kMaxFibersPerWg];
   __shared__ uint32_t f_send[kMaxFibersPerWg], f_recv[kMaxFibersPerWg];
   // messages of this run the fiber's receiver is known to have consumed (last head flag value seen): a push
   // polls the head flag only when this does not already show a free slot
   __shared__ uint32_t f_head[kMaxFibersPerWg];
+  __shared__ uint32_t f_epoch[kMaxFibersPerWg];    // runs the fiber has completed before this one
   __shared__ uint32_t s_headv[2];
   __shared__ uint64_t f_off0[kMaxFibersPerWg], f_share[kMaxFibersPerWg];
   // per fiber: its thread block's record and the three buffer pointers of its rank, fetched once
@@ -316,9 +426,7 @@ __global__ void __launch_bounds__(512) gc3_interpreter(KParams p) {
   // critical path of every hop
   __shared__ uint32_t s_instr[kLdsInstrs * 8];
   __shared__ int s_res[2];
-#if GC3_LDS_STAGE
-  __shared__ __attribute__((aligned(16))) unsigned char s_stage[kStageBytes];
-#endif
+  __shared__ __attribute__((aligned(16))) unsigned char s_stage[STAGE ? kStageBytes : 16];
   const uint32_t tid = threadIdx.x, nthreads = blockDim.x;
   // blockIdx = (sub * W_active + lane) * wgs_per_lane + bin: this workgroup takes entries sub, sub + nsplit, ...
   // of the fiber list the plan gives (lane, bin)
@@ -328,21 +436,7 @@ __global__ void __launch_bounds__(512) gc3_interpreter(KParams p) {
   const uint32_t nf = hdr.nfibers > sub ? (hdr.nfibers - sub + nsplit - 1) / nsplit : 0;
   if (nf == 0) return;
   if (p.hold) {
-    // failure-path test facility: wait (bounded) for a start word that the host never sets
-    if (tid == 0) {
-      int res = 1;
-      const uint64_t start = wall_clock64();
-      while (__hip_atomic_load(p.hold, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0) {
-        __builtin_amdgcn_s_sleep(8);
-        if (__hip_atomic_load(p.error, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) { res = -1; break; }
-        if (wall_clock64() - start > p.spin_limit_ticks) {
-          atomicCAS(p.error, 0u, (uint32_t)(-GC3_ERR_TIMEOUT));
-          res = -1;
-          break;
-        }
-      }
-      s_res[0] = res;
-    }
+    if (tid == 0) s_res[0] = hold_wait(p) ? 1 : -1;
     __syncthreads();
     if (s_res[0] < 0) return;
     __syncthreads();
@@ -360,6 +454,7 @@ __global__ void __launch_bounds__(512) gc3_interpreter(KParams p) {
     f_send[tid] = 0;
     f_recv[tid] = 0;
     f_head[tid] = 0;
+    f_epoch[tid] = (uint32_t)load_flag(p.sems + (uint64_t)f.fid * kFlagStrideWords + 1);
     f_off0[tid] = o;
     f_share[tid] = lane_begin(p.chunk_bytes, lane + 1, p.W_active) - o;
     f_ninstr[tid] = f.ninstr;
@@ -385,31 +480,29 @@ __global__ void __launch_bounds__(512) gc3_interpreter(KParams p) {
       if (t == kFiberDone) continue;
       const uint32_t fid = uni(f_id[fi]);
       const uint32_t tbi = fid / W, lane = fid % W;
-      DTb tb;
-      tb.rank = hdr.rank;
-      tb.instr_begin = uni(f_ibeg[fi]);
-      tb.ninstr = uni(f_ninstr[fi]);
-      tb.send_conn = (int32_t)uni((uint32_t)f_sconn[fi]);
-      tb.recv_conn = (int32_t)uni((uint32_t)f_rconn[fi]);
+      const uint32_t tb_instr_begin = uni(f_ibeg[fi]), tb_ninstr = uni(f_ninstr[fi]);
+      const int32_t send_conn = (int32_t)uni((uint32_t)f_sconn[fi]), recv_conn = (int32_t)uni((uint32_t)f_rconn[fi]);
       const uint32_t ilds = uni(f_ilds[fi]) * 8;
+      const uint32_t epoch = uni(f_epoch[fi]);
+      const uint64_t run_base = (uint64_t)(epoch + 1) << 32;
       const uint64_t off0 = ((uint64_t)uni((uint32_t)(f_off0[fi] >> 32)) << 32) | uni((uint32_t)f_off0[fi]);
       const uint64_t share = ((uint64_t)uni((uint32_t)(f_share[fi] >> 32)) << 32) | uni((uint32_t)f_share[fi]);
       const uint32_t ntiles = (uint32_t)((share + tile - 1) / tile);
       uint32_t s = uni(f_s[fi]), send_seq = uni(f_send[fi]), recv_seq = uni(f_recv[fi]);
       uint32_t head_known = uni(f_head[fi]);
 
-      uint64_t* const tail_send = tb.send_conn >= 0 ? p.flags + ((uint64_t)(tb.send_conn * W + lane) * 2 + 0) * kFlagStrideWords : nullptr;
-      uint64_t* const head_send = tb.send_conn >= 0 ? p.flags + ((uint64_t)(tb.send_conn * W + lane) * 2 + 1) * kFlagStrideWords : nullptr;
-      uint64_t* const tail_recv = tb.recv_conn >= 0 ? p.flags + ((uint64_t)(tb.recv_conn * W + lane) * 2 + 0) * kFlagStrideWords : nullptr;
-      uint64_t* const head_recv = tb.recv_conn >= 0 ? p.flags + ((uint64_t)(tb.recv_conn * W + lane) * 2 + 1) * kFlagStrideWords : nullptr;
+      uint64_t* const tail_send = send_conn >= 0 ? flag_of(p, send_conn, lane, 0) : nullptr;
+      uint64_t* const head_send = send_conn >= 0 ? flag_of(p, send_conn, lane, 1) : nullptr;
+      uint64_t* const tail_recv = recv_conn >= 0 ? flag_of(p, recv_conn, lane, 0) : nullptr;
+      uint64_t* const head_recv = recv_conn >= 0 ? flag_of(p, recv_conn, lane, 1) : nullptr;
       unsigned char* const fifo_base = LL ? p.ll_fifo : p.fifo;            // LL slots have a region of their own
       const uint32_t slot_bytes = LL ? p.ll_slot_bytes : p.slot_bytes;
-      unsigned char* const fifo_send = tb.send_conn >= 0 ? fifo_base + (uint64_t)(tb.send_conn * W + lane) * p.slots * slot_bytes : nullptr;
-      unsigned char* const fifo_recv = tb.recv_conn >= 0 ? fifo_base + (uint64_t)(tb.recv_conn * W + lane) * p.slots * slot_bytes : nullptr;
-      uint64_t* const my_sem = p.sems + (uint64_t)(tbi * W + lane) * kFlagStrideWords;
+      unsigned char* const fifo_send = send_conn >= 0 ? fifo_base + (uint64_t)((uint32_t)send_conn * W + lane) * p.slots * slot_bytes : nullptr;
+      unsigned char* const fifo_recv = recv_conn >= 0 ? fifo_base + (uint64_t)((uint32_t)recv_conn * W + lane) * p.slots * slot_bytes : nullptr;
+      uint64_t* const my_sem = sem_of(p, tbi, lane);
 
       bool progressed = false;
-      while (t < ntiles && s < tb.ninstr) {              // tile loop outside, instruction loop inside
+      while (t < ntiles && s < tb_ninstr) {              // tile loop outside, instruction loop inside
         const uint64_t toff = (uint64_t)t * tile;
         const uint32_t len = (uint32_t)(share - toff < tile ? share - toff : tile);   // bytes of this tile, per chunk
         const uint32_t nvec = len >> 4;
@@ -419,11 +512,10 @@ __global__ void __launch_bounds__(512) gc3_interpreter(KParams p) {
           ins.op = uni(w[0]); ins.srcbuf = uni(w[1]); ins.dstbuf = uni(w[2]); ins.srcidx = uni(w[3]);
           ins.dstidx = uni(w[4]); ins.count = uni(w[5]); ins.dep_begin = uni(w[6]); ins.ndeps_hasdep = uni(w[7]);
         } else {
-          ins = p.instrs[tb.instr_begin + s];
+          ins = p.instrs[tb_instr_begin + s];
         }
         const uint32_t op = ins.op;
-        const bool pops = op == GC3_OP_RECV || op == GC3_OP_RRC || op == GC3_OP_RCS || op == GC3_OP_RRCS || op == GC3_OP_RRS;
-        const bool pushes = op == GC3_OP_SEND || op == GC3_OP_RCS || op == GC3_OP_RRCS || op == GC3_OP_RRS;
+        const bool pops = op_pops(op), pushes = op_pushes(op);
         const uint32_t ndeps = ins.ndeps_hasdep >> 1;
         const bool hasdep = ins.ndeps_hasdep & 1;
         const bool wait_slot = pushes && send_seq >= head_known + p.slots;
@@ -435,52 +527,18 @@ __global__ void __launch_bounds__(512) gc3_interpreter(KParams p) {
         // (in LL mode a blocking receive needs no announcement: every thread polls its own data)
         if ((pops && !(LL && block)) || wait_slot || ndeps) {
           if (tid < 64) {
-            int res = 1;                                   // 1 ready, 0 not ready, -1 run abandoned
-            uint64_t seen = 0;                             // last flag value this lane loaded
-            const uint32_t total = 2 + ndeps;
-            for (uint32_t it0 = 0; it0 < total && res == 1; it0 += 64) {
-              const uint32_t it = it0 + tid;
-              const uint64_t* ptr = nullptr;
-              uint64_t want = 0;
-              if (it == 0) {
-                if (pops && !LL) { ptr = tail_recv; want = p.run_base + recv_seq + 1; }
-              } else if (it == 1) {
-                if (wait_slot) { ptr = head_send; want = p.run_base + send_seq + 1 - p.slots; }
-              } else if (it < total) {
-                const DDep d = p.deps[ins.dep_begin + it - 2];
-                ptr = p.sems + (uint64_t)(d.tb * W + lane) * kFlagStrideWords;
-                want = p.run_base + (uint64_t)t * d.ninstr + d.step + 1;
-              }
-              bool pending = ptr != nullptr;
-              const uint64_t start = wall_clock64();
-              uint32_t spins = 0;
-              for (;;) {
-                if (pending) {
-                  seen = load_flag(ptr);
-                  if (seen >= want) pending = false;
-                }
-                if (!__any(pending)) break;
-                if (!block) { res = 0; break; }
-                if (++spins > 16) __builtin_amdgcn_s_sleep(1);     // poll hard first, politely later
-                if ((spins & 255u) == 0) {
-                  if (__hip_atomic_load(p.error, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) { res = -1; break; }
-                  if (wall_clock64() - start > p.spin_limit_ticks) {
-                    atomicCAS(p.error, 0u, (uint32_t)(-GC3_ERR_TIMEOUT));
-                    res = -1;
-                    break;
-                  }
-                }
-              }
-            }
-            // (only more than 62 dependencies would take the loop above past its first round, in which lane 1
+            uint64_t seen;
+            int res = poll_flags(p, tid, block, (pops && !LL) ? tail_recv : nullptr, run_base + recv_seq + 1,
+                                 wait_slot ? head_send : nullptr, run_base + send_seq + 1 - p.slots,
+                                 ins.dep_begin, ndeps, lane, run_base, t, seen);
+            // (only more than 62 dependencies would take the polling past its first round, in which lane 1
             // polls the head flag)
-            if (tid == 1 && wait_slot && res == 1 && ndeps <= 62) s_headv[phase & 1] = (uint32_t)(seen - p.run_base);
+            if (tid == 1 && wait_slot && res == 1 && ndeps <= 62) s_headv[phase & 1] = (uint32_t)(seen - run_base);
             if (LL && pops && !block && res == 1) {
               // non-blocking readiness probe: has the first element of the message arrived?
               const uint32_t* first = (const uint32_t*)(fifo_recv + (uint64_t)(recv_seq % p.slots) * slot_bytes);
               if (__hip_atomic_load(first + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != ll_fin) res = 0;
             }
-            if (GC3_CONSERVATIVE_FENCES) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
             if (tid == 0) s_res[phase & 1] = res;
           }
           __syncthreads();
@@ -498,12 +556,11 @@ __global__ void __launch_bounds__(512) gc3_interpreter(KParams p) {
         unsigned char* const rslot = pops ? fifo_recv + (uint64_t)(recv_seq % p.slots) * slot_bytes : nullptr;
         unsigned char* const sslot = pushes ? fifo_send + (uint64_t)(send_seq % p.slots) * slot_bytes : nullptr;
         bool data_ok = true;
-        constexpr int UL = COH ? GC3_POL_USER_LD_COH : GC3_POL_USER_LD, US = COH ? GC3_POL_USER_ST_COH : GC3_POL_USER_ST;
-        constexpr int SL = GC3_POL_SLOT_LD, SS = GC3_POL_SLOT_ST;
-        for (uint32_t j = 0; j < ins.count; ++j) {
-          const rsrc_t src = make_rsrc(srcb + (uint64_t)j * p.chunk_bytes, srcb ? len : 0);
-          const rsrc_t dst = make_rsrc(dstb + (uint64_t)j * p.chunk_bytes, dstb ? len : 0);
-          if (LL && (pops || pushes)) {
+        if (LL && (pops || pushes)) {
+          constexpr int UL = COH ? kUserLdCoh : kUserLd, US = COH ? kUserStCoh : kUserSt;
+          for (uint32_t j = 0; j < ins.count; ++j) {
+            const rsrc_t src = make_rsrc(srcb + (uint64_t)j * p.chunk_bytes, srcb ? len : 0);
+            const rsrc_t dst = make_rsrc(dstb + (uint64_t)j * p.chunk_bytes, dstb ? len : 0);
             const rsrc_t rl = make_rsrc(rslot + (uint64_t)j * len * 2, rslot ? len * 2 : 0);
             const rsrc_t sl = make_rsrc(sslot + (uint64_t)j * len * 2, sslot ? len * 2 : 0);
             switch (op) {
@@ -515,29 +572,9 @@ __global__ void __launch_bounds__(512) gc3_interpreter(KParams p) {
               case GC3_OP_RRS:  data_ok &= move_tile_ll<true, true, false, true, DT, UL, US>(rl, src, dst, sl, nvec, tid, nthreads, ll_fin, ll_fout, p); break;
               default: break;
             }
-            continue;
           }
-          const rsrc_t rs = make_rsrc(rslot + (uint64_t)j * len, rslot ? len : 0);
-          const rsrc_t ss = make_rsrc(sslot + (uint64_t)j * len, sslot ? len : 0);
-          switch (op) {
-            case GC3_OP_SEND:   move_tile<false, false, DT, UL, 0, SS, 0>(src, src, ss, ss, nvec, tid, nthreads); break;
-            case GC3_OP_COPY:   move_tile<false, false, DT, UL, 0, US, 0>(src, src, dst, dst, nvec, tid, nthreads); break;
-            case GC3_OP_REDUCE: move_tile<true, false, DT, UL, UL, US, 0>(dst, src, dst, dst, nvec, tid, nthreads); break;
-#if GC3_LDS_STAGE
-            case GC3_OP_RECV:   move_tile_staged<false, false, DT, SL, 0, US, 0>(rs, rs, dst, dst, nvec, tid, nthreads, s_stage); break;
-            case GC3_OP_RRC:    move_tile_staged<true, false, DT, SL, UL, US, 0>(rs, src, dst, dst, nvec, tid, nthreads, s_stage); break;
-            case GC3_OP_RCS:    move_tile_staged<false, true, DT, SL, 0, US, SS>(rs, rs, dst, ss, nvec, tid, nthreads, s_stage); break;
-            case GC3_OP_RRCS:   move_tile_staged<true, true, DT, SL, UL, US, SS>(rs, src, dst, ss, nvec, tid, nthreads, s_stage); break;
-            case GC3_OP_RRS:    move_tile_staged<true, false, DT, SL, UL, SS, 0>(rs, src, ss, ss, nvec, tid, nthreads, s_stage); break;
-#else
-            case GC3_OP_RECV:   move_tile<false, false, DT, SL, 0, US, 0>(rs, rs, dst, dst, nvec, tid, nthreads); break;
-            case GC3_OP_RRC:    move_tile<true, false, DT, SL, UL, US, 0>(rs, src, dst, dst, nvec, tid, nthreads); break;
-            case GC3_OP_RCS:    move_tile<false, true, DT, SL, 0, US, SS>(rs, rs, dst, ss, nvec, tid, nthreads); break;
-            case GC3_OP_RRCS:   move_tile<true, true, DT, SL, UL, US, SS>(rs, src, dst, ss, nvec, tid, nthreads); break;
-            case GC3_OP_RRS:    move_tile<true, false, DT, SL, UL, SS, 0>(rs, src, ss, ss, nvec, tid, nthreads); break;
-#endif
-            default: break;
-          }
+        } else {
+          move_simple<DT, COH, STAGE>(op, ins.count, srcb, dstb, rslot, sslot, len, p.chunk_bytes, tid, nthreads, s_stage);
         }
 
         // ---- publish: slot filled, slot freed, semaphore ----------------------------------------
@@ -558,17 +595,16 @@ __global__ void __launch_bounds__(512) gc3_interpreter(KParams p) {
             __syncthreads();
           }
           if (tid == 0) {
-            if (GC3_CONSERVATIVE_FENCES) __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
-            if (pushes && !LL) store_flag(tail_send, p.run_base + send_seq);
-            if (pops) store_flag(head_recv, p.run_base + recv_seq);
-            if (hasdep) store_flag(my_sem, p.run_base + (uint64_t)t * tb.ninstr + s + 1);
+            if (pushes && !LL) store_flag(tail_send, run_base + send_seq);
+            if (pops) store_flag(head_recv, run_base + recv_seq);
+            if (hasdep) store_flag(my_sem, run_base + (uint64_t)t * tb_ninstr + s + 1);
           }
         }
         progressed = true;
-        if (++s == tb.ninstr) { s = 0; ++t; }
+        if (++s == tb_ninstr) { s = 0; ++t; }
       }
 
-      const bool finished = t >= ntiles || tb.ninstr == 0;   // also true for a lane that owns no bytes
+      const bool finished = t >= ntiles || tb_ninstr == 0;   // also true for a lane that owns no bytes
       if (progressed || finished) {
         any_progress = true;
         __syncthreads();                                 // every wavefront has read this fiber's old state
@@ -578,6 +614,7 @@ __global__ void __launch_bounds__(512) gc3_interpreter(KParams p) {
           f_send[fi] = send_seq;
           f_recv[fi] = recv_seq;
           f_head[fi] = head_known;
+          if (finished) store_flag(my_sem + 1, (uint64_t)epoch + 1);   // this fiber has completed one more run
         }
       }
       if (finished) --live;
@@ -605,44 +642,165 @@ __global__ void __launch_bounds__(512) gc3_interpreter(KParams p) {
   }
 }
 
+// The same interpreter for workgroups of ONE wavefront that run ONE fiber (simple protocol): tile, step and
+// sequence counters live in registers, waits and publishes are wavefront-level - the lanes poll, the wavefront
+// waits for its own stores, lane 0 stores the flags - and there is no workgroup barrier and no state in LDS
+// anywhere on the path of a hop.  This is the instantiation for latency-bound sizes, where a lane's share of a
+// chunk is a few 128-bit accesses per thread.
+constexpr int kWaveLdsInstrs = 64;
+template <int DT, bool COH>
+__global__ void __launch_bounds__(64) gc3_interpreter_wave(KParams p) {
+  __shared__ uint32_t s_instr[kWaveLdsInstrs * 8];
+  const uint32_t tid = threadIdx.x;
+  const uint32_t slot = blockIdx.x / p.wgs_per_lane, bin = blockIdx.x % p.wgs_per_lane;
+  const uint32_t sub = slot / p.W_active;
+  const DWg hdr = p.wgs[(slot % p.W_active) * p.wgs_per_lane + bin];
+  if (hdr.nfibers <= sub) return;                     // (the host launches this kernel only when nfibers <= nsplit)
+  if (p.hold) {
+    int ok = 1;
+    if (tid == 0) ok = hold_wait(p) ? 1 : 0;
+    if (!uni((uint32_t)ok)) return;
+  }
+  const uint32_t W = p.W, tile = p.tile_bytes;
+  const DFiber f = p.fibers[hdr.fiber_begin + sub];
+  const uint32_t fid = uni(f.fid), tb_ninstr = uni(f.ninstr), tb_instr_begin = uni(f.instr_begin);
+  const int32_t send_conn = (int32_t)uni((uint32_t)f.send_conn), recv_conn = (int32_t)uni((uint32_t)f.recv_conn);
+  const uint32_t tbi = fid / W, lane = fid % W;
+  uint64_t* const my_sem = sem_of(p, tbi, lane);
+  const uint32_t epoch = uni((uint32_t)load_flag(my_sem + 1));
+  const uint64_t run_base = (uint64_t)(epoch + 1) << 32;
+  unsigned char* bufs[3];
+#pragma unroll
+  for (int k = 0; k < 3; ++k) bufs[k] = (unsigned char*)uni64((uint64_t)p.bufs[hdr.rank * 3 + k]);
+  const bool instr_in_lds = tb_ninstr <= (uint32_t)kWaveLdsInstrs;
+  if (instr_in_lds) {
+    const uint32_t* gi = (const uint32_t*)(p.instrs + tb_instr_begin);
+    for (uint32_t k = tid; k < tb_ninstr * 8; k += 64) s_instr[k] = gi[k];
+    __syncthreads();                                   // one wavefront: only orders the LDS writes before the reads
+  }
+  const uint64_t off0 = lane_begin(p.chunk_bytes, lane, p.W_active);
+  const uint64_t share = lane_begin(p.chunk_bytes, lane + 1, p.W_active) - off0;
+  const uint32_t ntiles = (uint32_t)((share + tile - 1) / tile);
+  uint64_t* const tail_send = send_conn >= 0 ? flag_of(p, send_conn, lane, 0) : nullptr;
+  uint64_t* const head_send = send_conn >= 0 ? flag_of(p, send_conn, lane, 1) : nullptr;
+  uint64_t* const tail_recv = recv_conn >= 0 ? flag_of(p, recv_conn, lane, 0) : nullptr;
+  uint64_t* const head_recv = recv_conn >= 0 ? flag_of(p, recv_conn, lane, 1) : nullptr;
+  unsigned char* const fifo_send = send_conn >= 0 ? p.fifo + (uint64_t)((uint32_t)send_conn * W + lane) * p.slots * p.slot_bytes : nullptr;
+  unsigned char* const fifo_recv = recv_conn >= 0 ? p.fifo + (uint64_t)((uint32_t)recv_conn * W + lane) * p.slots * p.slot_bytes : nullptr;
+  uint32_t send_seq = 0, recv_seq = 0, head_known = 0;
+
+  for (uint32_t t = 0; t < ntiles; ++t) {               // tile loop outside, instruction loop inside
+    const uint64_t toff = (uint64_t)t * tile;
+    const uint32_t len = (uint32_t)(share - toff < tile ? share - toff : tile);
+    for (uint32_t s = 0; s < tb_ninstr; ++s) {
+      DInstr ins;
+      if (instr_in_lds) {
+        const uint32_t* w = s_instr + s * 8;
+        ins.op = uni(w[0]); ins.srcbuf = uni(w[1]); ins.dstbuf = uni(w[2]); ins.srcidx = uni(w[3]);
+        ins.dstidx = uni(w[4]); ins.count = uni(w[5]); ins.dep_begin = uni(w[6]); ins.ndeps_hasdep = uni(w[7]);
+      } else {
+        ins = p.instrs[tb_instr_begin + s];
+      }
+      const uint32_t op = ins.op;
+      const bool pops = op_pops(op), pushes = op_pushes(op);
+      const uint32_t ndeps = ins.ndeps_hasdep >> 1;
+      const bool hasdep = ins.ndeps_hasdep & 1;
+      const bool wait_slot = pushes && send_seq >= head_known + p.slots;
+      if (pops || wait_slot || ndeps) {
+        uint64_t seen;
+        const int res = poll_flags(p, tid, true, pops ? tail_recv : nullptr, run_base + recv_seq + 1,
+                                   wait_slot ? head_send : nullptr, run_base + send_seq + 1 - p.slots,
+                                   ins.dep_begin, ndeps, lane, run_base, t, seen);
+        if (res < 0) return;                           // (the same value in every lane: decided by wavefront votes)
+        if (wait_slot && ndeps <= 62) head_known = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(seen - run_base), 1);
+      }
+      const uint64_t coff = off0 + toff;
+      unsigned char* const srcb = ins.srcbuf < 3 ? bufs[ins.srcbuf] + (uint64_t)ins.srcidx * p.chunk_bytes + coff : nullptr;
+      unsigned char* const dstb = ins.dstbuf < 3 ? bufs[ins.dstbuf] + (uint64_t)ins.dstidx * p.chunk_bytes + coff : nullptr;
+      unsigned char* const rslot = pops ? fifo_recv + (uint64_t)(recv_seq % p.slots) * p.slot_bytes : nullptr;
+      unsigned char* const sslot = pushes ? fifo_send + (uint64_t)(send_seq % p.slots) * p.slot_bytes : nullptr;
+      move_simple<DT, COH, false>(op, ins.count, srcb, dstb, rslot, sslot, len, p.chunk_bytes, tid, 64, nullptr);
+      if (pushes) ++send_seq;
+      if (pops) ++recv_seq;
+      if (pushes || pops || hasdep) {
+        // the wavefront's own device-scope stores have completed when its counter reaches zero; all of the
+        // fiber's stores are this wavefront's, so nothing else has to be waited for before the flags
+        __builtin_amdgcn_s_waitcnt(0);
+        if (tid == 0) {
+          if (pushes) store_flag(tail_send, run_base + send_seq);
+          if (pops) store_flag(head_recv, run_base + recv_seq);
+          if (hasdep) store_flag(my_sem, run_base + (uint64_t)t * tb_ninstr + s + 1);
+        }
+      }
+    }
+  }
+  if (tid == 0) store_flag(my_sem + 1, (uint64_t)epoch + 1);   // this fiber has completed one more run
+}
+
 // Host-callable launcher; returns the hipError_t of the launch.  `coherent_user` selects the
-// instantiation for programs with cross-thread-block dependencies, `ll` the LL protocol.
+// instantiation for programs with cross-thread-block dependencies; `mode`: 0 simple, 1 LL, 2 simple with the
+// FIFO payload staged through LDS, 3 the one-wavefront one-fiber interpreter (block must be 64).
 template <int DT>
-static int launch_dt(bool coh, bool ll, unsigned grid, unsigned block, hipStream_t st, const KParams& p) {
-  if (coh && ll) hipLaunchKernelGGL((gc3_interpreter<DT, true, true>), dim3(grid), dim3(block), 0, st, p);
-  else if (coh) hipLaunchKernelGGL((gc3_interpreter<DT, true, false>), dim3(grid), dim3(block), 0, st, p);
-  else if (ll) hipLaunchKernelGGL((gc3_interpreter<DT, false, true>), dim3(grid), dim3(block), 0, st, p);
-  else hipLaunchKernelGGL((gc3_interpreter<DT, false, false>), dim3(grid), dim3(block), 0, st, p);
+static int launch_dt(bool coh, int mode, unsigned grid, unsigned block, hipStream_t st, const KParams& p) {
+#define GC3_LAUNCH(K) hipLaunchKernelGGL((K), dim3(grid), dim3(block), 0, st, p)
+  switch (mode * 2 + (coh ? 1 : 0)) {
+    case 0: GC3_LAUNCH((gc3_interpreter<DT, false, kSimple>)); break;
+    case 1: GC3_LAUNCH((gc3_interpreter<DT, true, kSimple>)); break;
+    case 2: GC3_LAUNCH((gc3_interpreter<DT, false, kLL>)); break;
+    case 3: GC3_LAUNCH((gc3_interpreter<DT, true, kLL>)); break;
+    case 4: GC3_LAUNCH((gc3_interpreter<DT, false, kStaged>)); break;
+    case 5: GC3_LAUNCH((gc3_interpreter<DT, true, kStaged>)); break;
+    case 6: GC3_LAUNCH((gc3_interpreter_wave<DT, false>)); break;
+    case 7: GC3_LAUNCH((gc3_interpreter_wave<DT, true>)); break;
+    default: return (int)hipErrorInvalidValue;
+  }
+#undef GC3_LAUNCH
   return (int)hipGetLastError();
 }
 
-int launch_interpreter(int dtype, bool coherent_user, bool ll, unsigned grid, unsigned block, void* stream, const KParams& p) {
+int launch_interpreter(int dtype, bool coherent_user, int mode, unsigned grid, unsigned block, void* stream, const KParams& p) {
   hipStream_t st = (hipStream_t)stream;
+  if (mode == 3 && block != 64) return (int)hipErrorInvalidValue;
   switch (dtype) {
-    case GC3_F32: return launch_dt<GC3_F32>(coherent_user, ll, grid, block, st, p);
-    case GC3_F16: return launch_dt<GC3_F16>(coherent_user, ll, grid, block, st, p);
-    case GC3_BF16: return launch_dt<GC3_BF16>(coherent_user, ll, grid, block, st, p);
+    case GC3_F32: return launch_dt<GC3_F32>(coherent_user, mode, grid, block, st, p);
+    case GC3_F16: return launch_dt<GC3_F16>(coherent_user, mode, grid, block, st, p);
+    case GC3_BF16: return launch_dt<GC3_BF16>(coherent_user, mode, grid, block, st, p);
     default: return (int)hipErrorInvalidValue;
   }
 }
 
 // Occupancy of the interpreter (workgroups of `block` threads per compute unit), minimum over the
-// instantiations.
-int interpreter_occupancy(unsigned block, int* out) {
+// instantiations that a communicator with this block size may launch: the LDS-staged ones when `staged`,
+// else the register-path ones (both protocols, and the wavefront-level kernel for 64 threads).
+int interpreter_occupancy(unsigned block, bool staged, int* out) {
   int best = 1 << 30;
-  const void* fns[] = {
-      (const void*)gc3_interpreter<GC3_F32, false, false>, (const void*)gc3_interpreter<GC3_F32, true, false>,
-      (const void*)gc3_interpreter<GC3_F16, false, false>, (const void*)gc3_interpreter<GC3_F16, true, false>,
-      (const void*)gc3_interpreter<GC3_BF16, false, false>, (const void*)gc3_interpreter<GC3_BF16, true, false>,
-      (const void*)gc3_interpreter<GC3_F32, false, true>, (const void*)gc3_interpreter<GC3_F32, true, true>,
-      (const void*)gc3_interpreter<GC3_F16, false, true>, (const void*)gc3_interpreter<GC3_F16, true, true>,
-      (const void*)gc3_interpreter<GC3_BF16, false, true>, (const void*)gc3_interpreter<GC3_BF16, true, true>};
-  for (const void* f : fns) {
-    int n = 0;
-    hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, f, (int)block, 0);
-    if (e != hipSuccess) return (int)e;
-    if (n < best) best = n;
-  }
+  const void* plain[] = {
+      (const void*)gc3_interpreter<GC3_F32, false, kSimple>, (const void*)gc3_interpreter<GC3_F32, true, kSimple>,
+      (const void*)gc3_interpreter<GC3_F16, false, kSimple>, (const void*)gc3_interpreter<GC3_F16, true, kSimple>,
+      (const void*)gc3_interpreter<GC3_BF16, false, kSimple>, (const void*)gc3_interpreter<GC3_BF16, true, kSimple>,
+      (const void*)gc3_interpreter<GC3_F32, false, kLL>, (const void*)gc3_interpreter<GC3_F32, true, kLL>,
+      (const void*)gc3_interpreter<GC3_F16, false, kLL>, (const void*)gc3_interpreter<GC3_F16, true, kLL>,
+      (const void*)gc3_interpreter<GC3_BF16, false, kLL>, (const void*)gc3_interpreter<GC3_BF16, true, kLL>};
+  const void* with_stage[] = {
+      (const void*)gc3_interpreter<GC3_F32, false, kStaged>, (const void*)gc3_interpreter<GC3_F32, true, kStaged>,
+      (const void*)gc3_interpreter<GC3_F16, false, kStaged>, (const void*)gc3_interpreter<GC3_F16, true, kStaged>,
+      (const void*)gc3_interpreter<GC3_BF16, false, kStaged>, (const void*)gc3_interpreter<GC3_BF16, true, kStaged>};
+  const void* wave[] = {
+      (const void*)gc3_interpreter_wave<GC3_F32, false>, (const void*)gc3_interpreter_wave<GC3_F32, true>,
+      (const void*)gc3_interpreter_wave<GC3_F16, false>, (const void*)gc3_interpreter_wave<GC3_F16, true>,
+      (const void*)gc3_interpreter_wave<GC3_BF16, false>, (const void*)gc3_interpreter_wave<GC3_BF16, true>};
+  auto take = [&](const void* const* fns, int n) -> int {
+    for (int i = 0; i < n; ++i) {
+      int occ = 0;
+      hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, fns[i], (int)block, 0);
+      if (e != hipSuccess) return (int)e;
+      if (occ < best) best = occ;
+    }
+    return 0;
+  };
+  int e = staged ? take(with_stage, 6) : take(plain, 12);
+  if (e == 0 && !staged && block == 64) e = take(wave, 6);
+  if (e != 0) return e;
   *out = best;
   return 0;
 }

@@ -33,7 +33,7 @@ int resolve_config(const gc3_comm_config* cfg_in, gc3_comm_config& cfg, std::str
   if (cfg.team_width < 0 || cfg.team_width > 256) { msg = "team_width must be 0..256"; return GC3_ERR_ARG; }
 
   if (cfg.target_wgs < 0) { msg = "target_wgs must not be negative"; return GC3_ERR_ARG; }
-  if (cfg.reserved0 != 0) { msg = "reserved0 must be 0"; return GC3_ERR_ARG; }
+  if (cfg.lds_stage < 0 || cfg.lds_stage > 1) { msg = "lds_stage must be 0 or 1"; return GC3_ERR_ARG; }
   if (cfg.debug_hold < 0 || cfg.debug_hold > 1) { msg = "debug_hold must be 0 or 1"; return GC3_ERR_ARG; }
   if (cfg.protocol < 0 || cfg.protocol > 3) { msg = "protocol must be 0..3"; return GC3_ERR_ARG; }
   if (cfg.ll_max_lane_bytes == 0) cfg.ll_max_lane_bytes = 8192;

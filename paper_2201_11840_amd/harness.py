@@ -108,6 +108,11 @@ class Collective:
         st = STORAGE[self.dtype]
         return [b[:n].cpu().numpy().view(st).copy() for b in bufs]
 
+    @property
+    def launch(self) -> B.LaunchInfo:
+        """What a run of the current size launches (grid, workgroup size, kernel variant ...)."""
+        return B.gc3_comm_launch_info(self.comm, self.elems, self.code)
+
     def run(self) -> None:
         """One collective, asynchronous on torch's current stream."""
         B.gc3_comm_run(self.comm, self.elems, self.code, B.GC3_SUM, torch.cuda.current_stream().cuda_stream)

@@ -55,7 +55,8 @@ def compare_special(got, want, dtype, exact_only=False):
                            f"{gb[~nan][bad][0]:#x} want {wb[~nan][bad][0]:#x}")
 
 
-def run_case(prog, dtype, elems, dist="normal", seed=1234, cfg=None, repeats=1, exact_only=False, compare=None):
+def run_case(prog, dtype, elems, dist="normal", seed=1234, cfg=None, repeats=1, exact_only=False, compare=None,
+             expect_kernel=None):
     """Run `prog` on the GPU and in the oracle on the same seeded inputs; compare every output element
     of every rank (and the inputs of out-of-place programs, which most programs leave untouched).  With an explicit
     configuration both protocols (payload + flag, and LL) are exercised unless it fixes one."""
@@ -78,6 +79,8 @@ def run_case(prog, dtype, elems, dist="normal", seed=1234, cfg=None, repeats=1, 
             cfg.protocol = proto
         coll = H.Collective(text, dtype, elems, cfg)
         try:
+            if expect_kernel is not None:                  # the kernel variant this case is meant to exercise
+                assert coll.launch.kernel == expect_kernel, (prog.name, coll.launch.kernel)
             for _ in range(repeats):
                 coll.upload(ins, outs)
                 coll.run()
@@ -661,6 +664,139 @@ def test_special_values_multi_hop(dtype):
         run_case(prog, dtype, elems, "special", 950, cfg, compare=compare_special)
         # all ranks of an AllReduce end with the same bits wherever the result is not a NaN: checked by the
         # element-wise comparison with the oracle, whose ranks agree by construction
+
+
+# ---- the wavefront-level interpreter (64-thread workgroups that run one thread-block lane each) ------------------
+
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
+def test_wavefront_level_interpreter(dtype):
+    """Every workgroup is one wavefront with one fiber: counters in registers, no barrier, no LDS state.  Programs
+    with and without cross-thread-block dependencies, aggregated instructions, scratch buffers, many peers;
+    tiny tiles with ragged tails and the default tile; 2 and 8 slots.  Thread blocks that share a workgroup in
+    the plan are dealt to workgroups of their own when the chunk is small (split), which is how the hierarchical
+    and All Pairs programs get here."""
+    H = _harness()
+    from paper_2201_11840_amd import binding as B
+    m = 4 // inputs.ITEMSIZE[dtype]
+    wave = lambda **kw: H.make_config(wg_size=64, protocol=1, **kw)
+    cases = [(programs.ring_allreduce(8), 8 * 2500 * m, wave(tile_bytes=1024, team_width=3, min_lane_bytes=16)),
+             (programs.ring_allreduce(4, use_rrs=True), 4 * 2500 * m, wave(tile_bytes=256, team_width=2, min_lane_bytes=16, fifo_slots=8)),
+             (programs.ring_allreduce(8, instances=2), 16 * 16384 * m, wave(team_width=32, min_lane_bytes=1024, target_wgs=2048)),
+             (programs.ring_allreduce(8, instances=8), 64 * 32768 * m, wave(team_width=32, target_wgs=4096)),
+             (programs.hierarchical_allreduce(2, 3), 6 * 2000 * m, wave(tile_bytes=1024, team_width=8, min_lane_bytes=4096)),
+             (programs.hierarchical_allreduce(2, 8), 16 * 3072 * m, wave(team_width=16, min_lane_bytes=8192)),
+             (programs.allpairs_allreduce(8), 8 * 3072 * m, wave(team_width=16, min_lane_bytes=8192)),
+             (programs.allpairs_allreduce(4, via_scratch=True), 4 * 1000 * m, wave(tile_bytes=1024, team_width=8, min_lane_bytes=4096)),
+             (programs.multichannel_ring_allreduce(5, 3), 5 * 1000 * m, wave(tile_bytes=512, team_width=8, min_lane_bytes=4096))]
+    for prog, elems, cfg in cases:
+        run_case(prog, dtype, elems, "normal", 1200, cfg, repeats=2, expect_kernel=B.KERNEL_WAVE)
+    run_case(programs.direct_alltoall(8), dtype, 8 * 2048 * m, "normal", 1201, wave(team_width=16, min_lane_bytes=8192),
+             exact_only=True, expect_kernel=B.KERNEL_WAVE)
+    run_case(programs.alltonext(2, 3), dtype, 3 * 2048 * m, "normal", 1202, wave(team_width=16, min_lane_bytes=8192),
+             exact_only=True, expect_kernel=B.KERNEL_WAVE)
+    # instruction lists longer than the wavefront-level kernel keeps in LDS (124 per thread block)
+    run_case(programs.ring_allreduce(32, fuse=False), dtype, 32 * 256 * m, "uniform", 1203, wave(team_width=1),
+             expect_kernel=B.KERNEL_WAVE)
+    # and 64-thread workgroups that do hold several fibers fall back to the general interpreter
+    run_case(programs.hierarchical_allreduce(2, 3), dtype, 6 * 20000 * m, "normal", 1204, wave(team_width=2),
+             expect_kernel=B.KERNEL_GENERAL)
+
+
+# ---- FIFO payload staged through LDS (direct-to-LDS loads) --------------------------------------------------------
+
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
+def test_lds_staged_payload_path(dtype):
+    H = _harness()
+    es = inputs.ITEMSIZE[dtype]
+    staged = lambda **kw: H.make_config(lds_stage=1, protocol=1, **kw)
+    for opcode in ("send", "rrc", "rcs", "rrcs", "rrs"):        # "send" pairs with recv: every receiving instruction
+        for count, chunk_bytes in ((1, 16), (2, 3 * 1024 + 48), (1, 40000), (3, 70000 // 16 * 16)):
+            prog = _opcode_program(opcode, count)
+            run_case(prog, dtype, 2 * count * chunk_bytes // es, "normal", 1300 + count,
+                     staged(tile_bytes=20480, team_width=2, min_lane_bytes=16))          # tiles larger than the staging area
+        run_case(_opcode_program(opcode, 1), dtype, 2 * (1 << 18) // es, "uniform", 1310, staged())
+        run_case(_opcode_program(opcode, 1), dtype, 2 * 50000 * 16 // es, "special", 1311, staged(wg_size=512), compare=compare_special)
+    run_case(programs.hierarchical_allreduce(2, 3), dtype, 6 * 30000 // es * 4, "normal", 1320, staged(wg_size=128))
+    run_case(programs.ring_allreduce(8, instances=8), dtype, (4 << 20) // es, "uniform", 1321, staged())
+    run_case(programs.alltonext(2, 3), dtype, 3 * 65536, "normal", 1322, staged(wg_size=64), exact_only=True)
+
+
+def test_config3_with_lds_staging():
+    w = workloads.ring_ar_r8x8(16)
+    run_case(w.build(), w.dtype, w.elems_per_rank, w.dist, w.seed, _harness().make_config(lds_stage=1, protocol=1))
+
+
+# ---- a run recorded into a HIP graph ---------------------------------------------------------------------------
+
+def test_captured_runs_replay_bit_exactly():
+    """gc3_comm_run has constant kernel arguments (the run counters live in device memory), so a launch can be
+    captured and replayed.  A graph of [restore inputs, run] x 10 is replayed several times, with eager runs of
+    the same communicator and synchronisations in between; every replay must give the eager (oracle-checked)
+    result.  The restore is a copy kernel, not a memset node."""
+    import torch
+    H = _harness()
+    for prog, dtype, elems in ((programs.ring_allreduce(8, instances=2), "f32", 16 * 8192),
+                               (programs.hierarchical_allreduce(2, 3), "bf16", 6 * 40000)):
+        text = prog.to_text()
+        p = oracle.parse_program(text)
+        ins = inputs.make_inputs(p.ranks, elems, dtype, "normal", 1400)
+        want = [a.copy() for a in ins]
+        oracle.run_program(p, want, None, dtype, slots=2)
+        coll = H.Collective(text, dtype, elems, H.make_config(protocol=1))
+        try:
+            coll.upload(ins)
+            pristine = [t.clone() for t in coll.inputs]
+            coll.run()                                         # eager reference, also the warm-up
+            coll.status()
+            for g, w_ in zip(coll.download(), want):
+                compare(g, w_, dtype)
+            graph = torch.cuda.CUDAGraph()
+            side = torch.cuda.Stream()
+            side.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.graph(graph, stream=side):
+                for _ in range(10):
+                    for d, s_ in zip(coll.inputs, pristine):
+                        d.copy_(s_)
+                    coll.run()
+            for replay in range(4):
+                for d in coll.inputs:
+                    d.fill_(0)                                 # whatever a replay leaves must come from the replay
+                graph.replay()
+                torch.cuda.synchronize()
+                coll.status()
+                for g, w_ in zip(coll.download(), want):
+                    compare(g, w_, dtype)
+                # eager work of the same communicator between replays
+                coll.upload(ins)
+                coll.run()
+                coll.status()
+                for g, w_ in zip(coll.download(), want):
+                    compare(g, w_, dtype)
+        finally:
+            coll.close()
+    # the LL protocol's message numbers are kernel arguments: such a run is refused while its stream is capturing
+    import ctypes
+    from paper_2201_11840_amd import binding as B
+    hip = ctypes.CDLL("libamdhip64.so")
+    coll = H.Collective(programs.ring_allreduce(4).to_text(), "f32", 4 * 64, H.make_config(protocol=2))
+    side = torch.cuda.Stream()
+    try:
+        torch.cuda.synchronize()
+        relaxed = 2                                            # hipStreamCaptureModeRelaxed
+        assert hip.hipStreamBeginCapture(ctypes.c_void_p(side.cuda_stream), relaxed) == 0
+        try:
+            with pytest.raises(B.Gc3Error) as e:
+                B.gc3_comm_run(coll.comm, coll.elems, coll.code, B.GC3_SUM, side.cuda_stream)
+            assert e.value.status == B.GC3_ERR_ARG
+        finally:
+            g = ctypes.c_void_p()
+            assert hip.hipStreamEndCapture(ctypes.c_void_p(side.cuda_stream), ctypes.byref(g)) == 0
+            if g.value:
+                hip.hipGraphDestroy(g)
+        coll.run()                                             # outside capture the same communicator runs
+        coll.status()
+    finally:
+        coll.close()
 
 
 def test_buffers_beyond_4GiB_sampled():

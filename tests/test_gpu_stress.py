@@ -85,3 +85,61 @@ def test_two_communicators_and_a_side_stream():
     finally:
         ca.close()
         cb.close()
+
+
+def test_two_communicators_on_two_streams_share_the_device():
+    """Two full-device grids (1024 workgroups each) launched back to back on two streams could not both be resident;
+    the library's ledger makes the second stream wait for the first run, so both complete with oracle-exact
+    results.  (The rule itself is unit-tested on the CPU; this test never lets two grids compete.)"""
+    a, b = workloads.ring_ar_r8x8(16), workloads.hier_ar_2x8(16)
+    ca = H.Collective(a.build().to_text(), a.dtype, a.elems_per_rank)
+    cb = H.Collective(b.build().to_text(), b.dtype, b.elems_per_rank)
+    assert ca.info.grid + cb.info.grid > ca.info.max_resident_wgs
+    ia = inputs.make_inputs(8, a.elems_per_rank, a.dtype, a.dist, a.seed)
+    ib = inputs.make_inputs(16, b.elems_per_rank, b.dtype, b.dist, b.seed)
+    wa, wb = [x.copy() for x in ia], [x.copy() for x in ib]
+    oracle.run_program(oracle.parse_program(a.build().to_text()), wa, None, a.dtype, slots=2)
+    oracle.run_program(oracle.parse_program(b.build().to_text()), wb, None, b.dtype, slots=2)
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    try:
+        for it in range(4):
+            ca.upload(ia)
+            cb.upload(ib)
+            with torch.cuda.stream(s1):
+                ca.run()
+            with torch.cuda.stream(s2):
+                cb.run()
+            s1.synchronize()
+            s2.synchronize()
+            ca.status()
+            cb.status()
+            for g, w_ in zip(ca.download(), wa):
+                assert g.tobytes() == w_.tobytes(), f"ring, round {it}"
+            for g, w_ in zip(cb.download(), wb):
+                assert g.tobytes() == w_.tobytes(), f"hierarchical, round {it}"
+        # small grids that fit side by side are not serialised and still give the right answers
+        small_a = H.Collective(programs.ring_allreduce(4).to_text(), "f32", 4 * 4096, H.make_config(team_width=2))
+        small_b = H.Collective(programs.allpairs_allreduce(4).to_text(), "f32", 4 * 4096, H.make_config(team_width=2))
+        xa = inputs.make_inputs(4, 4 * 4096, "f32", "uniform", 3)
+        ya = [x.copy() for x in xa]
+        oracle.run_program(oracle.parse_program(programs.ring_allreduce(4).to_text()), ya, None, "f32", slots=2)
+        yb = [x.copy() for x in xa]
+        oracle.run_program(oracle.parse_program(programs.allpairs_allreduce(4).to_text()), yb, None, "f32", slots=2)
+        for it in range(4):
+            small_a.upload(xa)
+            small_b.upload(xa)
+            with torch.cuda.stream(s1):
+                small_a.run()
+            with torch.cuda.stream(s2):
+                small_b.run()
+            s1.synchronize()
+            s2.synchronize()
+            small_a.status()
+            small_b.status()
+            assert all(g.tobytes() == w_.tobytes() for g, w_ in zip(small_a.download(), ya))
+            assert all(g.tobytes() == w_.tobytes() for g, w_ in zip(small_b.download(), yb))
+        small_a.close()
+        small_b.close()
+    finally:
+        ca.close()
+        cb.close()

@@ -215,7 +215,7 @@ def test_plan_respects_configuration_and_limits():
     small = plan(prog, cus=8, resident=16)                     # a tiny device: thread blocks must share
     assert small.active_wgs <= 16 and small.max_fibers_per_wg >= 4
     for bad in (dict(fifo_slots=9), dict(tile_bytes=24), dict(tile_bytes=2 << 20), dict(wg_size=100),
-                dict(team_width=257), dict(target_wgs=-1), dict(min_lane_bytes=24), dict(debug_hold=2)):
+                dict(team_width=257), dict(target_wgs=-1), dict(min_lane_bytes=24), dict(debug_hold=2), dict(lds_stage=2)):
         with pytest.raises(B.Gc3Error) as e:
             plan(prog, **bad)
         assert e.value.status == B.GC3_ERR_ARG
@@ -246,6 +246,27 @@ def test_ring_user_buffer_traffic_closed_form(R, k):
     assert p.fifo_chunks() == R * k * 2 * (2 * R - 2)       # 2R-2 messages per thread block, written once and read once
 
 
+def test_residency_rule_for_runs_of_different_communicators():
+    """Which runs in flight a new run must wait for (Section 6.2: every grid in flight must be wholly resident).
+    Pure host logic behind gc3_comm_run's per-device ledger."""
+    plan = B.gc3_residency_plan
+    cap = 1792
+    assert plan([], 7, 1024, cap) == []
+    assert plan([(1, 1024, cap)], 1, 1024, cap) == [0]                 # same stream: ordered by the stream
+    assert plan([(1, 1024, cap)], 2, 1024, cap) == [1]                 # 1024 + 1024 > 1792 on two streams
+    assert plan([(1, 768, cap)], 2, 1024, cap) == [0]                  # fits beside it
+    assert plan([(1, 512, cap), (2, 512, cap)], 3, 1024, cap) == [1, 0]          # oldest first, only as many as needed
+    assert plan([(1, 512, cap), (3, 512, cap), (2, 512, cap)], 3, 1024, cap) == [1, 0, 0]   # own stream does not count
+    assert plan([(1, 1000, cap), (2, 1000, cap)], 3, 1792, cap) == [1, 1]        # a grid that fills the device waits for all
+    # different workgroup sizes: shares of the device, not workgroup counts (64-thread groups: 5120 fit)
+    assert plan([(1, 2560, 5120)], 2, 1024, cap) == [1]                # 0.5 + 0.571 > 1
+    assert plan([(1, 2048, 5120)], 2, 1024, cap) == [0]                # 0.4 + 0.571 <= 1
+    for bad in (([(1, -1, cap)], 2, 10, cap), ([], 2, 10, 0), ([], 2, -1, cap)):
+        with pytest.raises(B.Gc3Error) as e:
+            plan(*bad)
+        assert e.value.status == B.GC3_ERR_ARG
+
+
 def test_selector_argument_checks_without_a_device():
     sel = B.gc3_selector_create()
     with pytest.raises(B.Gc3Error) as e:
@@ -270,11 +291,16 @@ def test_kernel_resources_of_the_built_library():
     if not os.path.exists(path):
         pytest.skip("library was built without the resource report")
     kernels = [k for k in json.load(open(path)) if "gc3_interpreter" in k["name"]]
-    assert len(kernels) == 12                       # 3 data types x dependencies or not x protocol
+    # 3 data types x dependencies or not x (simple, LL, simple with LDS staging, wavefront-level)
+    assert len(kernels) == 24
     for k in kernels:
         assert k["scratch_bytes"] == 0, k
         assert k["occupancy"] >= 6, k
-        assert k["vgprs"] <= 80 and k["lds_bytes"] <= 16384, k
+        staged = k["lds_bytes"] > 16384               # the staging area is 16 KiB on top of the interpreter's state
+        assert k["vgprs"] <= 80 and k["lds_bytes"] <= (32768 if staged else 16384), k
+    assert sum(k["lds_bytes"] > 16384 for k in kernels) == 6
+    wave = [k for k in kernels if "gc3_interpreter_wave" in k["name"]]
+    assert len(wave) == 6 and all(k["lds_bytes"] <= 2048 for k in wave)
 
 
 def test_compiler_command_line_writes_loadable_programs(tmp_path):
