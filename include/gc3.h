@@ -112,7 +112,8 @@ typedef struct gc3_comm_config {
                               start word that nobody sets, so each run ends, after spin_limit_us, with
                               GC3_ERR_TIMEOUT and all workgroups leaving through the error path */
   int32_t min_lane_bytes;  /* a run splits a chunk over at most chunk bytes / min_lane_bytes lanes (at least
-                              one): small chunks are not worth spreading; multiple of 16, default 8192.  The workgroups of
+                              one): small chunks are not worth spreading; multiple of 16.  0 = automatic: 8192, or
+                              4096 for runs of the wavefront-level interpreter.  The workgroups of
                               the lanes left without bytes then share the thread blocks of the active ones */
   int32_t protocol;        /* Section 6.1 "Protocols".  0 = what the program's `protocol` line says:
                               `simple` (payload, then a separate flag), `ll` (every 8 bytes carry 4 bytes of
@@ -190,7 +191,7 @@ int gc3_comm_create(const gc3_program* prog, const gc3_comm_config* cfg, gc3_com
 int gc3_comm_info_get(const gc3_comm* comm, gc3_comm_info* out);
 
 /* What gc3_comm_tune tried. */
-#define GC3_TUNE_MAX_TRIED 24
+#define GC3_TUNE_MAX_TRIED 40
 typedef struct gc3_tune_entry {
   int32_t team_width;      /* W of the plan */
   int32_t target_wgs;      /* as passed to the planner (0 = default) */
@@ -210,7 +211,8 @@ typedef struct gc3_tune_report {
  * parallelization of every algorithm is tuned for the system and the buffer size; this does it for the
  * parallelization the runtime applies).  For the configuration in `base` (may be null) and for team
  * widths 4..64 x workgroup targets {default, 512, 768}, then for the fastest of them the slot tiles 16, 32
- * and 64 KiB, then workgroups of 128 threads - only over fields `base` leaves 0 - it creates
+ * and 64 KiB, then workgroups of 128 threads, then workgroups of one wavefront (64 threads) with team widths
+ * 16..64 x workgroup targets {2048, 4096} and again the slot tiles - only over fields `base` leaves 0 - it creates
  * a communicator on the current device, binds stand-in buffers of the real sizes (non-zero filler) that it
  * allocates and frees itself, times 5 runs after 2 warm-up runs (8 for the first plan) on `hip_stream`, and writes the
  * chosen configuration to `*best` (ready for gc3_comm_create): the fastest one if it beats `base`,

@@ -67,7 +67,7 @@ class CommInfo(C.Structure):
                 ("wgs_per_lane", C.c_int32), ("protocol", C.c_int32), ("ll_fifo_bytes", C.c_uint64)]
 
 
-GC3_TUNE_MAX_TRIED = 24
+GC3_TUNE_MAX_TRIED = 40
 
 
 class LaunchInfo(C.Structure):

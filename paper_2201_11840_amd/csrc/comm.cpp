@@ -152,8 +152,24 @@ struct Launch {
   uint64_t lane_share = 0;   // largest share a lane has of a chunk, bytes
 };
 
+void shape_run_with(const gc3_comm_info& info, uint64_t cb, uint64_t min_lane_bytes, uint64_t ll_max_lane_bytes,
+                    bool lds_stage, Launch& L);
+
+// min_lane_bytes = 0 selects it per run: 8192 (one sweep of a 128-thread workgroup with four 128-bit accesses
+// in flight per thread), or 4096 (the same for one wavefront) when the run then uses the wavefront-level
+// interpreter - measured on MI355X, ring AllReduce on 8 ranks at 256 KiB: 4 lanes x 8 KiB 45 us, 8 x 4 KiB 38 us.
 void shape_run(const gc3_comm_info& info, uint64_t cb, uint64_t min_lane_bytes, uint64_t ll_max_lane_bytes, bool lds_stage,
                Launch& L) {
+  if (min_lane_bytes != 0) { shape_run_with(info, cb, min_lane_bytes, ll_max_lane_bytes, lds_stage, L); return; }
+  shape_run_with(info, cb, 8192, ll_max_lane_bytes, lds_stage, L);
+  if (L.mode != 3) return;
+  Launch finer = L;
+  shape_run_with(info, cb, 4096, ll_max_lane_bytes, lds_stage, finer);
+  if (finer.mode == 3) L = finer;
+}
+
+void shape_run_with(const gc3_comm_info& info, uint64_t cb, uint64_t min_lane_bytes, uint64_t ll_max_lane_bytes,
+                    bool lds_stage, Launch& L) {
   KParams& p = L.p;
   p.chunk_bytes = cb;
   p.W = (uint32_t)info.team_width;
@@ -191,16 +207,21 @@ void shape_run(const gc3_comm_info& info, uint64_t cb, uint64_t min_lane_bytes, 
   p.wgs_per_lane = (uint32_t)info.wgs_per_lane;
   p.nsplit = std::max<uint32_t>(1, std::min<uint32_t>(p.W / p.W_active, (uint32_t)info.max_fibers_per_wg));
   L.grid = p.W_active * p.nsplit * p.wgs_per_lane;
-  // a lane share of a few KiB is one sweep for two wavefronts: fewer threads to synchronise per instruction
-  // (measured 2-3 % faster up to 8 KiB per lane, slower above)
+  // A lane share of a few KiB is a handful of 128-bit accesses per thread even for one wavefront: such runs are
+  // latency-bound, and fewer threads mean less to synchronise per instruction.  When every workgroup runs a
+  // single fiber, one wavefront per workgroup needs no synchronisation at all (measured on MI355X: ring
+  // AllReduce on 8 ranks up to 1 MiB 44-47 us with 128 threads, 37-39 us with 64); otherwise two wavefronts
+  // (2-3 % faster than four up to 8 KiB per lane, slower above).
   L.block = (unsigned)info.wg_size;
-  if (L.block > 128 && lane_share <= 8192) L.block = 128;
+  const bool single_fiber = (uint32_t)info.max_fibers_per_wg <= p.nsplit;
+  if (lane_share <= 8192 && !L.ll && !lds_stage && single_fiber) L.block = 64;
+  else if (L.block > 128 && lane_share <= 8192) L.block = 128;
   // Instantiation: LL, or payload staged through LDS, or - for workgroups of one wavefront that each run one
   // fiber - the wavefront-level interpreter, or the general one.
   L.mode = 0;
   if (L.ll) L.mode = 1;
   else if (lds_stage) L.mode = 2;
-  else if (L.block == 64 && (uint32_t)info.max_fibers_per_wg <= p.nsplit) L.mode = 3;
+  else if (L.block == 64 && single_fiber) L.mode = 3;
 }
 
 }  // namespace
@@ -579,13 +600,39 @@ int gc3_comm_tune(const gc3_program* prog, const gc3_comm_config* base, size_t e
       if ((rc = try_config(cfg)) != GC3_OK) return rc;
     }
   }
-  // pass 3: smaller workgroups (less to synchronise per instruction; pays on latency-bound sizes)
+  // pass 3: smaller workgroups for the winner (less to synchronise per instruction)
   if (have && cfg0.wg_size == 0) {
     gc3_comm_config cfg = *best;
     cfg.wg_size = 128;
     seen.clear();        // a plan of another workgroup size is a different plan even if W, grid and tile agree
     seen.emplace_back(-1, -1, -1);   // (keeps the longer warm-up for the very first plan only)
     if ((rc = try_config(cfg)) != GC3_OK) return rc;
+  }
+  // pass 4: workgroups of one wavefront.  Where every workgroup then runs a single fiber the wavefront-level
+  // interpreter is used (no barriers); four times as many workgroups fit the device, so wider teams and larger
+  // workgroup targets come into reach (All Pairs AllReduce at 64 MiB: 4.8 -> 6.2 TB/s on MI355X).
+  if (have && cfg0.wg_size == 0) {
+    seen.clear();
+    seen.emplace_back(-1, -1, -1);
+    for (int w : {16, 32, 64})
+      for (int t : {2048, 4096}) {
+        if ((cfg0.team_width && cfg0.team_width != w) || (cfg0.target_wgs && cfg0.target_wgs != t)) continue;
+        gc3_comm_config cfg = cfg0;
+        cfg.wg_size = 64;
+        cfg.team_width = w;
+        cfg.target_wgs = t;
+        if ((rc = try_config(cfg)) != GC3_OK) return rc;
+      }
+    if (best->wg_size == 64 && cfg0.tile_bytes == 0) {
+      const gc3_comm_config winner = *best;
+      const int winner_tile = best_tile;
+      for (int tile : {16384, 32768, 65536}) {
+        if (tile == winner_tile) continue;
+        gc3_comm_config cfg = winner;
+        cfg.tile_bytes = tile;
+        if ((rc = try_config(cfg)) != GC3_OK) return rc;
+      }
+    }
   }
   if (!have) {
     set_error("no configuration could be timed: " + last_msg);

@@ -41,8 +41,8 @@ int resolve_config(const gc3_comm_config* cfg_in, gc3_comm_config& cfg, std::str
     msg = "ll_max_lane_bytes must be a multiple of 16 in [16, 65536]";
     return GC3_ERR_ARG;
   }
-  if (cfg.min_lane_bytes == 0) cfg.min_lane_bytes = 8192;
-  if (cfg.min_lane_bytes < 16 || cfg.min_lane_bytes % 16) { msg = "min_lane_bytes must be a positive multiple of 16"; return GC3_ERR_ARG; }
+  // (0 stays 0 = automatic: 8192, or 4096 for runs of the wavefront-level interpreter; decided per run)
+  if (cfg.min_lane_bytes != 0 && (cfg.min_lane_bytes < 16 || cfg.min_lane_bytes % 16)) { msg = "min_lane_bytes must be a positive multiple of 16"; return GC3_ERR_ARG; }
   return GC3_OK;
 }
 

@@ -405,3 +405,29 @@ def alltonext(N: int, G: int, name: Optional[str] = None) -> Program:
             else:
                 prog.tb(j, recv=relay1, chan=k).add("recv", dst=("o", k))
     return prog
+
+
+# ---------------------------------------------------------------------------
+# Local instructions on their own (Section 4.2: copy and reduce without any connection)
+# ---------------------------------------------------------------------------
+
+def local_stream(R: int, tbs_per_rank: int = 8, reduce: bool = False, name: Optional[str] = None) -> Program:
+    """No communication at all, thread block j of `tbs_per_rank` on every rank handling its own chunks, no FIFO,
+    no flag.  `copy`: out of place, output chunk j = input chunk j.  `reduce`: in place on 2 x tbs_per_rank
+    chunks, chunk j += chunk tbs_per_rank + j (two streams read, one written).  Over buffers larger than the
+    memory-side cache this is the rate at which the interpreter streams device memory, i.e. the ceiling for
+    the user-buffer part of every collective's traffic."""
+    if R < 1 or tbs_per_rank < 1:
+        raise ValueError("bad shape")
+    T = tbs_per_rank
+    if reduce:
+        prog = Program(name or f"local_reduce_r{R}_x{T}", "custom", R, 2 * T, 2 * T, inplace=True)
+        for r in range(R):
+            for j in range(T):
+                prog.tb(r, chan=j).add("reduce", src=("i", T + j), dst=("i", j))
+        return prog
+    prog = Program(name or f"local_copy_r{R}_x{T}", "custom", R, T, T, inplace=False)
+    for r in range(R):
+        for j in range(T):
+            prog.tb(r, chan=j).add("copy", src=("i", j), dst=("o", j))
+    return prog

@@ -86,5 +86,15 @@ def next_row_workloads() -> List[Workload]:
     ]
 
 
+def dram_workloads() -> List[Workload]:
+    """The local `copy` and `reduce` instructions on their own (no connection, no FIFO) over 2 - 4 GiB of buffers,
+    8 to 16 times the 256 MiB memory-side cache: what device memory sustains for the interpreter's tile moves."""
+    return [
+        Workload("local_copy_r8_f32_256MiB", lambda: programs.local_stream(8, 8), "f32", 256 * MiB, "uniform", 67840),
+        Workload("local_reduce_r8_f32_256MiB", lambda: programs.local_stream(8, 8, reduce=True), "f32", 256 * MiB,
+                 "uniform", 67841),
+    ]
+
+
 def by_name() -> Dict[str, Workload]:
-    return {w.name: w for w in all_workloads() + next_row_workloads()}
+    return {w.name: w for w in all_workloads() + next_row_workloads() + dram_workloads()}

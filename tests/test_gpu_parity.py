@@ -226,6 +226,16 @@ def test_many_ranks_and_thread_blocks():
         run_case(prog, dt, prog.in_chunks * 4096 // inputs.ITEMSIZE[dt], "normal", 5, None, exact_only=exact)
 
 
+def test_local_instructions_without_any_connection():
+    # the streaming programs bench.py uses for its device-memory ceiling: copy and reduce only, no FIFO, no flag
+    for dtype in ("f32", "bf16"):
+        m = 4 // inputs.ITEMSIZE[dtype]
+        run_case(programs.local_stream(3, 2), dtype, 2 * 2500 * m, "normal", 1500, small_cfg(), exact_only=True)
+        run_case(programs.local_stream(3, 2, reduce=True), dtype, 4 * 2500 * m, "normal", 1501, small_cfg())
+        run_case(programs.local_stream(8, 8), dtype, 8 * 50000 * m, "normal", 1502, exact_only=True)
+        run_case(programs.local_stream(8, 8, reduce=True), dtype, 16 * 50000 * m, "uniform", 1503)
+
+
 # ---- edge cases ------------------------------------------------------------------------------------
 
 def test_instruction_lists_longer_than_the_workgroup_cache():

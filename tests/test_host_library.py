@@ -41,6 +41,7 @@ def generated():
     out += [programs.hierarchical_allreduce(N, G) for N, G in ((2, 2), (2, 3), (3, 2), (2, 8), (3, 8))]
     out += [programs.alltonext(N, G) for N, G in ((1, 1), (1, 4), (4, 1), (3, 8))]
     out += [programs.twostep_alltoall(N, G) for N, G in ((1, 4), (4, 1), (2, 3), (3, 8))]
+    out += [programs.local_stream(8), programs.local_stream(3, 2, reduce=True)]
     return out
 
 
