@@ -53,7 +53,8 @@ typedef enum gc3_status {
   GC3_ERR_TIMEOUT = -7,          /* a wait inside the kernel exceeded the spin limit */
   GC3_ERR_HIP = -8,              /* a HIP runtime call failed */
   GC3_ERR_ARG = -9,              /* bad argument (null pointer, out-of-range value) */
-  GC3_ERR_POISONED = -10         /* communicator had a failed run; call gc3_comm_reset */
+  GC3_ERR_POISONED = -10,        /* communicator had a failed run; call gc3_comm_reset */
+  GC3_ERR_PLACEMENT = -11        /* die-scope FIFOs: the two ends of a connection did not run on one die */
 } gc3_status;
 
 typedef enum gc3_dtype { GC3_F32 = 0, GC3_F16 = 1, GC3_BF16 = 2 } gc3_dtype;
@@ -122,6 +123,21 @@ typedef struct gc3_comm_config {
                               2 = force LL, 3 = force auto */
   int32_t ll_max_lane_bytes; /* `auto` switches to LL up to this many bytes per lane and chunk; also the LL
                               tile size; multiple of 16, at most 65536; default 8192 */
+  int32_t fifo_scope;      /* where FIFO payload lives (Section 6.1: the remote buffer of a connection).
+                              0 or 1 = device scope: slots are written through to the memory system and read from
+                              there, valid wherever the two ends of a connection run.
+                              2 = die scope: consecutive workgroups run on consecutive dies (XCDs) round-robin,
+                              so a run whose number of active lanes is a multiple of 8 is launched bin-major
+                              (workgroup = bin x active lanes + lane): lane w of every thread block then runs on die
+                              w mod 8, both ends of every connection share a die, and the payload is read from
+                              that die's L2 (plain stores, loads that bypass the compute unit's L1) instead of
+                              from the memory system.  It pays while the slots of a die fit its 4 MiB L2, so the
+                              slot tile defaults to the largest of 64 ... 4 KiB with which all FIFOs together stay
+                              within 16 MiB.  Simple protocol only; runs with another number of active lanes, or
+                              that split fiber lists over idle lanes' workgroups (small chunks), use device scope.
+                              Every receiver checks at run time that it shares its sender's die and abandons the
+                              run with GC3_ERR_PLACEMENT otherwise */
+  int32_t reserved1;       /* must be 0 */
 } gc3_comm_config;
 
 typedef struct gc3_comm_info {
@@ -191,7 +207,7 @@ int gc3_comm_create(const gc3_program* prog, const gc3_comm_config* cfg, gc3_com
 int gc3_comm_info_get(const gc3_comm* comm, gc3_comm_info* out);
 
 /* What gc3_comm_tune tried. */
-#define GC3_TUNE_MAX_TRIED 40
+#define GC3_TUNE_MAX_TRIED 48
 typedef struct gc3_tune_entry {
   int32_t team_width;      /* W of the plan */
   int32_t target_wgs;      /* as passed to the planner (0 = default) */
@@ -199,6 +215,8 @@ typedef struct gc3_tune_entry {
   int32_t active_wgs;      /* of them, workgroups that hold work */
   int32_t tile_bytes;      /* slot tile of the plan */
   int32_t wg_size;         /* threads per workgroup */
+  int32_t fifo_scope;      /* 1 device, 2 die */
+  int32_t reserved;
   double ms;               /* mean duration of one run */
 } gc3_tune_entry;
 typedef struct gc3_tune_report {
@@ -212,7 +230,8 @@ typedef struct gc3_tune_report {
  * parallelization the runtime applies).  For the configuration in `base` (may be null) and for team
  * widths 4..64 x workgroup targets {default, 512, 768}, then for the fastest of them the slot tiles 16, 32
  * and 64 KiB, then workgroups of 128 threads, then workgroups of one wavefront (64 threads) with team widths
- * 16..64 x workgroup targets {2048, 4096} and again the slot tiles - only over fields `base` leaves 0 - it creates
+ * 16..64 x workgroup targets {2048, 4096} and again the slot tiles, then die-scope FIFOs with 64, 128 and 256
+ * threads x team widths 8..64 and their slot tiles - only over fields `base` leaves 0 - it creates
  * a communicator on the current device, binds stand-in buffers of the real sizes (non-zero filler) that it
  * allocates and frees itself, times 5 runs after 2 warm-up runs (8 for the first plan) on `hip_stream`, and writes the
  * chosen configuration to `*best` (ready for gc3_comm_create): the fastest one if it beats `base`,
@@ -248,6 +267,9 @@ typedef struct gc3_launch_info {
   int32_t tile_bytes;     /* bytes of one chunk a fiber moves per tile in this run */
   int32_t kernel;         /* 0 general interpreter, 1 LL protocol, 2 FIFO payload staged through LDS,
                              3 wavefront-level interpreter (one wavefront, one thread-block lane per workgroup) */
+  int32_t die_scope;      /* 1 = this run reads FIFO payload from the dies' L2s (fifo_scope 2, active lanes a
+                             multiple of 8, no split) and is launched bin-major */
+  int32_t reserved;
   uint64_t lane_bytes;    /* largest share a lane has of one chunk */
 } gc3_launch_info;
 

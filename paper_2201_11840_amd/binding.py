@@ -24,6 +24,8 @@ GC3_ERR_TIMEOUT = -7
 GC3_ERR_HIP = -8
 GC3_ERR_ARG = -9
 GC3_ERR_POISONED = -10
+GC3_ERR_PLACEMENT = -11
+FIFO_DEVICE, FIFO_DIE = 1, 2
 
 GC3_F32, GC3_F16, GC3_BF16 = 0, 1, 2
 GC3_SUM = 0
@@ -48,15 +50,17 @@ class CommConfig(C.Structure):
     _fields_ = [("fifo_slots", C.c_int32), ("tile_bytes", C.c_int32), ("team_width", C.c_int32),
                 ("wg_size", C.c_int32), ("lds_stage", C.c_int32), ("target_wgs", C.c_int32),
                 ("spin_limit_us", C.c_uint64), ("debug_hold", C.c_int32), ("min_lane_bytes", C.c_int32),
-                ("protocol", C.c_int32), ("ll_max_lane_bytes", C.c_int32)]
+                ("protocol", C.c_int32), ("ll_max_lane_bytes", C.c_int32), ("fifo_scope", C.c_int32),
+                ("reserved1", C.c_int32)]
 
 
 def make_config(fifo_slots: int = 0, tile_bytes: int = 0, team_width: int = 0, wg_size: int = 0,
                 spin_limit_us: int = 0, target_wgs: int = 0, debug_hold: int = 0,
-                min_lane_bytes: int = 0, protocol: int = 0, ll_max_lane_bytes: int = 0, lds_stage: int = 0) -> CommConfig:
+                min_lane_bytes: int = 0, protocol: int = 0, ll_max_lane_bytes: int = 0, lds_stage: int = 0,
+                fifo_scope: int = 0) -> CommConfig:
     """A gc3_comm_config; zero fields select the library's defaults."""
     return CommConfig(fifo_slots, tile_bytes, team_width, wg_size, lds_stage, target_wgs, spin_limit_us,
-                      debug_hold, min_lane_bytes, protocol, ll_max_lane_bytes)
+                      debug_hold, min_lane_bytes, protocol, ll_max_lane_bytes, fifo_scope, 0)
 
 
 class CommInfo(C.Structure):
@@ -67,12 +71,13 @@ class CommInfo(C.Structure):
                 ("wgs_per_lane", C.c_int32), ("protocol", C.c_int32), ("ll_fifo_bytes", C.c_uint64)]
 
 
-GC3_TUNE_MAX_TRIED = 40
+GC3_TUNE_MAX_TRIED = 48
 
 
 class LaunchInfo(C.Structure):
     _fields_ = [("grid", C.c_int32), ("wg_size", C.c_int32), ("active_lanes", C.c_int32), ("split", C.c_int32),
-                ("tile_bytes", C.c_int32), ("kernel", C.c_int32), ("lane_bytes", C.c_uint64)]
+                ("tile_bytes", C.c_int32), ("kernel", C.c_int32), ("die_scope", C.c_int32), ("reserved", C.c_int32),
+                ("lane_bytes", C.c_uint64)]
 
 
 KERNEL_GENERAL, KERNEL_LL, KERNEL_STAGED, KERNEL_WAVE = 0, 1, 2, 3
@@ -84,7 +89,8 @@ class InFlight(C.Structure):
 
 class TuneEntry(C.Structure):
     _fields_ = [("team_width", C.c_int32), ("target_wgs", C.c_int32), ("grid", C.c_int32),
-                ("active_wgs", C.c_int32), ("tile_bytes", C.c_int32), ("wg_size", C.c_int32), ("ms", C.c_double)]
+                ("active_wgs", C.c_int32), ("tile_bytes", C.c_int32), ("wg_size", C.c_int32), ("fifo_scope", C.c_int32),
+                ("reserved", C.c_int32), ("ms", C.c_double)]
 
 
 class TuneReport(C.Structure):

@@ -50,7 +50,9 @@ struct DFiber {            // 32 bytes: one lane of one IR thread block
   uint32_t fid;            // global thread-block index * W + lane
   uint32_t instr_begin, ninstr;
   int32_t send_conn, recv_conn;  // connection index or -1
-  uint32_t pad[3];
+  uint32_t recv_from_tb;   // global index of the thread block at the sending end of recv_conn (die-scope FIFOs:
+                           // the receiver checks that it runs on the sender's die), 0xffffffff if none
+  uint32_t pad[2];
 };
 
 struct KParams {
@@ -63,7 +65,8 @@ struct KParams {
   unsigned char* ll_fifo;  // the same for the LL protocol, slots of ll_slot_bytes (data + flag pairs only)
   uint64_t* flags;         // [((conn*W + lane)*2 + {0 tail, 1 head}) * kFlagStrideWords]
   uint64_t* sems;          // [(tb*W + lane) * kFlagStrideWords]: word 0 the semaphore, word 1 the fiber's epoch
-                           // (runs it has completed); flag values of a run lie above (epoch + 1) << 32
+                           // (runs it has completed); flag values of a run lie above (epoch + 1) << 32;
+                           // word 2 (die-scope FIFOs) the die the fiber runs on in this run, as run base + die + 1
   uint32_t* error;         // 0 = fine, else a gc3_status (negated) set by the first failing workgroup
   const uint32_t* hold;    // null, or a start word every workgroup waits for (failure-path tests)
   uint64_t chunk_bytes;
@@ -75,6 +78,9 @@ struct KParams {
   uint32_t wgs_per_lane;   // workgroups per lane of the static plan (the grid is lane-major)
   uint32_t nsplit;         // in this run the fiber list of every (lane, bin) is dealt round-robin to this many
                            // workgroups (1 = as planned); uses the workgroups of lanes that own no bytes
+  uint32_t bin_major;      // 0: workgroup = (sub * W_active + lane) * wgs_per_lane + bin.  1 (die-scope FIFOs, needs
+                           // W_active a multiple of 8 and nsplit 1): workgroup = bin * W_active + lane, so that lane w of
+                           // every thread block runs on die w mod 8 (consecutive workgroups go to consecutive dies)
 };
 
 }  // namespace gc3

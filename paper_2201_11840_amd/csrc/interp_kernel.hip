@@ -274,6 +274,23 @@ namespace {
 constexpr int kSimple = 0;   // payload, completion wait, separate flag; payload moves through registers
 constexpr int kLL = 1;       // every 8 bytes carry 4 bytes of data and a 4-byte flag
 constexpr int kStaged = 2;   // simple protocol, FIFO payload of the receiving instructions staged through LDS
+constexpr int kDie = 3;      // simple protocol, FIFO payload kept in the L2 of the die both ends of a connection run on
+
+// Die-scope FIFO payload.  Such a run is launched bin-major with a multiple of 8 active lanes, so that the two ends
+// of every connection - always the same lane of two thread blocks - run on one die (XCD), whose L2 all its compute
+// units share.  The sender writes slots with plain stores - through the compute unit's L1 into that L2, complete
+// when the store counter retires - and the receiver reads them with non-temporal loads, which never hit in its L1
+// (MISS_EVICT policy) and find the line in the shared L2: FIFO reads no longer cross the fabric (measured: 94 % of
+// them with 2 MiB of slots per die; the writes are still written back to memory).  A line evicted in between is
+// simply fetched again.  Flags stay device-scope atomics.  Because a receiver on another die would silently read
+// stale memory, every fiber publishes the die it runs on and every receiver checks it against its own before its
+// first pop.
+constexpr int kDieSlotLd = kPolNt, kDieSlotSt = 0;
+
+__device__ __forceinline__ uint32_t this_die() {
+  // XCC_ID hardware register (id 20), bits 3:0
+  return (uint32_t)__builtin_amdgcn_s_getreg(20 | (0 << 6) | ((4 - 1) << 11)) & 0xfu;
+}
 
 __device__ __forceinline__ uint64_t* flag_of(const KParams& p, int32_t conn, uint32_t lane, uint32_t which) {
   return p.flags + ((uint64_t)((uint32_t)conn * p.W + lane) * 2 + which) * kFlagStrideWords;
@@ -350,12 +367,12 @@ __device__ __forceinline__ int poll_flags(const KParams& p, uint32_t lane_id, bo
 
 // One tile of one instruction under the simple protocol: `count` pieces of `len` bytes, piece j at
 // srcb / dstb + j * chunk_bytes in the user buffers and packed back to back in the FIFO slots.
-template <int DT, bool COH, bool STAGE>
+template <int DT, bool COH, bool STAGE, bool DIE>
 __device__ __forceinline__ void move_simple(uint32_t op, uint32_t count, unsigned char* srcb, unsigned char* dstb,
                                             unsigned char* rslot, unsigned char* sslot, uint32_t len,
                                             uint64_t chunk_bytes, uint32_t tid, uint32_t nthreads, unsigned char* stage) {
   constexpr int UL = COH ? kUserLdCoh : kUserLd, US = COH ? kUserStCoh : kUserSt;
-  constexpr int SL = kSlotLd, SS = kSlotSt;
+  constexpr int SL = DIE ? kDieSlotLd : kSlotLd, SS = DIE ? kDieSlotSt : kSlotSt;
   const uint32_t nvec = len >> 4;
   for (uint32_t j = 0; j < count; ++j) {
     const rsrc_t src = make_rsrc(srcb + (uint64_t)j * chunk_bytes, srcb ? len : 0);
@@ -409,12 +426,14 @@ template <int DT, bool COH, int MODE>
 __global__ void __launch_bounds__(512) gc3_interpreter(KParams p) {
   constexpr bool LL = MODE == kLL;
   constexpr bool STAGE = MODE == kStaged;
+  constexpr bool DIE = MODE == kDie;
   __shared__ uint32_t f_id[kMaxFibersPerWg], f_t[kMaxFibersPerWg], f_s[kMaxFibersPerWg];
   __shared__ uint32_t f_send[kMaxFibersPerWg], f_recv[kMaxFibersPerWg];
   // messages of this run the fiber's receiver is known to have consumed (last head flag value seen): a push
   // polls the head flag only when this does not already show a free slot
   __shared__ uint32_t f_head[kMaxFibersPerWg];
   __shared__ uint32_t f_epoch[kMaxFibersPerWg];    // runs the fiber has completed before this one
+  __shared__ uint32_t f_from[kMaxFibersPerWg];     // thread block at the sending end of the fiber's receive connection
   __shared__ uint32_t s_headv[2];
   __shared__ uint64_t f_off0[kMaxFibersPerWg], f_share[kMaxFibersPerWg];
   // per fiber: its thread block's record and the three buffer pointers of its rank, fetched once
@@ -429,8 +448,9 @@ __global__ void __launch_bounds__(512) gc3_interpreter(KParams p) {
   __shared__ __attribute__((aligned(16))) unsigned char s_stage[STAGE ? kStageBytes : 16];
   const uint32_t tid = threadIdx.x, nthreads = blockDim.x;
   // blockIdx = (sub * W_active + lane) * wgs_per_lane + bin: this workgroup takes entries sub, sub + nsplit, ...
-  // of the fiber list the plan gives (lane, bin)
-  const uint32_t slot = blockIdx.x / p.wgs_per_lane, bin = blockIdx.x % p.wgs_per_lane;
+  // of the fiber list the plan gives (lane, bin); or, bin-major, blockIdx = bin * W_active + lane
+  const uint32_t slot = p.bin_major ? blockIdx.x % p.W_active : blockIdx.x / p.wgs_per_lane;
+  const uint32_t bin = p.bin_major ? blockIdx.x / p.W_active : blockIdx.x % p.wgs_per_lane;
   const uint32_t sub = slot / p.W_active, nsplit = p.nsplit;
   const DWg hdr = p.wgs[(slot % p.W_active) * p.wgs_per_lane + bin];
   const uint32_t nf = hdr.nfibers > sub ? (hdr.nfibers - sub + nsplit - 1) / nsplit : 0;
@@ -454,7 +474,10 @@ __global__ void __launch_bounds__(512) gc3_interpreter(KParams p) {
     f_send[tid] = 0;
     f_recv[tid] = 0;
     f_head[tid] = 0;
-    f_epoch[tid] = (uint32_t)load_flag(p.sems + (uint64_t)f.fid * kFlagStrideWords + 1);
+    const uint32_t epoch = (uint32_t)load_flag(p.sems + (uint64_t)f.fid * kFlagStrideWords + 1);
+    f_epoch[tid] = epoch;
+    f_from[tid] = f.recv_from_tb;
+    if (DIE) store_flag(p.sems + (uint64_t)f.fid * kFlagStrideWords + 2, ((uint64_t)(epoch + 1) << 32) + this_die() + 1);
     f_off0[tid] = o;
     f_share[tid] = lane_begin(p.chunk_bytes, lane + 1, p.W_active) - o;
     f_ninstr[tid] = f.ninstr;
@@ -534,6 +557,13 @@ __global__ void __launch_bounds__(512) gc3_interpreter(KParams p) {
             // (only more than 62 dependencies would take the polling past its first round, in which lane 1
             // polls the head flag)
             if (tid == 1 && wait_slot && res == 1 && ndeps <= 62) s_headv[phase & 1] = (uint32_t)(seen - run_base);
+            if (DIE && pops && recv_seq == 0 && res == 1 && tid == 0) {
+              // first message of this run on this connection: the sender published its die before the message
+              if (load_flag(sem_of(p, uni(f_from[fi]), lane) + 2) != run_base + this_die() + 1) {
+                atomicCAS(p.error, 0u, (uint32_t)(-GC3_ERR_PLACEMENT));
+                res = -1;
+              }
+            }
             if (LL && pops && !block && res == 1) {
               // non-blocking readiness probe: has the first element of the message arrived?
               const uint32_t* first = (const uint32_t*)(fifo_recv + (uint64_t)(recv_seq % p.slots) * slot_bytes);
@@ -574,7 +604,7 @@ __global__ void __launch_bounds__(512) gc3_interpreter(KParams p) {
             }
           }
         } else {
-          move_simple<DT, COH, STAGE>(op, ins.count, srcb, dstb, rslot, sslot, len, p.chunk_bytes, tid, nthreads, s_stage);
+          move_simple<DT, COH, STAGE, DIE>(op, ins.count, srcb, dstb, rslot, sslot, len, p.chunk_bytes, tid, nthreads, s_stage);
         }
 
         // ---- publish: slot filled, slot freed, semaphore ----------------------------------------
@@ -648,11 +678,12 @@ __global__ void __launch_bounds__(512) gc3_interpreter(KParams p) {
 // anywhere on the path of a hop.  This is the instantiation for latency-bound sizes, where a lane's share of a
 // chunk is a few 128-bit accesses per thread.
 constexpr int kWaveLdsInstrs = 64;
-template <int DT, bool COH>
+template <int DT, bool COH, bool DIE>
 __global__ void __launch_bounds__(64) gc3_interpreter_wave(KParams p) {
   __shared__ uint32_t s_instr[kWaveLdsInstrs * 8];
   const uint32_t tid = threadIdx.x;
-  const uint32_t slot = blockIdx.x / p.wgs_per_lane, bin = blockIdx.x % p.wgs_per_lane;
+  const uint32_t slot = p.bin_major ? blockIdx.x % p.W_active : blockIdx.x / p.wgs_per_lane;
+  const uint32_t bin = p.bin_major ? blockIdx.x / p.W_active : blockIdx.x % p.wgs_per_lane;
   const uint32_t sub = slot / p.W_active;
   const DWg hdr = p.wgs[(slot % p.W_active) * p.wgs_per_lane + bin];
   if (hdr.nfibers <= sub) return;                     // (the host launches this kernel only when nfibers <= nsplit)
@@ -669,6 +700,8 @@ __global__ void __launch_bounds__(64) gc3_interpreter_wave(KParams p) {
   uint64_t* const my_sem = sem_of(p, tbi, lane);
   const uint32_t epoch = uni((uint32_t)load_flag(my_sem + 1));
   const uint64_t run_base = (uint64_t)(epoch + 1) << 32;
+  const uint32_t recv_from_tb = uni(f.recv_from_tb);
+  if (DIE && tid == 0) store_flag(my_sem + 2, run_base + this_die() + 1);
   unsigned char* bufs[3];
 #pragma unroll
   for (int k = 0; k < 3; ++k) bufs[k] = (unsigned char*)uni64((uint64_t)p.bufs[hdr.rank * 3 + k]);
@@ -713,13 +746,22 @@ __global__ void __launch_bounds__(64) gc3_interpreter_wave(KParams p) {
                                    ins.dep_begin, ndeps, lane, run_base, t, seen);
         if (res < 0) return;                           // (the same value in every lane: decided by wavefront votes)
         if (wait_slot && ndeps <= 62) head_known = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(seen - run_base), 1);
+        if (DIE && pops && recv_seq == 0) {
+          // first message of this run on this connection: the sender published its die before the message
+          uint32_t same = 1;
+          if (tid == 0) {
+            same = load_flag(sem_of(p, recv_from_tb, lane) + 2) == run_base + this_die() + 1 ? 1u : 0u;
+            if (!same) atomicCAS(p.error, 0u, (uint32_t)(-GC3_ERR_PLACEMENT));
+          }
+          if (!uni(same)) return;
+        }
       }
       const uint64_t coff = off0 + toff;
       unsigned char* const srcb = ins.srcbuf < 3 ? bufs[ins.srcbuf] + (uint64_t)ins.srcidx * p.chunk_bytes + coff : nullptr;
       unsigned char* const dstb = ins.dstbuf < 3 ? bufs[ins.dstbuf] + (uint64_t)ins.dstidx * p.chunk_bytes + coff : nullptr;
       unsigned char* const rslot = pops ? fifo_recv + (uint64_t)(recv_seq % p.slots) * p.slot_bytes : nullptr;
       unsigned char* const sslot = pushes ? fifo_send + (uint64_t)(send_seq % p.slots) * p.slot_bytes : nullptr;
-      move_simple<DT, COH, false>(op, ins.count, srcb, dstb, rslot, sslot, len, p.chunk_bytes, tid, 64, nullptr);
+      move_simple<DT, COH, false, DIE>(op, ins.count, srcb, dstb, rslot, sslot, len, p.chunk_bytes, tid, 64, nullptr);
       if (pushes) ++send_seq;
       if (pops) ++recv_seq;
       if (pushes || pops || hasdep) {
@@ -739,40 +781,48 @@ __global__ void __launch_bounds__(64) gc3_interpreter_wave(KParams p) {
 
 // Host-callable launcher; returns the hipError_t of the launch.  `coherent_user` selects the
 // instantiation for programs with cross-thread-block dependencies; `mode`: 0 simple, 1 LL, 2 simple with the
-// FIFO payload staged through LDS, 3 the one-wavefront one-fiber interpreter (block must be 64).
+// FIFO payload staged through LDS, 3 the one-wavefront one-fiber interpreter (block must be 64); `die_scope`
+// (modes 0 and 3): FIFO payload kept in the L2 of the die both ends of a connection run on.
 template <int DT>
-static int launch_dt(bool coh, int mode, unsigned grid, unsigned block, hipStream_t st, const KParams& p) {
+static int launch_dt(bool coh, int mode, bool die, unsigned grid, unsigned block, hipStream_t st, const KParams& p) {
 #define GC3_LAUNCH(K) hipLaunchKernelGGL((K), dim3(grid), dim3(block), 0, st, p)
-  switch (mode * 2 + (coh ? 1 : 0)) {
+  if (die && mode != 0 && mode != 3) return (int)hipErrorInvalidValue;
+  switch ((die ? 4 : mode) * 2 + (coh ? 1 : 0) + (die && mode == 3 ? 2 : 0)) {
     case 0: GC3_LAUNCH((gc3_interpreter<DT, false, kSimple>)); break;
     case 1: GC3_LAUNCH((gc3_interpreter<DT, true, kSimple>)); break;
     case 2: GC3_LAUNCH((gc3_interpreter<DT, false, kLL>)); break;
     case 3: GC3_LAUNCH((gc3_interpreter<DT, true, kLL>)); break;
     case 4: GC3_LAUNCH((gc3_interpreter<DT, false, kStaged>)); break;
     case 5: GC3_LAUNCH((gc3_interpreter<DT, true, kStaged>)); break;
-    case 6: GC3_LAUNCH((gc3_interpreter_wave<DT, false>)); break;
-    case 7: GC3_LAUNCH((gc3_interpreter_wave<DT, true>)); break;
+    case 6: GC3_LAUNCH((gc3_interpreter_wave<DT, false, false>)); break;
+    case 7: GC3_LAUNCH((gc3_interpreter_wave<DT, true, false>)); break;
+    case 8: GC3_LAUNCH((gc3_interpreter<DT, false, kDie>)); break;
+    case 9: GC3_LAUNCH((gc3_interpreter<DT, true, kDie>)); break;
+    case 10: GC3_LAUNCH((gc3_interpreter_wave<DT, false, true>)); break;
+    case 11: GC3_LAUNCH((gc3_interpreter_wave<DT, true, true>)); break;
     default: return (int)hipErrorInvalidValue;
   }
 #undef GC3_LAUNCH
   return (int)hipGetLastError();
 }
 
-int launch_interpreter(int dtype, bool coherent_user, int mode, unsigned grid, unsigned block, void* stream, const KParams& p) {
+int launch_interpreter(int dtype, bool coherent_user, int mode, bool die_scope, unsigned grid, unsigned block, void* stream,
+                       const KParams& p) {
   hipStream_t st = (hipStream_t)stream;
   if (mode == 3 && block != 64) return (int)hipErrorInvalidValue;
   switch (dtype) {
-    case GC3_F32: return launch_dt<GC3_F32>(coherent_user, mode, grid, block, st, p);
-    case GC3_F16: return launch_dt<GC3_F16>(coherent_user, mode, grid, block, st, p);
-    case GC3_BF16: return launch_dt<GC3_BF16>(coherent_user, mode, grid, block, st, p);
+    case GC3_F32: return launch_dt<GC3_F32>(coherent_user, mode, die_scope, grid, block, st, p);
+    case GC3_F16: return launch_dt<GC3_F16>(coherent_user, mode, die_scope, grid, block, st, p);
+    case GC3_BF16: return launch_dt<GC3_BF16>(coherent_user, mode, die_scope, grid, block, st, p);
     default: return (int)hipErrorInvalidValue;
   }
 }
 
-// Occupancy of the interpreter (workgroups of `block` threads per compute unit), minimum over the
-// instantiations that a communicator with this block size may launch: the LDS-staged ones when `staged`,
-// else the register-path ones (both protocols, and the wavefront-level kernel for 64 threads).
-int interpreter_occupancy(unsigned block, bool staged, int* out) {
+// Occupancy of the interpreter (workgroups of `block` threads per compute unit), minimum over the instantiations
+// that a communicator of this kind may launch.  kind 0: simple and LL protocol through registers, device-scope
+// FIFOs (and the wavefront-level kernel for 64 threads); 1: FIFO payload staged through LDS; 2: die-scope FIFOs
+// (and, for runs that fall back to it, device scope).
+int interpreter_occupancy(unsigned block, int kind, int* out) {
   int best = 1 << 30;
   const void* plain[] = {
       (const void*)gc3_interpreter<GC3_F32, false, kSimple>, (const void*)gc3_interpreter<GC3_F32, true, kSimple>,
@@ -781,14 +831,22 @@ int interpreter_occupancy(unsigned block, bool staged, int* out) {
       (const void*)gc3_interpreter<GC3_F32, false, kLL>, (const void*)gc3_interpreter<GC3_F32, true, kLL>,
       (const void*)gc3_interpreter<GC3_F16, false, kLL>, (const void*)gc3_interpreter<GC3_F16, true, kLL>,
       (const void*)gc3_interpreter<GC3_BF16, false, kLL>, (const void*)gc3_interpreter<GC3_BF16, true, kLL>};
+  const void* die[] = {
+      (const void*)gc3_interpreter<GC3_F32, false, kDie>, (const void*)gc3_interpreter<GC3_F32, true, kDie>,
+      (const void*)gc3_interpreter<GC3_F16, false, kDie>, (const void*)gc3_interpreter<GC3_F16, true, kDie>,
+      (const void*)gc3_interpreter<GC3_BF16, false, kDie>, (const void*)gc3_interpreter<GC3_BF16, true, kDie>};
   const void* with_stage[] = {
       (const void*)gc3_interpreter<GC3_F32, false, kStaged>, (const void*)gc3_interpreter<GC3_F32, true, kStaged>,
       (const void*)gc3_interpreter<GC3_F16, false, kStaged>, (const void*)gc3_interpreter<GC3_F16, true, kStaged>,
       (const void*)gc3_interpreter<GC3_BF16, false, kStaged>, (const void*)gc3_interpreter<GC3_BF16, true, kStaged>};
   const void* wave[] = {
-      (const void*)gc3_interpreter_wave<GC3_F32, false>, (const void*)gc3_interpreter_wave<GC3_F32, true>,
-      (const void*)gc3_interpreter_wave<GC3_F16, false>, (const void*)gc3_interpreter_wave<GC3_F16, true>,
-      (const void*)gc3_interpreter_wave<GC3_BF16, false>, (const void*)gc3_interpreter_wave<GC3_BF16, true>};
+      (const void*)gc3_interpreter_wave<GC3_F32, false, false>, (const void*)gc3_interpreter_wave<GC3_F32, true, false>,
+      (const void*)gc3_interpreter_wave<GC3_F16, false, false>, (const void*)gc3_interpreter_wave<GC3_F16, true, false>,
+      (const void*)gc3_interpreter_wave<GC3_BF16, false, false>, (const void*)gc3_interpreter_wave<GC3_BF16, true, false>};
+  const void* wave_die[] = {
+      (const void*)gc3_interpreter_wave<GC3_F32, false, true>, (const void*)gc3_interpreter_wave<GC3_F32, true, true>,
+      (const void*)gc3_interpreter_wave<GC3_F16, false, true>, (const void*)gc3_interpreter_wave<GC3_F16, true, true>,
+      (const void*)gc3_interpreter_wave<GC3_BF16, false, true>, (const void*)gc3_interpreter_wave<GC3_BF16, true, true>};
   auto take = [&](const void* const* fns, int n) -> int {
     for (int i = 0; i < n; ++i) {
       int occ = 0;
@@ -798,8 +856,10 @@ int interpreter_occupancy(unsigned block, bool staged, int* out) {
     }
     return 0;
   };
-  int e = staged ? take(with_stage, 6) : take(plain, 12);
-  if (e == 0 && !staged && block == 64) e = take(wave, 6);
+  int e = kind == 1 ? take(with_stage, 6) : take(plain, 12);
+  if (e == 0 && kind != 1 && block == 64) e = take(wave, 6);
+  if (e == 0 && kind == 2) e = take(die, 6);
+  if (e == 0 && kind == 2 && block == 64) e = take(wave_die, 6);
   if (e != 0) return e;
   *out = best;
   return 0;

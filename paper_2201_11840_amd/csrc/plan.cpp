@@ -36,6 +36,12 @@ int resolve_config(const gc3_comm_config* cfg_in, gc3_comm_config& cfg, std::str
   if (cfg.lds_stage < 0 || cfg.lds_stage > 1) { msg = "lds_stage must be 0 or 1"; return GC3_ERR_ARG; }
   if (cfg.debug_hold < 0 || cfg.debug_hold > 1) { msg = "debug_hold must be 0 or 1"; return GC3_ERR_ARG; }
   if (cfg.protocol < 0 || cfg.protocol > 3) { msg = "protocol must be 0..3"; return GC3_ERR_ARG; }
+  if (cfg.fifo_scope < 0 || cfg.fifo_scope > 2) { msg = "fifo_scope must be 0, 1 or 2"; return GC3_ERR_ARG; }
+  if (cfg.reserved1 != 0) { msg = "reserved1 must be 0"; return GC3_ERR_ARG; }
+  if (cfg.fifo_scope == 2 && (cfg.lds_stage || cfg.protocol > 1)) {
+    msg = "die-scope FIFOs run the simple protocol through registers (protocol 0 or 1, lds_stage 0)";
+    return GC3_ERR_ARG;
+  }
   if (cfg.ll_max_lane_bytes == 0) cfg.ll_max_lane_bytes = 8192;
   if (cfg.ll_max_lane_bytes < 16 || cfg.ll_max_lane_bytes % 16 || cfg.ll_max_lane_bytes > 65536) {
     msg = "ll_max_lane_bytes must be a multiple of 16 in [16, 65536]";
@@ -67,6 +73,11 @@ int make_plan(const gc3_program& prog, const gc3_comm_config& cfg, int cus, long
     conn_id[key] = id;
     return id;
   };
+  std::vector<int> conn_sender;   // global thread-block index of the sending end of every connection
+  auto note_end = [&](std::vector<int>& ends, int conn, int tb) {
+    if ((int)ends.size() <= conn) ends.resize(conn + 1, -1);
+    ends[conn] = tb;
+  };
   std::vector<DTb>& tbs = plan.tbs;
   std::vector<DInstr>& instrs = plan.instrs;
   std::vector<DDep>& deps = plan.deps;
@@ -86,7 +97,7 @@ int make_plan(const gc3_program& prog, const gc3_comm_config& cfg, int cus, long
       d.ninstr = (uint32_t)tb.instrs.size();
       d.send_conn = d.recv_conn = -1;
       for (const Instr& in : tb.instrs) {
-        if (op_pushes(in.op)) d.send_conn = conn_of(r, tb.send, tb.chan);
+        if (op_pushes(in.op)) { d.send_conn = conn_of(r, tb.send, tb.chan); note_end(conn_sender, d.send_conn, g); }
         if (op_pops(in.op)) d.recv_conn = conn_of(tb.recv, r, tb.chan);
         DInstr di{};
         di.op = in.op;
@@ -240,6 +251,8 @@ int make_plan(const gc3_program& prog, const gc3_comm_config& cfg, int cus, long
         f.ninstr = tbs[g].ninstr;
         f.send_conn = tbs[g].send_conn;
         f.recv_conn = tbs[g].recv_conn;
+        f.recv_from_tb = (tbs[g].recv_conn >= 0 && (size_t)tbs[g].recv_conn < conn_sender.size())
+                             ? (uint32_t)conn_sender[tbs[g].recv_conn] : 0xffffffffu;
         fibers.push_back(f);
         h.ninstr += tbs[g].ninstr;
         h.rank = tbs[g].rank;
@@ -256,8 +269,10 @@ int make_plan(const gc3_program& prog, const gc3_comm_config& cfg, int cus, long
   int tile_bytes = cfg.tile_bytes;
   if (tile_bytes == 0) {
     tile_bytes = 65536;
-    const uint64_t soft = fifo_limit ? fifo_limit : (256ull << 20);
-    const int floor_bytes = fifo_limit ? 1024 : 16384;
+    // device scope: the FIFOs should stay in the 256 MiB memory-side cache; die scope: in the dies' L2s (8 x 4 MiB,
+    // shared with the user data that streams through)
+    const uint64_t soft = fifo_limit ? fifo_limit : cfg.fifo_scope == 2 ? (16ull << 20) : (256ull << 20);
+    const int floor_bytes = fifo_limit ? 1024 : cfg.fifo_scope == 2 ? 4096 : 16384;
     while (tile_bytes > floor_bytes && (uint64_t)nconn * W * cfg.fifo_slots * max_count * (uint64_t)tile_bytes > soft)
       tile_bytes /= 2;
   }
@@ -270,6 +285,7 @@ int make_plan(const gc3_program& prog, const gc3_comm_config& cfg, int cus, long
     return GC3_ERR_SIZE;
   }
   int protocol = cfg.protocol;
+  if (cfg.fifo_scope == 2) protocol = 1;
   if (protocol == 0) protocol = prog.protocol == "simple" ? 1 : (prog.protocol == "ll" || prog.protocol == "ll128") ? 2 : 3;
   const uint64_t ll_slot_bytes = 2ull * max_count * (uint64_t)cfg.ll_max_lane_bytes;
   const uint64_t ll_fifo_bytes = protocol == 1 ? 0 : std::max<uint64_t>(16, (uint64_t)nconn * W * cfg.fifo_slots * ll_slot_bytes);

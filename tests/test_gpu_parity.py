@@ -56,7 +56,7 @@ def compare_special(got, want, dtype, exact_only=False):
 
 
 def run_case(prog, dtype, elems, dist="normal", seed=1234, cfg=None, repeats=1, exact_only=False, compare=None,
-             expect_kernel=None):
+             expect_kernel=None, expect_die=None):
     """Run `prog` on the GPU and in the oracle on the same seeded inputs; compare every output element
     of every rank (and the inputs of out-of-place programs, which most programs leave untouched).  With an explicit
     configuration both protocols (payload + flag, and LL) are exercised unless it fixes one."""
@@ -72,7 +72,7 @@ def run_case(prog, dtype, elems, dist="normal", seed=1234, cfg=None, repeats=1, 
     with np.errstate(over="ignore", invalid="ignore"):
         oracle.run_program(p, want_in, want_out, dtype, slots=8)
     protocols = [None]
-    if cfg is not None and cfg.protocol == 0:
+    if cfg is not None and cfg.protocol == 0 and cfg.fifo_scope != 2:
         protocols = [1, 2]
     for proto in protocols:
         if proto is not None:
@@ -81,6 +81,8 @@ def run_case(prog, dtype, elems, dist="normal", seed=1234, cfg=None, repeats=1, 
         try:
             if expect_kernel is not None:                  # the kernel variant this case is meant to exercise
                 assert coll.launch.kernel == expect_kernel, (prog.name, coll.launch.kernel)
+            if expect_die is not None:
+                assert bool(coll.launch.die_scope) == expect_die, prog.name
             for _ in range(repeats):
                 coll.upload(ins, outs)
                 coll.run()
@@ -209,7 +211,8 @@ def test_random_launch_configurations(seed):
     dtype = ("f32", "f16", "bf16")[int(rng.integers(3))]
     cfg = H.make_config(fifo_slots=int(rng.integers(2, 9)), tile_bytes=int(rng.choice([256, 1024, 4096, 16384, 65536])),
                         team_width=int(rng.choice([1, 2, 3, 5, 8, 13, 32])), wg_size=int(rng.choice([64, 128, 256, 512])),
-                        target_wgs=int(rng.choice([0, 16, 100, 512])), min_lane_bytes=int(rng.choice([16, 256, 4096, 8192])))
+                        target_wgs=int(rng.choice([0, 16, 100, 512])), min_lane_bytes=int(rng.choice([16, 256, 4096, 8192])),
+                        fifo_scope=int(rng.choice([0, 2])))
     unit = 16 // inputs.ITEMSIZE[dtype]
     chunk_elems = int(rng.choice([1, 3, 17, 250, 1031, 4100])) * unit          # 16 B .. 64 KiB per chunk
     exact = prog.collective != "allreduce"
@@ -422,10 +425,11 @@ def test_tune_measures_plans_and_the_chosen_one_is_correct():
             assert fastest >= 0.98 * tried[0].ms
         else:
             assert tried[rep.best].ms == fastest < 0.98 * tried[0].ms
-        assert len({(t.team_width, t.grid, t.tile_bytes, t.wg_size) for t in tried}) == rep.count   # no plan timed twice
+        assert len({(t.team_width, t.grid, t.tile_bytes, t.wg_size, t.fifo_scope) for t in tried}) == rep.count   # no plan timed twice
         b = tried[rep.best]
         assert (coll.info.team_width, coll.info.grid, coll.info.tile_bytes, coll.info.wg_size) == \
             (b.team_width, b.grid, b.tile_bytes, b.wg_size)
+        assert coll.cfg.fifo_scope == (2 if b.fifo_scope == 2 else 0)
         coll.upload(ins, outs)
         coll.run()
         coll.status()
@@ -710,6 +714,51 @@ def test_wavefront_level_interpreter(dtype):
     # and 64-thread workgroups that do hold several fibers fall back to the general interpreter
     run_case(programs.hierarchical_allreduce(2, 3), dtype, 6 * 20000 * m, "normal", 1204, wave(team_width=2),
              expect_kernel=B.KERNEL_GENERAL)
+
+
+# ---- die-scope FIFOs: payload stays in the L2 of the die both ends of a connection run on -------------------------
+
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
+def test_die_scope_fifos(dtype):
+    """Plain stores into the slots, loads that bypass the compute unit's L1: correct only if sender and receiver of
+    every connection share a die, which the planner arranges and every receiver verifies (a violation would end the run
+    with GC3_ERR_PLACEMENT, i.e. fail status()).  Programs of every shape - one ring, many rings, pairs, relays,
+    cross-thread-block dependencies, thread blocks sharing a workgroup - with slots far smaller than a die's L2
+    (the lines are rewritten while still cached) and larger (they are evicted and fetched back)."""
+    H = _harness()
+    from paper_2201_11840_amd import binding as B
+    m = 4 // inputs.ITEMSIZE[dtype]
+    die = lambda **kw: H.make_config(fifo_scope=2, **kw)
+    cases = [(programs.ring_allreduce(8), 8 * 65536 * m, die(team_width=16)),
+             (programs.ring_allreduce(8, instances=8), 64 * 32768 * m, die()),
+             (programs.ring_allreduce(8, instances=8), 64 * 16384 * m, die(wg_size=64, team_width=32, target_wgs=4096, min_lane_bytes=1024)),
+             (programs.ring_allreduce(5, instances=3, use_rrs=True), 15 * 20000 * m, die(tile_bytes=4096, team_width=8, min_lane_bytes=2048)),
+             (programs.ring_allreduce(3, fuse=False), 3 * 50000 * m, die(fifo_slots=1, tile_bytes=2048, team_width=8, min_lane_bytes=1024)),
+             (programs.hierarchical_allreduce(2, 8), 16 * 131072 * m, die()),          # every lane active: no split
+             (programs.hierarchical_allreduce(3, 2, fuse=False), 6 * 20000 * m, die(team_width=24, tile_bytes=8192, min_lane_bytes=512)),
+             (programs.allpairs_allreduce(8), 8 * 65536 * m, die()),
+             (programs.allpairs_allreduce(8), 8 * 65536 * m, die(wg_size=64, team_width=64, target_wgs=4096, min_lane_bytes=2048)),
+             (programs.allpairs_allreduce(4, via_scratch=True), 4 * 30000 * m, die(team_width=8, tile_bytes=1024, min_lane_bytes=256)),
+             (programs.multichannel_ring_allreduce(8, 4), 8 * 65536 * m, die(team_width=16)),
+             (programs.ring_allreduce(8, instances=2), 16 * 262144 * m, die(tile_bytes=65536, fifo_slots=8, team_width=16))]
+    for prog, elems, cfg in cases:
+        run_case(prog, dtype, elems, "normal", 1600, cfg, repeats=3, expect_die=True)
+    for prog, elems, cfg in [(programs.alltonext(3, 8), 8 * 65536 * 2, die(team_width=8)), (programs.twostep_alltoall(3, 8), 24 * 32768 * 2, die(team_width=8)),
+                             (programs.direct_alltoall(8), 8 * 65536 * 2, die(team_width=16)),
+                             (programs.ring_allgather(8, instances=8), 8 * 65536 * m, die(team_width=8))]:
+        run_case(prog, dtype, elems, "normal", 1601, cfg, repeats=2, exact_only=True, expect_die=True)
+    run_case(programs.ring_allreduce(8, instances=2), dtype, 16 * 32768 * m, "special", 1602, die(team_width=8), compare=compare_special, expect_die=True)
+    # small chunks (fiber lists dealt to the idle lanes' workgroups) or a number of active lanes that is not a
+    # multiple of 8: such a run uses device-scope FIFOs on the same communicator
+    run_case(programs.hierarchical_allreduce(2, 3), dtype, 6 * 1024 * m, "normal", 1603, die(team_width=8), expect_die=False)
+    run_case(programs.ring_allreduce(4), dtype, 4 * 40000 * m, "normal", 1604, die(team_width=12, min_lane_bytes=1024), expect_die=False)
+
+
+def test_config3_and_config4_with_die_scope_fifos():
+    H = _harness()
+    for w in (workloads.ring_ar_r8x8(64), workloads.ring_ar_r8x8(1), workloads.hier_ar_2x8(64), workloads.alltonext_3x8(32)):
+        run_case(w.build(), w.dtype, w.elems_per_rank, w.dist, w.seed, H.make_config(fifo_scope=2), repeats=2,
+                 exact_only=w.build().collective == "alltonext")
 
 
 # ---- FIFO payload staged through LDS (direct-to-LDS loads) --------------------------------------------------------

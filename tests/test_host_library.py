@@ -216,7 +216,8 @@ def test_plan_respects_configuration_and_limits():
     small = plan(prog, cus=8, resident=16)                     # a tiny device: thread blocks must share
     assert small.active_wgs <= 16 and small.max_fibers_per_wg >= 4
     for bad in (dict(fifo_slots=9), dict(tile_bytes=24), dict(tile_bytes=2 << 20), dict(wg_size=100),
-                dict(team_width=257), dict(target_wgs=-1), dict(min_lane_bytes=24), dict(debug_hold=2), dict(lds_stage=2)):
+                dict(team_width=257), dict(target_wgs=-1), dict(min_lane_bytes=24), dict(debug_hold=2), dict(lds_stage=2),
+                dict(fifo_scope=3), dict(fifo_scope=2, lds_stage=1), dict(fifo_scope=2, protocol=2)):
         with pytest.raises(B.Gc3Error) as e:
             plan(prog, **bad)
         assert e.value.status == B.GC3_ERR_ARG
@@ -292,8 +293,8 @@ def test_kernel_resources_of_the_built_library():
     if not os.path.exists(path):
         pytest.skip("library was built without the resource report")
     kernels = [k for k in json.load(open(path)) if "gc3_interpreter" in k["name"]]
-    # 3 data types x dependencies or not x (simple, LL, simple with LDS staging, wavefront-level)
-    assert len(kernels) == 24
+    # 3 data types x dependencies or not x (simple, LL, LDS staging, die-scope FIFOs; wavefront-level at device and die scope)
+    assert len(kernels) == 36
     for k in kernels:
         assert k["scratch_bytes"] == 0, k
         assert k["occupancy"] >= 6, k
@@ -301,7 +302,7 @@ def test_kernel_resources_of_the_built_library():
         assert k["vgprs"] <= 80 and k["lds_bytes"] <= (32768 if staged else 16384), k
     assert sum(k["lds_bytes"] > 16384 for k in kernels) == 6
     wave = [k for k in kernels if "gc3_interpreter_wave" in k["name"]]
-    assert len(wave) == 6 and all(k["lds_bytes"] <= 2048 for k in wave)
+    assert len(wave) == 12 and all(k["lds_bytes"] <= 2048 for k in wave)
 
 
 def test_compiler_command_line_writes_loadable_programs(tmp_path):
