@@ -31,10 +31,18 @@ def _verified_first_run(w, coll, ins):
                                workloads.Workload("allpairs_r8_f32_8MiB", lambda: programs.allpairs_allreduce(8),
                                                   "f32", 8 << 20, "uniform", 7)],
                          ids=lambda w: w.name)
-def test_many_runs_give_the_same_verified_result(w):
+@pytest.mark.parametrize("scope", ["device", "die"])
+def test_many_runs_give_the_same_verified_result(w, scope):
+    # die scope: the plan the tuner picks for the ring (one-wavefront workgroups, 4 KiB tiles: the slots of a die fit
+    # its L2 and are rewritten while cached), and 256-thread workgroups with 16 lanes for the others
     prog = w.build()
     ins = inputs.make_inputs(prog.ranks, w.elems_per_rank, w.dtype, w.dist, w.seed)
-    coll = H.Collective(prog.to_text(), w.dtype, w.elems_per_rank)
+    cfg = None
+    if scope == "die":
+        cfg = H.make_config(fifo_scope=2, wg_size=64, team_width=32, target_wgs=4096) if "ring" in w.name else \
+            H.make_config(fifo_scope=2, team_width=16)
+    coll = H.Collective(prog.to_text(), w.dtype, w.elems_per_rank, cfg)
+    assert bool(coll.launch.die_scope) == (scope == "die")
     try:
         _verified_first_run(w, coll, ins)
         good = [t.clone() for t in coll.outputs]
