@@ -663,8 +663,10 @@ int gc3_comm_tune(const gc3_program* prog, const gc3_comm_config* base, size_t e
     struct Shape { int wg, target; };
     for (Shape sh : {Shape{64, 4096}, Shape{128, 2048}, Shape{256, 0}}) {
       if (cfg0.wg_size && cfg0.wg_size != sh.wg) continue;
-      for (int w : {8, 16, 32, 64}) {
-        if (sh.wg == 256 ? w > 16 : w < 16) continue;             // 256 threads: 8, 16 lanes; fewer threads: 16, 32, 64
+      for (int w : {8, 16, 32, 64, 128, 256}) {
+        // 256 threads: 8, 16 lanes; 128 threads: 16, 32, 64; one wavefront: 16 .. 256 (programs with few thread
+        // blocks need that many lanes to fill the device; plans that do not fit are skipped)
+        if (sh.wg == 256 ? w > 16 : (w < 16 || (sh.wg == 128 && w > 64))) continue;
         if (cfg0.team_width && cfg0.team_width != w) continue;
         gc3_comm_config cfg = cfg0;
         cfg.fifo_scope = 2;
