@@ -51,6 +51,9 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
+KERNEL_NAMES = ("general", "ll", "lds_staged", "wavefront", "wavefront_ll")   # gc3_launch_info.kernel
+
+
 def measured_traffic():
     """workload -> bytes per launch (fetch + write), from the tracked profile data; empty when the file is missing."""
     out = {}
@@ -172,7 +175,7 @@ def report(w, coll, mean_ms, min_ms, wall_ms, prog, launches_before_timed=0):
            "fifo_MiB": round(coll.info.fifo_bytes / 2 ** 20, 1),
            "launch": {"grid": li.grid, "wg_size": li.wg_size, "active_lanes": li.active_lanes, "split": li.split,
                       "tile_bytes": li.tile_bytes, "fifo_scope": "die" if li.die_scope else "device",
-                      "kernel": ("general", "ll", "lds_staged", "wavefront")[li.kernel]}}
+                      "kernel": KERNEL_NAMES[li.kernel]}}
     rep = coll.tune_report
     if rep is not None:
         rec["tuned"] = {"team_width": coll.cfg.team_width, "target_wgs": coll.cfg.target_wgs,
@@ -212,7 +215,7 @@ def size_sweep(steps, warmup, tune, cfg):
             row[name] = {"us": round(m * 1e3, 2), "us_back_to_back": round(wall * 1e3, 2),
                          "algbw_GBps": round(kib * 1024 / (m * 1e-3) / 1e9, 2),
                          "team_width": c.info.team_width, "grid": li.grid, "wg_size": li.wg_size,
-                         "kernel": ("general", "ll", "lds_staged", "wavefront")[li.kernel]}
+                         "kernel": KERNEL_NAMES[li.kernel]}
             c.close()
             del pr, c
             torch.cuda.empty_cache()

@@ -71,7 +71,7 @@ class CommInfo(C.Structure):
                 ("wgs_per_lane", C.c_int32), ("protocol", C.c_int32), ("ll_fifo_bytes", C.c_uint64)]
 
 
-GC3_TUNE_MAX_TRIED = 48
+GC3_TUNE_MAX_TRIED = 56
 
 
 class LaunchInfo(C.Structure):
@@ -80,7 +80,7 @@ class LaunchInfo(C.Structure):
                 ("lane_bytes", C.c_uint64)]
 
 
-KERNEL_GENERAL, KERNEL_LL, KERNEL_STAGED, KERNEL_WAVE = 0, 1, 2, 3
+KERNEL_GENERAL, KERNEL_LL, KERNEL_STAGED, KERNEL_WAVE, KERNEL_WAVE_LL = 0, 1, 2, 3, 4
 
 
 class InFlight(C.Structure):
@@ -90,6 +90,7 @@ class InFlight(C.Structure):
 class TuneEntry(C.Structure):
     _fields_ = [("team_width", C.c_int32), ("target_wgs", C.c_int32), ("grid", C.c_int32),
                 ("active_wgs", C.c_int32), ("tile_bytes", C.c_int32), ("wg_size", C.c_int32), ("fifo_scope", C.c_int32),
+                ("protocol", C.c_int32), ("min_lane_bytes", C.c_int32),
                 ("reserved", C.c_int32), ("ms", C.c_double)]
 
 

@@ -150,7 +150,7 @@ struct Launch {
   KParams p{};
   unsigned grid = 0, block = 0;
   bool ll = false;
-  int mode = 0;              // kernel variant: 0 general, 1 LL, 2 payload staged through LDS, 3 wavefront-level
+  int mode = 0;              // kernel variant: 0 general, 1 LL, 2 payload staged through LDS, 3 wavefront-level, 4 wavefront-level LL
   bool die = false;          // FIFO payload at die scope in this run
   uint64_t lane_share = 0;   // largest share a lane has of a chunk, bytes
 };
@@ -177,10 +177,10 @@ void shape_run(const gc3_comm_info& info, uint64_t cb, uint64_t min_lane_bytes, 
                Launch& L) {
   if (min_lane_bytes != 0) { shape_run_with(info, cb, min_lane_bytes, ll_max_lane_bytes, lds_stage, L); return; }
   shape_run_with(info, cb, 8192, ll_max_lane_bytes, lds_stage, L);
-  if (L.mode != 3) return;
+  if (L.mode != 3 && L.mode != 4) return;
   Launch finer = L;
   shape_run_with(info, cb, 4096, ll_max_lane_bytes, lds_stage, finer);
-  if (finer.mode == 3) L = finer;
+  if (finer.mode == L.mode) L = finer;
 }
 
 void shape_run_with(const gc3_comm_info& info, uint64_t cb, uint64_t min_lane_bytes, uint64_t ll_max_lane_bytes,
@@ -229,12 +229,12 @@ void shape_run_with(const gc3_comm_info& info, uint64_t cb, uint64_t min_lane_by
   // (2-3 % faster than four up to 8 KiB per lane, slower above).
   L.block = (unsigned)info.wg_size;
   const bool single_fiber = (uint32_t)info.max_fibers_per_wg <= p.nsplit;
-  if (lane_share <= 8192 && !L.ll && !lds_stage && single_fiber) L.block = 64;
+  if (lane_share <= 8192 && (L.ll || !lds_stage) && single_fiber) L.block = 64;
   else if (L.block > 128 && lane_share <= 8192) L.block = 128;
   // Instantiation: LL, or payload staged through LDS, or - for workgroups of one wavefront that each run one
-  // fiber - the wavefront-level interpreter, or the general one.
+  // fiber - the wavefront-level interpreter (simple or LL protocol), or the general one.
   L.mode = 0;
-  if (L.ll) L.mode = 1;
+  if (L.ll) L.mode = (L.block == 64 && single_fiber) ? 4 : 1;
   else if (lds_stage) L.mode = 2;
   else if (L.block == 64 && single_fiber) L.mode = 3;
 }
@@ -585,7 +585,7 @@ int gc3_comm_tune(const gc3_program* prog, const gc3_comm_config* base, size_t e
     if (report && report->count < GC3_TUNE_MAX_TRIED) {
       auto& e = report->tried[report->count];
       e.team_width = c->info.team_width; e.target_wgs = cfg.target_wgs; e.grid = c->info.grid;
-      e.active_wgs = c->info.active_wgs; e.tile_bytes = c->info.tile_bytes; e.wg_size = c->info.wg_size; e.fifo_scope = cfg.fifo_scope == 2 ? 2 : 1; e.ms = per;
+      e.active_wgs = c->info.active_wgs; e.tile_bytes = c->info.tile_bytes; e.wg_size = c->info.wg_size; e.fifo_scope = cfg.fifo_scope == 2 ? 2 : 1; e.protocol = c->info.protocol; e.min_lane_bytes = cfg.min_lane_bytes; e.ms = per;
       if (better) report->best = report->count;
       ++report->count;
     }
@@ -687,6 +687,30 @@ int gc3_comm_tune(const gc3_program* prog, const gc3_comm_config* base, size_t e
         cfg.tile_bytes = tile;
         if ((rc = try_config(cfg)) != GC3_OK) return rc;
       }
+    }
+  }
+  // pass 6: the LL protocol (Section 6.1) with workgroups of one wavefront, for runs that are latency-bound.  A hop
+  // is then one flagged store and the polling load that finds it.  On MI355X this pays where consecutive steps of
+  // a chain are spread over several thread blocks (one ring over four channels, 4 KiB to 256 KiB: 34 -> 25-28 us)
+  // and loses where one thread block executes them back to back (its next poll queues behind the completion of
+  // its own stores), so it is decided by measurement.
+  if (have && cfg0.protocol == 0 && cfg0.lds_stage == 0 && cfg0.fifo_scope != 2 && best_ms < 0.1 &&
+      (cfg0.wg_size == 0 || cfg0.wg_size == 64)) {
+    seen.clear();
+    seen.emplace_back(-1, -1, -1);
+    for (int mlb : {0, 1024}) {
+      if (cfg0.min_lane_bytes && mlb) continue;
+      for (int w : {16, 64}) {
+        if (cfg0.team_width && cfg0.team_width != w) continue;
+        gc3_comm_config cfg = cfg0;
+        cfg.protocol = 2;
+        cfg.wg_size = 64;
+        cfg.team_width = w;
+        if (mlb) cfg.min_lane_bytes = mlb;
+        if ((rc = try_config(cfg)) != GC3_OK) return rc;
+      }
+      seen.clear();
+      seen.emplace_back(-1, -1, -1);
     }
   }
   if (!have) {

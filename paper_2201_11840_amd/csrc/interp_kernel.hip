@@ -677,9 +677,15 @@ __global__ void __launch_bounds__(512) gc3_interpreter(KParams p) {
 // waits for its own stores, lane 0 stores the flags - and there is no workgroup barrier and no state in LDS
 // anywhere on the path of a hop.  This is the instantiation for latency-bound sizes, where a lane's share of a
 // chunk is a few 128-bit accesses per thread.
+//
+// WM selects the protocol / payload path as for the general kernel: kSimple, kDie, or kLL - there a message needs
+// no tail flag, no completion wait and no separate load of the payload, so a hop is one store and the polling
+// load that finds it (the receiver's loads have completed when it has seen the flags, so the head flag needs no
+// wait either).
 constexpr int kWaveLdsInstrs = 64;
-template <int DT, bool COH, bool DIE>
+template <int DT, bool COH, int WM>
 __global__ void __launch_bounds__(64) gc3_interpreter_wave(KParams p) {
+  constexpr bool DIE = WM == kDie, LL = WM == kLL;
   __shared__ uint32_t s_instr[kWaveLdsInstrs * 8];
   const uint32_t tid = threadIdx.x;
   const uint32_t slot = p.bin_major ? blockIdx.x % p.W_active : blockIdx.x / p.wgs_per_lane;
@@ -718,8 +724,10 @@ __global__ void __launch_bounds__(64) gc3_interpreter_wave(KParams p) {
   uint64_t* const head_send = send_conn >= 0 ? flag_of(p, send_conn, lane, 1) : nullptr;
   uint64_t* const tail_recv = recv_conn >= 0 ? flag_of(p, recv_conn, lane, 0) : nullptr;
   uint64_t* const head_recv = recv_conn >= 0 ? flag_of(p, recv_conn, lane, 1) : nullptr;
-  unsigned char* const fifo_send = send_conn >= 0 ? p.fifo + (uint64_t)((uint32_t)send_conn * W + lane) * p.slots * p.slot_bytes : nullptr;
-  unsigned char* const fifo_recv = recv_conn >= 0 ? p.fifo + (uint64_t)((uint32_t)recv_conn * W + lane) * p.slots * p.slot_bytes : nullptr;
+  unsigned char* const fifo_base = LL ? p.ll_fifo : p.fifo;
+  const uint32_t slot_bytes = LL ? p.ll_slot_bytes : p.slot_bytes;
+  unsigned char* const fifo_send = send_conn >= 0 ? fifo_base + (uint64_t)((uint32_t)send_conn * W + lane) * p.slots * slot_bytes : nullptr;
+  unsigned char* const fifo_recv = recv_conn >= 0 ? fifo_base + (uint64_t)((uint32_t)recv_conn * W + lane) * p.slots * slot_bytes : nullptr;
   uint32_t send_seq = 0, recv_seq = 0, head_known = 0;
 
   for (uint32_t t = 0; t < ntiles; ++t) {               // tile loop outside, instruction loop inside
@@ -739,9 +747,9 @@ __global__ void __launch_bounds__(64) gc3_interpreter_wave(KParams p) {
       const uint32_t ndeps = ins.ndeps_hasdep >> 1;
       const bool hasdep = ins.ndeps_hasdep & 1;
       const bool wait_slot = pushes && send_seq >= head_known + p.slots;
-      if (pops || wait_slot || ndeps) {
+      if ((pops && !LL) || wait_slot || ndeps) {
         uint64_t seen;
-        const int res = poll_flags(p, tid, true, pops ? tail_recv : nullptr, run_base + recv_seq + 1,
+        const int res = poll_flags(p, tid, true, (pops && !LL) ? tail_recv : nullptr, run_base + recv_seq + 1,
                                    wait_slot ? head_send : nullptr, run_base + send_seq + 1 - p.slots,
                                    ins.dep_begin, ndeps, lane, run_base, t, seen);
         if (res < 0) return;                           // (the same value in every lane: decided by wavefront votes)
@@ -759,17 +767,40 @@ __global__ void __launch_bounds__(64) gc3_interpreter_wave(KParams p) {
       const uint64_t coff = off0 + toff;
       unsigned char* const srcb = ins.srcbuf < 3 ? bufs[ins.srcbuf] + (uint64_t)ins.srcidx * p.chunk_bytes + coff : nullptr;
       unsigned char* const dstb = ins.dstbuf < 3 ? bufs[ins.dstbuf] + (uint64_t)ins.dstidx * p.chunk_bytes + coff : nullptr;
-      unsigned char* const rslot = pops ? fifo_recv + (uint64_t)(recv_seq % p.slots) * p.slot_bytes : nullptr;
-      unsigned char* const sslot = pushes ? fifo_send + (uint64_t)(send_seq % p.slots) * p.slot_bytes : nullptr;
-      move_simple<DT, COH, false, DIE>(op, ins.count, srcb, dstb, rslot, sslot, len, p.chunk_bytes, tid, 64, nullptr);
+      unsigned char* const rslot = pops ? fifo_recv + (uint64_t)(recv_seq % p.slots) * slot_bytes : nullptr;
+      unsigned char* const sslot = pushes ? fifo_send + (uint64_t)(send_seq % p.slots) * slot_bytes : nullptr;
+      if (LL && (pops || pushes)) {
+        constexpr int UL = COH ? kUserLdCoh : kUserLd, US = COH ? kUserStCoh : kUserSt;
+        const uint32_t ll_fin = p.ll_base + recv_seq + 1, ll_fout = p.ll_base + send_seq + 1, nvec = len >> 4;
+        bool data_ok = true;
+        for (uint32_t j = 0; j < ins.count; ++j) {
+          const rsrc_t src = make_rsrc(srcb + (uint64_t)j * p.chunk_bytes, srcb ? len : 0);
+          const rsrc_t dst = make_rsrc(dstb + (uint64_t)j * p.chunk_bytes, dstb ? len : 0);
+          const rsrc_t rl = make_rsrc(rslot + (uint64_t)j * len * 2, rslot ? len * 2 : 0);
+          const rsrc_t sl = make_rsrc(sslot + (uint64_t)j * len * 2, sslot ? len * 2 : 0);
+          switch (op) {
+            case GC3_OP_SEND: move_tile_ll<false, false, false, true, DT, UL, US>(rl, src, dst, sl, nvec, tid, 64, ll_fin, ll_fout, p); break;
+            case GC3_OP_RECV: data_ok &= move_tile_ll<true, false, true, false, DT, UL, US>(rl, src, dst, sl, nvec, tid, 64, ll_fin, ll_fout, p); break;
+            case GC3_OP_RRC:  data_ok &= move_tile_ll<true, true, true, false, DT, UL, US>(rl, src, dst, sl, nvec, tid, 64, ll_fin, ll_fout, p); break;
+            case GC3_OP_RCS:  data_ok &= move_tile_ll<true, false, true, true, DT, UL, US>(rl, src, dst, sl, nvec, tid, 64, ll_fin, ll_fout, p); break;
+            case GC3_OP_RRCS: data_ok &= move_tile_ll<true, true, true, true, DT, UL, US>(rl, src, dst, sl, nvec, tid, 64, ll_fin, ll_fout, p); break;
+            case GC3_OP_RRS:  data_ok &= move_tile_ll<true, true, false, true, DT, UL, US>(rl, src, dst, sl, nvec, tid, 64, ll_fin, ll_fout, p); break;
+            default: break;
+          }
+        }
+        if (__any(!data_ok)) return;                     // a lane gave up waiting for data: the run is abandoned
+      } else {
+        move_simple<DT, COH, false, DIE>(op, ins.count, srcb, dstb, rslot, sslot, len, p.chunk_bytes, tid, 64, nullptr);
+      }
       if (pushes) ++send_seq;
       if (pops) ++recv_seq;
-      if (pushes || pops || hasdep) {
+      if (LL ? (pops || hasdep) : (pushes || pops || hasdep)) {
         // the wavefront's own device-scope stores have completed when its counter reaches zero; all of the
-        // fiber's stores are this wavefront's, so nothing else has to be waited for before the flags
-        __builtin_amdgcn_s_waitcnt(0);
+        // fiber's stores are this wavefront's, so nothing else has to be waited for before the flags.  (LL: only a
+        // semaphore, which covers plain user-buffer stores, needs that.)
+        if (!LL || hasdep) __builtin_amdgcn_s_waitcnt(0);
         if (tid == 0) {
-          if (pushes) store_flag(tail_send, run_base + send_seq);
+          if (pushes && !LL) store_flag(tail_send, run_base + send_seq);
           if (pops) store_flag(head_recv, run_base + recv_seq);
           if (hasdep) store_flag(my_sem, run_base + (uint64_t)t * tb_ninstr + s + 1);
         }
@@ -781,25 +812,31 @@ __global__ void __launch_bounds__(64) gc3_interpreter_wave(KParams p) {
 
 // Host-callable launcher; returns the hipError_t of the launch.  `coherent_user` selects the
 // instantiation for programs with cross-thread-block dependencies; `mode`: 0 simple, 1 LL, 2 simple with the
-// FIFO payload staged through LDS, 3 the one-wavefront one-fiber interpreter (block must be 64); `die_scope`
-// (modes 0 and 3): FIFO payload kept in the L2 of the die both ends of a connection run on.
+// FIFO payload staged through LDS, 3 the one-wavefront one-fiber interpreter (block must be 64), 4 the same under
+// the LL protocol; `die_scope` (modes 0 and 3): FIFO payload kept in the L2 of the die both ends of a connection
+// run on.
 template <int DT>
 static int launch_dt(bool coh, int mode, bool die, unsigned grid, unsigned block, hipStream_t st, const KParams& p) {
 #define GC3_LAUNCH(K) hipLaunchKernelGGL((K), dim3(grid), dim3(block), 0, st, p)
   if (die && mode != 0 && mode != 3) return (int)hipErrorInvalidValue;
-  switch ((die ? 4 : mode) * 2 + (coh ? 1 : 0) + (die && mode == 3 ? 2 : 0)) {
+  int variant = mode;                       // 0..3 as above, 4 die-scope general, 5 die-scope wavefront, 6 LL wavefront
+  if (die) variant = mode == 3 ? 5 : 4;
+  else if (mode == 4) variant = 6;
+  switch (variant * 2 + (coh ? 1 : 0)) {
     case 0: GC3_LAUNCH((gc3_interpreter<DT, false, kSimple>)); break;
     case 1: GC3_LAUNCH((gc3_interpreter<DT, true, kSimple>)); break;
     case 2: GC3_LAUNCH((gc3_interpreter<DT, false, kLL>)); break;
     case 3: GC3_LAUNCH((gc3_interpreter<DT, true, kLL>)); break;
     case 4: GC3_LAUNCH((gc3_interpreter<DT, false, kStaged>)); break;
     case 5: GC3_LAUNCH((gc3_interpreter<DT, true, kStaged>)); break;
-    case 6: GC3_LAUNCH((gc3_interpreter_wave<DT, false, false>)); break;
-    case 7: GC3_LAUNCH((gc3_interpreter_wave<DT, true, false>)); break;
+    case 6: GC3_LAUNCH((gc3_interpreter_wave<DT, false, kSimple>)); break;
+    case 7: GC3_LAUNCH((gc3_interpreter_wave<DT, true, kSimple>)); break;
     case 8: GC3_LAUNCH((gc3_interpreter<DT, false, kDie>)); break;
     case 9: GC3_LAUNCH((gc3_interpreter<DT, true, kDie>)); break;
-    case 10: GC3_LAUNCH((gc3_interpreter_wave<DT, false, true>)); break;
-    case 11: GC3_LAUNCH((gc3_interpreter_wave<DT, true, true>)); break;
+    case 10: GC3_LAUNCH((gc3_interpreter_wave<DT, false, kDie>)); break;
+    case 11: GC3_LAUNCH((gc3_interpreter_wave<DT, true, kDie>)); break;
+    case 12: GC3_LAUNCH((gc3_interpreter_wave<DT, false, kLL>)); break;
+    case 13: GC3_LAUNCH((gc3_interpreter_wave<DT, true, kLL>)); break;
     default: return (int)hipErrorInvalidValue;
   }
 #undef GC3_LAUNCH
@@ -809,7 +846,7 @@ static int launch_dt(bool coh, int mode, bool die, unsigned grid, unsigned block
 int launch_interpreter(int dtype, bool coherent_user, int mode, bool die_scope, unsigned grid, unsigned block, void* stream,
                        const KParams& p) {
   hipStream_t st = (hipStream_t)stream;
-  if (mode == 3 && block != 64) return (int)hipErrorInvalidValue;
+  if ((mode == 3 || mode == 4) && block != 64) return (int)hipErrorInvalidValue;
   switch (dtype) {
     case GC3_F32: return launch_dt<GC3_F32>(coherent_user, mode, die_scope, grid, block, st, p);
     case GC3_F16: return launch_dt<GC3_F16>(coherent_user, mode, die_scope, grid, block, st, p);
@@ -840,13 +877,17 @@ int interpreter_occupancy(unsigned block, int kind, int* out) {
       (const void*)gc3_interpreter<GC3_F16, false, kStaged>, (const void*)gc3_interpreter<GC3_F16, true, kStaged>,
       (const void*)gc3_interpreter<GC3_BF16, false, kStaged>, (const void*)gc3_interpreter<GC3_BF16, true, kStaged>};
   const void* wave[] = {
-      (const void*)gc3_interpreter_wave<GC3_F32, false, false>, (const void*)gc3_interpreter_wave<GC3_F32, true, false>,
-      (const void*)gc3_interpreter_wave<GC3_F16, false, false>, (const void*)gc3_interpreter_wave<GC3_F16, true, false>,
-      (const void*)gc3_interpreter_wave<GC3_BF16, false, false>, (const void*)gc3_interpreter_wave<GC3_BF16, true, false>};
+      (const void*)gc3_interpreter_wave<GC3_F32, false, kSimple>, (const void*)gc3_interpreter_wave<GC3_F32, true, kSimple>,
+      (const void*)gc3_interpreter_wave<GC3_F16, false, kSimple>, (const void*)gc3_interpreter_wave<GC3_F16, true, kSimple>,
+      (const void*)gc3_interpreter_wave<GC3_BF16, false, kSimple>, (const void*)gc3_interpreter_wave<GC3_BF16, true, kSimple>};
+  const void* wave_ll[] = {
+      (const void*)gc3_interpreter_wave<GC3_F32, false, kLL>, (const void*)gc3_interpreter_wave<GC3_F32, true, kLL>,
+      (const void*)gc3_interpreter_wave<GC3_F16, false, kLL>, (const void*)gc3_interpreter_wave<GC3_F16, true, kLL>,
+      (const void*)gc3_interpreter_wave<GC3_BF16, false, kLL>, (const void*)gc3_interpreter_wave<GC3_BF16, true, kLL>};
   const void* wave_die[] = {
-      (const void*)gc3_interpreter_wave<GC3_F32, false, true>, (const void*)gc3_interpreter_wave<GC3_F32, true, true>,
-      (const void*)gc3_interpreter_wave<GC3_F16, false, true>, (const void*)gc3_interpreter_wave<GC3_F16, true, true>,
-      (const void*)gc3_interpreter_wave<GC3_BF16, false, true>, (const void*)gc3_interpreter_wave<GC3_BF16, true, true>};
+      (const void*)gc3_interpreter_wave<GC3_F32, false, kDie>, (const void*)gc3_interpreter_wave<GC3_F32, true, kDie>,
+      (const void*)gc3_interpreter_wave<GC3_F16, false, kDie>, (const void*)gc3_interpreter_wave<GC3_F16, true, kDie>,
+      (const void*)gc3_interpreter_wave<GC3_BF16, false, kDie>, (const void*)gc3_interpreter_wave<GC3_BF16, true, kDie>};
   auto take = [&](const void* const* fns, int n) -> int {
     for (int i = 0; i < n; ++i) {
       int occ = 0;
@@ -858,6 +899,7 @@ int interpreter_occupancy(unsigned block, int kind, int* out) {
   };
   int e = kind == 1 ? take(with_stage, 6) : take(plain, 12);
   if (e == 0 && kind != 1 && block == 64) e = take(wave, 6);
+  if (e == 0 && kind != 1 && block == 64) e = take(wave_ll, 6);
   if (e == 0 && kind == 2) e = take(die, 6);
   if (e == 0 && kind == 2 && block == 64) e = take(wave_die, 6);
   if (e != 0) return e;

@@ -425,11 +425,13 @@ def test_tune_measures_plans_and_the_chosen_one_is_correct():
             assert fastest >= 0.98 * tried[0].ms
         else:
             assert tried[rep.best].ms == fastest < 0.98 * tried[0].ms
-        assert len({(t.team_width, t.grid, t.tile_bytes, t.wg_size, t.fifo_scope) for t in tried}) == rep.count   # no plan timed twice
+        assert len({(t.team_width, t.grid, t.tile_bytes, t.wg_size, t.fifo_scope, t.protocol, t.min_lane_bytes)
+                    for t in tried}) == rep.count   # no plan timed twice
         b = tried[rep.best]
         assert (coll.info.team_width, coll.info.grid, coll.info.tile_bytes, coll.info.wg_size) == \
             (b.team_width, b.grid, b.tile_bytes, b.wg_size)
         assert coll.cfg.fifo_scope == (2 if b.fifo_scope == 2 else 0)
+        assert coll.info.protocol == b.protocol
         coll.upload(ins, outs)
         coll.run()
         coll.status()
@@ -682,17 +684,21 @@ def test_special_values_multi_hop(dtype):
 
 # ---- the wavefront-level interpreter (64-thread workgroups that run one thread-block lane each) ------------------
 
+@pytest.mark.parametrize("protocol", ["simple", "ll"])
 @pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
-def test_wavefront_level_interpreter(dtype):
+def test_wavefront_level_interpreter(dtype, protocol):
     """Every workgroup is one wavefront with one fiber: counters in registers, no barrier, no LDS state.  Programs
     with and without cross-thread-block dependencies, aggregated instructions, scratch buffers, many peers;
     tiny tiles with ragged tails and the default tile; 2 and 8 slots.  Thread blocks that share a workgroup in
     the plan are dealt to workgroups of their own when the chunk is small (split), which is how the hierarchical
-    and All Pairs programs get here."""
+    and All Pairs programs get here.  Under both protocols: payload + flag, and LL (every 8 bytes carry their own
+    flag, Section 6.1), where the LL tile replaces the configured one."""
     H = _harness()
     from paper_2201_11840_amd import binding as B
     m = 4 // inputs.ITEMSIZE[dtype]
-    wave = lambda **kw: H.make_config(wg_size=64, protocol=1, **kw)
+    ll = protocol == "ll"
+    wave = lambda **kw: H.make_config(wg_size=64, protocol=2 if ll else 1, ll_max_lane_bytes=512 if ll else 0, **kw)
+    kernel = B.KERNEL_WAVE_LL if ll else B.KERNEL_WAVE
     cases = [(programs.ring_allreduce(8), 8 * 2500 * m, wave(tile_bytes=1024, team_width=3, min_lane_bytes=16)),
              (programs.ring_allreduce(4, use_rrs=True), 4 * 2500 * m, wave(tile_bytes=256, team_width=2, min_lane_bytes=16, fifo_slots=8)),
              (programs.ring_allreduce(8, instances=2), 16 * 16384 * m, wave(team_width=32, min_lane_bytes=1024, target_wgs=2048)),
@@ -703,17 +709,20 @@ def test_wavefront_level_interpreter(dtype):
              (programs.allpairs_allreduce(4, via_scratch=True), 4 * 1000 * m, wave(tile_bytes=1024, team_width=8, min_lane_bytes=4096)),
              (programs.multichannel_ring_allreduce(5, 3), 5 * 1000 * m, wave(tile_bytes=512, team_width=8, min_lane_bytes=4096))]
     for prog, elems, cfg in cases:
-        run_case(prog, dtype, elems, "normal", 1200, cfg, repeats=2, expect_kernel=B.KERNEL_WAVE)
+        run_case(prog, dtype, elems, "normal", 1200, cfg, repeats=2, expect_kernel=kernel)
     run_case(programs.direct_alltoall(8), dtype, 8 * 2048 * m, "normal", 1201, wave(team_width=16, min_lane_bytes=8192),
-             exact_only=True, expect_kernel=B.KERNEL_WAVE)
+             exact_only=True, expect_kernel=kernel)
     run_case(programs.alltonext(2, 3), dtype, 3 * 2048 * m, "normal", 1202, wave(team_width=16, min_lane_bytes=8192),
-             exact_only=True, expect_kernel=B.KERNEL_WAVE)
+             exact_only=True, expect_kernel=kernel)
     # instruction lists longer than the wavefront-level kernel keeps in LDS (124 per thread block)
     run_case(programs.ring_allreduce(32, fuse=False), dtype, 32 * 256 * m, "uniform", 1203, wave(team_width=1),
-             expect_kernel=B.KERNEL_WAVE)
+             expect_kernel=kernel)
+    # special values travel through the flagged words unchanged
+    run_case(programs.ring_allreduce(4), dtype, 4 * 4096 * m, "special", 1205, wave(team_width=4, min_lane_bytes=1024),
+             compare=compare_special, expect_kernel=kernel)
     # and 64-thread workgroups that do hold several fibers fall back to the general interpreter
     run_case(programs.hierarchical_allreduce(2, 3), dtype, 6 * 20000 * m, "normal", 1204, wave(team_width=2),
-             expect_kernel=B.KERNEL_GENERAL)
+             expect_kernel=B.KERNEL_LL if ll else B.KERNEL_GENERAL)
 
 
 # ---- die-scope FIFOs: payload stays in the L2 of the die both ends of a connection run on -------------------------
