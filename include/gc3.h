@@ -207,7 +207,7 @@ int gc3_comm_create(const gc3_program* prog, const gc3_comm_config* cfg, gc3_com
 int gc3_comm_info_get(const gc3_comm* comm, gc3_comm_info* out);
 
 /* What gc3_comm_tune tried. */
-#define GC3_TUNE_MAX_TRIED 56
+#define GC3_TUNE_MAX_TRIED 64
 typedef struct gc3_tune_entry {
   int32_t team_width;      /* W of the plan */
   int32_t target_wgs;      /* as passed to the planner (0 = default) */
@@ -218,7 +218,7 @@ typedef struct gc3_tune_entry {
   int32_t fifo_scope;      /* 1 device, 2 die */
   int32_t protocol;        /* 1 simple, 2 LL, 3 chosen per run */
   int32_t min_lane_bytes;  /* as passed to the planner (0 = chosen per run) */
-  int32_t reserved;
+  int32_t fifo_slots;      /* s of the plan */
   double ms;               /* mean duration of one run */
 } gc3_tune_entry;
 typedef struct gc3_tune_report {
@@ -235,7 +235,7 @@ typedef struct gc3_tune_report {
  * 16..64 x workgroup targets {2048, 4096} and again the slot tiles, then die-scope FIFOs with 64, 128 and 256
  * threads x team widths 8..64 and their slot tiles, then - when the fastest run so far takes under 0.1 ms and `base`
  * leaves the protocol to the program - the LL protocol (Section 6.1) with workgroups of one wavefront, team widths
- * 16 and 64 and lane shares of at least 4 KiB or 1 KiB - only over fields `base` leaves 0 - it creates
+ * 16 and 64, lane shares of at least 4 KiB or 1 KiB and the default number of slots or 8 - only over fields `base` leaves 0 - it creates
  * a communicator on the current device, binds stand-in buffers of the real sizes (non-zero filler) that it
  * allocates and frees itself, times 5 runs after 2 warm-up runs (8 for the first plan) on `hip_stream`, and writes the
  * chosen configuration to `*best` (ready for gc3_comm_create): the fastest one if it beats `base`,

@@ -71,7 +71,7 @@ class CommInfo(C.Structure):
                 ("wgs_per_lane", C.c_int32), ("protocol", C.c_int32), ("ll_fifo_bytes", C.c_uint64)]
 
 
-GC3_TUNE_MAX_TRIED = 56
+GC3_TUNE_MAX_TRIED = 64
 
 
 class LaunchInfo(C.Structure):
@@ -91,7 +91,7 @@ class TuneEntry(C.Structure):
     _fields_ = [("team_width", C.c_int32), ("target_wgs", C.c_int32), ("grid", C.c_int32),
                 ("active_wgs", C.c_int32), ("tile_bytes", C.c_int32), ("wg_size", C.c_int32), ("fifo_scope", C.c_int32),
                 ("protocol", C.c_int32), ("min_lane_bytes", C.c_int32),
-                ("reserved", C.c_int32), ("ms", C.c_double)]
+                ("fifo_slots", C.c_int32), ("ms", C.c_double)]
 
 
 class TuneReport(C.Structure):

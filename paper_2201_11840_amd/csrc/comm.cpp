@@ -585,7 +585,7 @@ int gc3_comm_tune(const gc3_program* prog, const gc3_comm_config* base, size_t e
     if (report && report->count < GC3_TUNE_MAX_TRIED) {
       auto& e = report->tried[report->count];
       e.team_width = c->info.team_width; e.target_wgs = cfg.target_wgs; e.grid = c->info.grid;
-      e.active_wgs = c->info.active_wgs; e.tile_bytes = c->info.tile_bytes; e.wg_size = c->info.wg_size; e.fifo_scope = cfg.fifo_scope == 2 ? 2 : 1; e.protocol = c->info.protocol; e.min_lane_bytes = cfg.min_lane_bytes; e.ms = per;
+      e.active_wgs = c->info.active_wgs; e.tile_bytes = c->info.tile_bytes; e.wg_size = c->info.wg_size; e.fifo_scope = cfg.fifo_scope == 2 ? 2 : 1; e.protocol = c->info.protocol; e.min_lane_bytes = cfg.min_lane_bytes; e.fifo_slots = c->info.fifo_slots; e.ms = per;
       if (better) report->best = report->count;
       ++report->count;
     }
@@ -691,26 +691,30 @@ int gc3_comm_tune(const gc3_program* prog, const gc3_comm_config* base, size_t e
   }
   // pass 6: the LL protocol (Section 6.1) with workgroups of one wavefront, for runs that are latency-bound.  A hop
   // is then one flagged store and the polling load that finds it.  On MI355X this pays where consecutive steps of
-  // a chain are spread over several thread blocks (one ring over four channels, 4 KiB to 256 KiB: 34 -> 25-28 us)
-  // and loses where one thread block executes them back to back (its next poll queues behind the completion of
-  // its own stores), so it is decided by measurement.
+  // a chain are spread over several thread blocks, which then wait ahead of time (one ring over four channels, 4 KiB
+  // to 256 KiB: 34 -> 25-28 us), and gains little or loses where one thread block executes them back to back, so it
+  // is decided by measurement.
   if (have && cfg0.protocol == 0 && cfg0.lds_stage == 0 && cfg0.fifo_scope != 2 && best_ms < 0.1 &&
       (cfg0.wg_size == 0 || cfg0.wg_size == 64)) {
     seen.clear();
     seen.emplace_back(-1, -1, -1);
-    for (int mlb : {0, 1024}) {
-      if (cfg0.min_lane_bytes && mlb) continue;
-      for (int w : {16, 64}) {
-        if (cfg0.team_width && cfg0.team_width != w) continue;
-        gc3_comm_config cfg = cfg0;
-        cfg.protocol = 2;
-        cfg.wg_size = 64;
-        cfg.team_width = w;
-        if (mlb) cfg.min_lane_bytes = mlb;
-        if ((rc = try_config(cfg)) != GC3_OK) return rc;
+    for (int slots : {0, 8}) {                // eight slots: a push hardly ever has to look at the head flag
+      if (cfg0.fifo_slots && slots) continue;
+      for (int mlb : {0, 1024}) {
+        if (cfg0.min_lane_bytes && mlb) continue;
+        for (int w : {16, 64}) {
+          if (cfg0.team_width && cfg0.team_width != w) continue;
+          gc3_comm_config cfg = cfg0;
+          cfg.protocol = 2;
+          cfg.wg_size = 64;
+          cfg.team_width = w;
+          if (mlb) cfg.min_lane_bytes = mlb;
+          if (slots) cfg.fifo_slots = slots;
+          if ((rc = try_config(cfg)) != GC3_OK) return rc;
+        }
+        seen.clear();
+        seen.emplace_back(-1, -1, -1);
       }
-      seen.clear();
-      seen.emplace_back(-1, -1, -1);
     }
   }
   if (!have) {

@@ -196,7 +196,7 @@ __device__ __forceinline__ bool move_tile_ll(rsrc_t in_ll, rsrc_t src, rsrc_t ds
       for (int u = 0; u < UN; ++u) b[u] = __builtin_amdgcn_raw_buffer_load_b128(src, (base + u * nthreads) << 4, 0, P_SRC);
     }
     if (POP) {
-      const uint64_t start = wall_clock64();
+      uint64_t start = 0;                              // wall clock at the first periodic check (reading it costs ~0.1 us)
       uint32_t spins = 0;
       for (;;) {
         bool all = true;
@@ -210,8 +210,10 @@ __device__ __forceinline__ bool move_tile_ll(rsrc_t in_ll, rsrc_t src, rsrc_t ds
         }
         if (all) break;
         if ((++spins & 1023u) == 0) {
+          const uint64_t now = wall_clock64();
+          if (start == 0) start = now;
           if (__hip_atomic_load(p.error, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0 ||
-              wall_clock64() - start > p.spin_limit_ticks) {
+              now - start > p.spin_limit_ticks) {
             atomicCAS(p.error, 0u, (uint32_t)(-GC3_ERR_TIMEOUT));
             ok = false;
             break;
@@ -342,7 +344,7 @@ __device__ __forceinline__ int poll_flags(const KParams& p, uint32_t lane_id, bo
       want = run_base + (uint64_t)t * d.ninstr + d.step + 1;
     }
     bool pending = ptr != nullptr;
-    const uint64_t start = wall_clock64();
+    uint64_t start = 0;                                // wall clock at the first periodic check (reading it costs ~0.1 us)
     uint32_t spins = 0;
     for (;;) {
       if (pending) {
@@ -354,7 +356,9 @@ __device__ __forceinline__ int poll_flags(const KParams& p, uint32_t lane_id, bo
       if (++spins > 16) __builtin_amdgcn_s_sleep(1);     // poll hard first, politely later
       if ((spins & 255u) == 0) {
         if (__hip_atomic_load(p.error, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) { res = -1; break; }
-        if (wall_clock64() - start > p.spin_limit_ticks) {
+        const uint64_t now = wall_clock64();
+        if (start == 0) start = now;
+        if (now - start > p.spin_limit_ticks) {
           atomicCAS(p.error, 0u, (uint32_t)(-GC3_ERR_TIMEOUT));
           res = -1;
           break;

@@ -18,7 +18,7 @@ Dep = Tuple[ThreadBlock, int]
 
 
 # ---------------------------------------------------------------------------
-# Ring helpers (Section 2: "ReduceScatter and AllGather using the Ring algorithm")
+# Ring helpers: ReduceScatter and AllGather along a ring (Section 2)
 # ---------------------------------------------------------------------------
 
 def _emit_ring_reduce_scatter(tb: ThreadBlock, pos: int, G: int, index: Callable[[int], int],
@@ -146,9 +146,9 @@ def ring_allgather(R: int, instances: int = 1, name: Optional[str] = None) -> Pr
 
 
 def multichannel_ring_allreduce(R: int, channels: int, name: Optional[str] = None) -> Program:
-    """One logical ring spread over several channels (Section 7.1.1: "distributes a
-    single logical ring across multiple channels by varying the channel of copy
-    and reduce operations").  Ring chunk q travels on channel q mod channels, so
+    """One logical ring spread over several channels (Section 7.1.1, the schedule used for
+    small and medium buffers: the channel differs from operation to operation of the one
+    ring).  Ring chunk q travels on channel q mod channels, so
     a rank has one thread block per channel and the chunks of different
     channels overlap their sends and receives.  No cross-thread-block
     dependencies are needed: every location a thread block touches belongs to

@@ -425,7 +425,7 @@ def test_tune_measures_plans_and_the_chosen_one_is_correct():
             assert fastest >= 0.98 * tried[0].ms
         else:
             assert tried[rep.best].ms == fastest < 0.98 * tried[0].ms
-        assert len({(t.team_width, t.grid, t.tile_bytes, t.wg_size, t.fifo_scope, t.protocol, t.min_lane_bytes)
+        assert len({(t.team_width, t.grid, t.tile_bytes, t.wg_size, t.fifo_scope, t.protocol, t.min_lane_bytes, t.fifo_slots)
                     for t in tried}) == rep.count   # no plan timed twice
         b = tried[rep.best]
         assert (coll.info.team_width, coll.info.grid, coll.info.tile_bytes, coll.info.wg_size) == \
@@ -692,7 +692,9 @@ def test_wavefront_level_interpreter(dtype, protocol):
     tiny tiles with ragged tails and the default tile; 2 and 8 slots.  Thread blocks that share a workgroup in
     the plan are dealt to workgroups of their own when the chunk is small (split), which is how the hierarchical
     and All Pairs programs get here.  Under both protocols: payload + flag, and LL (every 8 bytes carry their own
-    flag, Section 6.1), where the LL tile replaces the configured one."""
+    flag, Section 6.1), where the LL tile replaces the configured one.  The unfused ring (`rrc` then `send` of the
+    same chunk) and the All Pairs variant with a chain of local `reduce` instructions are the cases where an
+    instruction reads what the previous one of its thread block wrote."""
     H = _harness()
     from paper_2201_11840_amd import binding as B
     m = 4 // inputs.ITEMSIZE[dtype]
@@ -707,7 +709,11 @@ def test_wavefront_level_interpreter(dtype, protocol):
              (programs.hierarchical_allreduce(2, 8), 16 * 3072 * m, wave(team_width=16, min_lane_bytes=8192)),
              (programs.allpairs_allreduce(8), 8 * 3072 * m, wave(team_width=16, min_lane_bytes=8192)),
              (programs.allpairs_allreduce(4, via_scratch=True), 4 * 1000 * m, wave(tile_bytes=1024, team_width=8, min_lane_bytes=4096)),
-             (programs.multichannel_ring_allreduce(5, 3), 5 * 1000 * m, wave(tile_bytes=512, team_width=8, min_lane_bytes=4096))]
+             (programs.multichannel_ring_allreduce(5, 3), 5 * 1000 * m, wave(tile_bytes=512, team_width=8, min_lane_bytes=4096)),
+             (programs.ring_allreduce(5, fuse=False), 5 * 3000 * m, wave(team_width=4, min_lane_bytes=1024)),
+             (programs.allpairs_allreduce(8, via_scratch=True), 8 * 2048 * m, wave(team_width=16, min_lane_bytes=2048)),
+             (programs.twostep_alltoall(2, 3), 6 * 1024 * m, wave(team_width=8, min_lane_bytes=1024)),
+             (programs.local_stream(4, tbs_per_rank=2, reduce=True), 4 * 4 * 1024 * m, wave(team_width=8, min_lane_bytes=512))]
     for prog, elems, cfg in cases:
         run_case(prog, dtype, elems, "normal", 1200, cfg, repeats=2, expect_kernel=kernel)
     run_case(programs.direct_alltoall(8), dtype, 8 * 2048 * m, "normal", 1201, wave(team_width=16, min_lane_bytes=8192),
