@@ -95,8 +95,10 @@ typedef struct gc3_comm_config {
   int32_t team_width;      /* W: lanes per IR thread block; lane w owns the w-th 1/W of every chunk and
                               has FIFO slots, flags and a semaphore of its own (the runtime applying
                               Section 5.1's parallelize(W)).  Lightly loaded thread blocks of one
-                              rank may share a workgroup.  0 = choose W and the sharing so that the
-                              heaviest workgroup is lightest */
+                              rank may share a workgroup (not with 64-thread workgroups when thread
+                              blocks x W stays within target_wgs: every lane then has a workgroup of its
+                              own).  0 = choose W and the sharing so that the heaviest workgroup is
+                              lightest */
   int32_t wg_size;         /* threads per workgroup: 64, 128, 256 or 512; default 256 (a run whose lanes get
                               at most 8 KiB of a chunk launches 128 of them).  With 64, runs in which every
                               workgroup executes a single thread-block lane use the wavefront-level
@@ -232,7 +234,8 @@ typedef struct gc3_tune_report {
  * parallelization the runtime applies).  For the configuration in `base` (may be null) and for team
  * widths 4..64 x workgroup targets {default, 512, 768}, then for the fastest of them the slot tiles 16, 32
  * and 64 KiB, then workgroups of 128 threads, then workgroups of one wavefront (64 threads) with team widths
- * 16..64 x workgroup targets {2048, 4096} and again the slot tiles, then die-scope FIFOs with 64, 128 and 256
+ * 16..64 (and the widest with which no two thread blocks share a workgroup) x workgroup targets {2048, 4096} and
+ * again the slot tiles, then die-scope FIFOs with 64, 128 and 256
  * threads x team widths 8..64 and their slot tiles, then - when the fastest run so far takes under 0.1 ms and `base`
  * leaves the protocol to the program - the LL protocol (Section 6.1) with workgroups of one wavefront, team widths
  * 16 and 64, lane shares of at least 4 KiB or 1 KiB and the default number of slots or 8 - only over fields `base` leaves 0 - it creates

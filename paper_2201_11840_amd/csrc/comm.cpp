@@ -634,8 +634,17 @@ int gc3_comm_tune(const gc3_program* prog, const gc3_comm_config* base, size_t e
   if (have && cfg0.wg_size == 0) {
     seen.clear();
     seen.emplace_back(-1, -1, -1);
-    for (int w : {16, 32, 64})
+    // besides 16, 32 and 64 lanes: the widest team with which every thread block still gets workgroups of its own
+    // (the planner shares nothing then), for programs with many thread blocks (AllToNext on 3 x 8 ranks: 396 thread
+    // blocks x 10 lanes, 6.36 -> 6.68 TB/s on MI355X)
+    int widths64[4] = {16, 32, 64, 0};
+    if (pi.num_tbs > 0) {
+      const int w1 = 4096 / pi.num_tbs;
+      if (w1 >= 2 && w1 < 64 && w1 != 16 && w1 != 32) widths64[3] = w1;
+    }
+    for (int w : widths64)
       for (int t : {2048, 4096}) {
+        if (w == 0 || (w == widths64[3] && t != 4096)) continue;
         if ((cfg0.team_width && cfg0.team_width != w) || (cfg0.target_wgs && cfg0.target_wgs != t)) continue;
         gc3_comm_config cfg = cfg0;
         cfg.wg_size = 64;

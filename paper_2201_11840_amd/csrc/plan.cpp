@@ -144,6 +144,9 @@ int make_plan(const gc3_program& prog, const gc3_comm_config& cfg, int cus, long
   auto pack = [&](int W, bool round_up, std::vector<std::vector<int>>* bins_out, double* heaviest) -> long {
     // returns the number of workgroups, or -1 when a workgroup would exceed the fiber limit
     const double ideal = (double)total_weight * W / (double)target;   // traffic of one workgroup if perfectly spread
+    // Workgroups of one wavefront run best with one fiber each (the wavefront-level interpreter: no barrier, no
+    // state in LDS): when every thread block can have workgroups of its own within the target, nothing is shared.
+    const bool singletons = cfg.wg_size == 64 && (long)ntb * W <= target;
     long wgs = 0;
     double worst = 0;
     for (int r = 0; r < R; ++r) {
@@ -158,6 +161,7 @@ int make_plan(const gc3_program& prog, const gc3_comm_config& cfg, int cus, long
       int k = round_up ? (int)std::ceil(rank_weight / cap - 1e-9) : (int)std::floor(rank_weight / cap + 1e-9);
       k = std::max(1, std::min(k, n));
       k = std::max(k, (n + kMaxFibersPerWg - 1) / kMaxFibersPerWg);
+      if (singletons) k = n;
       std::vector<std::vector<int>> bins(k);
       std::vector<double> load(k, 0.0);
       for (int g : order) {

@@ -726,8 +726,9 @@ def test_wavefront_level_interpreter(dtype, protocol):
     # special values travel through the flagged words unchanged
     run_case(programs.ring_allreduce(4), dtype, 4 * 4096 * m, "special", 1205, wave(team_width=4, min_lane_bytes=1024),
              compare=compare_special, expect_kernel=kernel)
-    # and 64-thread workgroups that do hold several fibers fall back to the general interpreter
-    run_case(programs.hierarchical_allreduce(2, 3), dtype, 6 * 20000 * m, "normal", 1204, wave(team_width=2),
+    # and 64-thread workgroups that do hold several fibers (24 thread blocks x 2 lanes, 16 workgroups wanted) fall back
+    # to the general interpreter
+    run_case(programs.hierarchical_allreduce(2, 3), dtype, 6 * 20000 * m, "normal", 1204, wave(team_width=2, target_wgs=16),
              expect_kernel=B.KERNEL_LL if ll else B.KERNEL_GENERAL)
 
 
