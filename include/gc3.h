@@ -243,7 +243,8 @@ typedef struct gc3_tune_report {
  * allocates and frees itself, times 5 runs after 2 warm-up runs (8 for the first plan) on `hip_stream`, and writes the
  * chosen configuration to `*best` (ready for gc3_comm_create): the fastest one if it beats `base`,
  * which is timed first (report entry 0), by more than 2 %, else `base`.  `report` may be null.
- * Synchronises the device.  Plans that do not fit the device are skipped.
+ * Synchronises the device.  Plans that do not fit the device are skipped.  The chosen configuration may name the LL
+ * protocol, whose runs cannot be captured in a graph: set base->protocol = 1 to keep the simple protocol.
  * Errors: GC3_ERR_SIZE (size not a multiple of the chunk count / 16 bytes, or zero), validation errors,
  * GC3_ERR_TIMEOUT or GC3_ERR_HIP from a tuning run, GC3_ERR_ARG. */
 int gc3_comm_tune(const gc3_program* prog, const gc3_comm_config* base, size_t elems_per_rank, gc3_dtype dtype,
