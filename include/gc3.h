@@ -209,7 +209,7 @@ int gc3_comm_create(const gc3_program* prog, const gc3_comm_config* cfg, gc3_com
 int gc3_comm_info_get(const gc3_comm* comm, gc3_comm_info* out);
 
 /* What gc3_comm_tune tried. */
-#define GC3_TUNE_MAX_TRIED 64
+#define GC3_TUNE_MAX_TRIED 96
 typedef struct gc3_tune_entry {
   int32_t team_width;      /* W of the plan */
   int32_t target_wgs;      /* as passed to the planner (0 = default) */

@@ -71,7 +71,7 @@ class CommInfo(C.Structure):
                 ("wgs_per_lane", C.c_int32), ("protocol", C.c_int32), ("ll_fifo_bytes", C.c_uint64)]
 
 
-GC3_TUNE_MAX_TRIED = 64
+GC3_TUNE_MAX_TRIED = 96
 
 
 class LaunchInfo(C.Structure):
