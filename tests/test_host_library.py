@@ -204,6 +204,17 @@ def test_plan_fills_the_device_without_exceeding_it():
     assert i.fifo_bytes <= 256 << 20 and i.tile_bytes < 65536   # tile shrunk to keep the FIFOs cache sized
     i = plan(programs.alltonext(3, 8))
     assert i.active_wgs <= 1024 and i.max_fibers_per_wg >= 2      # 396 thread blocks cannot each own 4 lanes
+    # workgroups of one wavefront share nothing while thread blocks x lanes fits the target (each lane of each
+    # thread block then runs on the wavefront-level interpreter), and share again beyond it
+    n = programs.alltonext(3, 8).num_tbs()
+    i = plan(programs.alltonext(3, 8), resident=7168, wg_size=64, team_width=10, target_wgs=4096)
+    assert (i.team_width, i.active_wgs, i.max_fibers_per_wg) == (10, 10 * n, 1)
+    i = plan(programs.alltonext(3, 8), resident=7168, wg_size=64, team_width=16, target_wgs=4096)
+    assert i.active_wgs <= 4096 and i.max_fibers_per_wg >= 2
+    i = plan(programs.hierarchical_allreduce(2, 8), resident=7168, wg_size=64, team_width=64, target_wgs=4096)
+    assert (i.active_wgs, i.max_fibers_per_wg) == (4096, 1)
+    i = plan(programs.hierarchical_allreduce(2, 8), resident=7168, wg_size=256, team_width=64, target_wgs=4096)
+    assert i.max_fibers_per_wg >= 2                                # larger workgroups keep sharing
 
 
 def test_plan_respects_configuration_and_limits():
