@@ -233,14 +233,17 @@ typedef struct gc3_tune_report {
  * parallelization of every algorithm is tuned for the system and the buffer size; this does it for the
  * parallelization the runtime applies).  For the configuration in `base` (may be null) and for team
  * widths 4..64 x workgroup targets {default, 512, 768}, then for the fastest of them the slot tiles 16, 32
- * and 64 KiB, then workgroups of 128 threads, then workgroups of one wavefront (64 threads) with team widths
+ * and 64 KiB, then workgroups of 128 threads (the winner's plan; team widths 64 and 128 with as many workgroups as
+ * the device holds and a 16 KiB tile), then workgroups of one wavefront (64 threads) with team widths
  * 16..64 (and the widest with which no two thread blocks share a workgroup) x workgroup targets {2048, 4096} and
  * again the slot tiles, then die-scope FIFOs with 64, 128 and 256
  * threads x team widths 8..64 and their slot tiles, then - when the fastest run so far takes under 0.1 ms and `base`
  * leaves the protocol to the program - the LL protocol (Section 6.1) with workgroups of one wavefront, team widths
  * 16 and 64, lane shares of at least 4 KiB or 1 KiB and the default number of slots or 8 - only over fields `base` leaves 0 - it creates
  * a communicator on the current device, binds stand-in buffers of the real sizes (non-zero filler) that it
- * allocates and frees itself, times 5 runs after 2 warm-up runs (8 for the first plan) on `hip_stream`, and writes the
+ * allocates and frees itself, times 5 runs after 2 warm-up runs (8 for the first plan) on `hip_stream` - back to back
+ * when all inputs together are under 32 MiB, else each run on its own after a fill of the input buffers, so that a run
+ * finds freshly written inputs as it does in use -, and writes the
  * chosen configuration to `*best` (ready for gc3_comm_create): the fastest one if it beats `base`,
  * which is timed first (report entry 0), by more than 2 %, else `base`.  `report` may be null.
  * Synchronises the device.  Plans that do not fit the device are skipped.  The chosen configuration may name the LL
