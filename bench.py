@@ -187,6 +187,38 @@ def report(w, coll, mean_ms, min_ms, wall_ms, prog, launches_before_timed=0):
     return rec
 
 
+def graph_replay_us(text, elems, w, cfg, tune, runs_per_graph=20, replays=5):
+    """Time per run when 20 runs are recorded once into a HIP graph and the graph is replayed: what is left of a
+    latency-bound collective without the host's enqueue path."""
+    import torch
+    from paper_2201_11840_amd import harness
+    c = harness.Collective(text, "f32", elems, cfg, tune=tune)
+    try:
+        device_inputs(c, w, w.seed)
+        for _ in range(3):
+            c.run()
+        c.status()
+        graph = torch.cuda.CUDAGraph()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.graph(graph, stream=side):
+            for _ in range(runs_per_graph):
+                c.run()
+        graph.replay()
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(replays):
+            graph.replay()
+        b.record()
+        torch.cuda.synchronize()
+        c.status()
+        return round(a.elapsed_time(b) * 1e3 / (replays * runs_per_graph), 2)
+    finally:
+        c.close()
+        torch.cuda.empty_cache()
+
+
 def size_sweep(steps, warmup, tune, cfg):
     """AllReduce on 8 ranks, fp32, per-rank sizes 4 KiB .. 256 MiB, five schedules of Section 7.1: the time per
     collective and the per-rank algorithm bandwidth S / time, to show which schedule wins at which size."""
@@ -219,6 +251,8 @@ def size_sweep(steps, warmup, tune, cfg):
             c.close()
             del pr, c
             torch.cuda.empty_cache()
+            if kib <= 1024:
+                row[name]["us_graph_replay"] = graph_replay_us(prog.to_text(), elems, w, cfg, tune)
         log("[bench] size sweep " + json.dumps(row))
         rows.append(row)
     return rows

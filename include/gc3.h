@@ -246,8 +246,7 @@ typedef struct gc3_tune_report {
  * finds freshly written inputs as it does in use -, and writes the
  * chosen configuration to `*best` (ready for gc3_comm_create): the fastest one if it beats `base`,
  * which is timed first (report entry 0), by more than 2 %, else `base`.  `report` may be null.
- * Synchronises the device.  Plans that do not fit the device are skipped.  The chosen configuration may name the LL
- * protocol, whose runs cannot be captured in a graph: set base->protocol = 1 to keep the simple protocol.
+ * Synchronises the device.  Plans that do not fit the device are skipped.
  * Errors: GC3_ERR_SIZE (size not a multiple of the chunk count / 16 bytes, or zero), validation errors,
  * GC3_ERR_TIMEOUT or GC3_ERR_HIP from a tuning run, GC3_ERR_ARG. */
 int gc3_comm_tune(const gc3_program* prog, const gc3_comm_config* base, size_t elems_per_rank, gc3_dtype dtype,
@@ -299,10 +298,10 @@ int gc3_comm_launch_info(const gc3_comm* comm, size_t elems_per_rank, gc3_dtype 
  * GC3_ERR_POISONED, GC3_ERR_HIP, GC3_ERR_ARG.  A GC3_ERR_TIMEOUT inside the kernel is reported by
  * gc3_comm_status.
  * Stream capture: the kernel's arguments depend only on the communicator, the size and the data type (the run
- * counters live in device memory), the call copies nothing and waits for nothing, so under the simple protocol
- * it may be recorded into a HIP graph and replayed any number of times, also interleaved with eager runs of the
- * same communicator (never overlapping them).  A run under the LL protocol is refused while capturing
- * (GC3_ERR_ARG).  A communicator serves 2^32 - 1 runs between resets. */
+ * counters and the LL message numbers live in device memory), the call copies nothing and waits for nothing, so
+ * under either protocol it may be recorded into a HIP graph and replayed any number of times, also interleaved
+ * with eager runs of the same communicator (never overlapping them).  A communicator serves 2^32 - 1 runs between
+ * resets. */
 int gc3_comm_run(gc3_comm* comm, size_t elems_per_rank, gc3_dtype dtype, gc3_redop op, void* hip_stream);
 
 /* Bytes the method itself loads and stores through global memory in one run of this size: the sum over all

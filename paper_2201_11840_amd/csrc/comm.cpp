@@ -54,7 +54,6 @@ struct gc3_comm {
   uint64_t ll_max_lane_bytes = 8192;
   uint32_t ll_slot_bytes = 0;
   int max_pushes = 0;
-  uint64_t ll_next = 0;     // LL message numbers handed out so far (64-bit; flags are its low 32 bits)
   uint64_t algorithmic_chunks = 0;
   std::vector<int32_t> scratch_chunks;
   gc3_comm_info info{};
@@ -427,18 +426,12 @@ int gc3_comm_run(gc3_comm* comm, size_t elems_per_rank, gc3_dtype dtype, gc3_red
   p.ll_fifo = comm->d_ll_fifo;
   p.ll_slot_bytes = comm->ll_slot_bytes;
   if (L.ll) {
-    if (capturing) {
-      set_error("a run under the LL protocol cannot be captured: its message numbers are kernel arguments that change "
-                "from run to run");
-      return GC3_ERR_ARG;
-    }
-    // message numbers of this run: [ll_next + 1, ll_next + messages]; their low 32 bits are the flags and
-    // must never be 0 (the value untouched slot memory holds), so a range never crosses a multiple of 2^32
+    // an upper bound of the messages one connection carries in this run: the same for every run of one size, so
+    // the kernel's arguments stay constant (the fibers keep the running message number in device memory)
     const uint64_t tiles = (L.lane_share + p.tile_bytes - 1) / p.tile_bytes;
     const uint64_t messages = (uint64_t)comm->max_pushes * tiles + 1;
-    if (((comm->ll_next + messages) >> 32) != (comm->ll_next >> 32)) comm->ll_next = ((comm->ll_next >> 32) + 1) << 32;
-    p.ll_base = (uint32_t)comm->ll_next;
-    comm->ll_next += messages;
+    if (messages >= (1ull << 31)) { set_error("too many tiles for the LL protocol"); return GC3_ERR_SIZE; }
+    p.ll_msgs = (uint32_t)messages;
   }
   // Outside capture the run enters the device's ledger: its stream first waits for runs of other communicators
   // on other streams beside which this grid could not be resident.  A captured launch is replayed at times
@@ -483,6 +476,8 @@ int gc3_comm_reset(gc3_comm* comm) {
   HIP_TRY(hipDeviceSynchronize());
   HIP_TRY(hipMemset(comm->d_flags, 0, comm->flags_bytes));
   HIP_TRY(hipMemset(comm->d_sems, 0, comm->sems_bytes));
+  // (the semaphore lines also hold the LL message numbers, which restart: no LL slot may keep a flag of the past)
+  if (comm->d_ll_fifo) HIP_TRY(hipMemset(comm->d_ll_fifo, 0, comm->info.ll_fifo_bytes));
   HIP_TRY(hipMemset(comm->d_error, 0, 256));
   HIP_TRY(hipDeviceSynchronize());
   comm->poisoned = false;

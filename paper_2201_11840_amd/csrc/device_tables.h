@@ -66,14 +66,17 @@ struct KParams {
   uint64_t* flags;         // [((conn*W + lane)*2 + {0 tail, 1 head}) * kFlagStrideWords]
   uint64_t* sems;          // [(tb*W + lane) * kFlagStrideWords]: word 0 the semaphore, word 1 the fiber's epoch
                            // (runs it has completed); flag values of a run lie above (epoch + 1) << 32;
-                           // word 2 (die-scope FIFOs) the die the fiber runs on in this run, as run base + die + 1
+                           // word 2 (die-scope FIFOs) the die the fiber runs on in this run, as run base + die + 1;
+                           // word 3 (LL protocol) LL message numbers the fiber's past runs have used up
   uint32_t* error;         // 0 = fine, else a gc3_status (negated) set by the first failing workgroup
   const uint32_t* hold;    // null, or a start word every workgroup waits for (failure-path tests)
   uint64_t chunk_bytes;
   uint64_t spin_limit_ticks;  // of the 100 MHz wall clock
   uint32_t W, slots, tile_bytes, slot_bytes;
   uint32_t ll_slot_bytes;  // 2 * max_count * LL tile bytes
-  uint32_t ll_base;        // LL flag of message k of this run = ll_base + k + 1 (never 0 within a run)
+  uint32_t ll_msgs;        // LL protocol: an upper bound of the messages one connection carries in this run.  Every
+                           // fiber keeps the number of LL messages of its past runs next to its epoch (word 3 of its
+                           // semaphore line); message k of this run carries flag = low 32 bits of that number + k + 1
   uint32_t W_active;       // lanes that own bytes in this run (<= W); the others own nothing and finish at once
   uint32_t wgs_per_lane;   // workgroups per lane of the static plan (the grid is lane-major)
   uint32_t nsplit;         // in this run the fiber list of every (lane, bin) is dealt round-robin to this many

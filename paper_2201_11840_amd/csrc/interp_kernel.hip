@@ -301,6 +301,14 @@ __device__ __forceinline__ uint64_t* sem_of(const KParams& p, uint32_t tb, uint3
   return p.sems + (uint64_t)(tb * p.W + lane) * kFlagStrideWords;
 }
 
+// LL message numbers of a run.  A fiber's past runs have used up `used` of them (kept in its semaphore line, the
+// same value at both ends of a connection because the fibers of one lane take part in the same runs); this run may
+// use `msgs`.  The low 32 bits are the flags that travel with the payload and 0 is what untouched slot memory holds,
+// so a run's range never crosses a multiple of 2^32.  Returns the number the run starts from.
+__device__ __forceinline__ uint64_t ll_run_start(uint64_t used, uint32_t msgs) {
+  return ((used + msgs) >> 32) != (used >> 32) ? ((used >> 32) + 1) << 32 : used;
+}
+
 // Failure-path test facility: wait (bounded by the spin limit) for a start word that the host never sets.
 // Called by one thread; returns false when the run is abandoned.
 __device__ __forceinline__ bool hold_wait(const KParams& p) {
@@ -437,6 +445,7 @@ __global__ void __launch_bounds__(512) gc3_interpreter(KParams p) {
   // polls the head flag only when this does not already show a free slot
   __shared__ uint32_t f_head[kMaxFibersPerWg];
   __shared__ uint32_t f_epoch[kMaxFibersPerWg];    // runs the fiber has completed before this one
+  __shared__ uint64_t f_ll[LL ? kMaxFibersPerWg : 1];   // LL message number the fiber's run starts from
   __shared__ uint32_t f_from[kMaxFibersPerWg];     // thread block at the sending end of the fiber's receive connection
   __shared__ uint32_t s_headv[2];
   __shared__ uint64_t f_off0[kMaxFibersPerWg], f_share[kMaxFibersPerWg];
@@ -480,6 +489,7 @@ __global__ void __launch_bounds__(512) gc3_interpreter(KParams p) {
     f_head[tid] = 0;
     const uint32_t epoch = (uint32_t)load_flag(p.sems + (uint64_t)f.fid * kFlagStrideWords + 1);
     f_epoch[tid] = epoch;
+    if (LL) f_ll[tid] = ll_run_start(load_flag(p.sems + (uint64_t)f.fid * kFlagStrideWords + 3), p.ll_msgs);
     f_from[tid] = f.recv_from_tb;
     if (DIE) store_flag(p.sems + (uint64_t)f.fid * kFlagStrideWords + 2, ((uint64_t)(epoch + 1) << 32) + this_die() + 1);
     f_off0[tid] = o;
@@ -517,6 +527,8 @@ __global__ void __launch_bounds__(512) gc3_interpreter(KParams p) {
       const uint32_t ntiles = (uint32_t)((share + tile - 1) / tile);
       uint32_t s = uni(f_s[fi]), send_seq = uni(f_send[fi]), recv_seq = uni(f_recv[fi]);
       uint32_t head_known = uni(f_head[fi]);
+      const uint64_t ll_start = LL ? uni64(f_ll[fi]) : 0;
+      const uint32_t ll_base = (uint32_t)ll_start;
 
       uint64_t* const tail_send = send_conn >= 0 ? flag_of(p, send_conn, lane, 0) : nullptr;
       uint64_t* const head_send = send_conn >= 0 ? flag_of(p, send_conn, lane, 1) : nullptr;
@@ -549,7 +561,7 @@ __global__ void __launch_bounds__(512) gc3_interpreter(KParams p) {
 
         // ---- wait for dependencies, for a message, for a free slot -----------------------------
         // LL: the message's number doubles as the flag carried by every 8 bytes of its payload
-        const uint32_t ll_fin = p.ll_base + recv_seq + 1, ll_fout = p.ll_base + send_seq + 1;
+        const uint32_t ll_fin = ll_base + recv_seq + 1, ll_fout = ll_base + send_seq + 1;
         const bool block = live == 1;
         // (in LL mode a blocking receive needs no announcement: every thread polls its own data)
         if ((pops && !(LL && block)) || wait_slot || ndeps) {
@@ -648,7 +660,10 @@ __global__ void __launch_bounds__(512) gc3_interpreter(KParams p) {
           f_send[fi] = send_seq;
           f_recv[fi] = recv_seq;
           f_head[fi] = head_known;
-          if (finished) store_flag(my_sem + 1, (uint64_t)epoch + 1);   // this fiber has completed one more run
+          if (finished) {
+            store_flag(my_sem + 1, (uint64_t)epoch + 1);   // this fiber has completed one more run
+            if (LL) store_flag(my_sem + 3, ll_start + p.ll_msgs);
+          }
         }
       }
       if (finished) --live;
@@ -711,6 +726,8 @@ __global__ void __launch_bounds__(64) gc3_interpreter_wave(KParams p) {
   const uint32_t epoch = uni((uint32_t)load_flag(my_sem + 1));
   const uint64_t run_base = (uint64_t)(epoch + 1) << 32;
   const uint32_t recv_from_tb = uni(f.recv_from_tb);
+  const uint64_t ll_start = LL ? uni64(ll_run_start(load_flag(my_sem + 3), p.ll_msgs)) : 0;
+  const uint32_t ll_base = (uint32_t)ll_start;
   if (DIE && tid == 0) store_flag(my_sem + 2, run_base + this_die() + 1);
   unsigned char* bufs[3];
 #pragma unroll
@@ -775,7 +792,7 @@ __global__ void __launch_bounds__(64) gc3_interpreter_wave(KParams p) {
       unsigned char* const sslot = pushes ? fifo_send + (uint64_t)(send_seq % p.slots) * slot_bytes : nullptr;
       if (LL && (pops || pushes)) {
         constexpr int UL = COH ? kUserLdCoh : kUserLd, US = COH ? kUserStCoh : kUserSt;
-        const uint32_t ll_fin = p.ll_base + recv_seq + 1, ll_fout = p.ll_base + send_seq + 1, nvec = len >> 4;
+        const uint32_t ll_fin = ll_base + recv_seq + 1, ll_fout = ll_base + send_seq + 1, nvec = len >> 4;
         bool data_ok = true;
         for (uint32_t j = 0; j < ins.count; ++j) {
           const rsrc_t src = make_rsrc(srcb + (uint64_t)j * p.chunk_bytes, srcb ? len : 0);
@@ -811,7 +828,10 @@ __global__ void __launch_bounds__(64) gc3_interpreter_wave(KParams p) {
       }
     }
   }
-  if (tid == 0) store_flag(my_sem + 1, (uint64_t)epoch + 1);   // this fiber has completed one more run
+  if (tid == 0) {
+    store_flag(my_sem + 1, (uint64_t)epoch + 1);   // this fiber has completed one more run
+    if (LL) store_flag(my_sem + 3, ll_start + p.ll_msgs);
+  }
 }
 
 // Host-callable launcher; returns the hipError_t of the launch.  `coherent_user` selects the

@@ -402,6 +402,33 @@ def test_timeout_poisons_and_reset_recovers():
     run_case(prog, "f32", elems, "uniform", 5, small_cfg())
 
 
+def test_reset_restarts_the_ll_message_numbers():
+    """The LL flags count on from run to run in device memory; gc3_comm_reset starts them again, so it must also wipe
+    the LL slots: the first run after a reset expects exactly the flags the very first run left there, and would
+    otherwise take that run's payload for its own."""
+    H = _harness()
+    for cfg in (dict(wg_size=64), dict(team_width=2, target_wgs=16)):       # wavefront-level and general kernel
+        prog = programs.hierarchical_allreduce(2, 3)
+        text = prog.to_text()
+        p = oracle.parse_program(text)
+        elems = 6 * 2048
+        coll = H.Collective(text, "f32", elems, H.make_config(protocol=2, **cfg))
+        try:
+            for seed in (61, 62, 63):
+                ins = inputs.make_inputs(6, elems, "f32", "normal", seed)
+                want = [a.copy() for a in ins]
+                oracle.run_program(p, want, None, "f32", slots=2)
+                coll.upload(ins)
+                coll.run()
+                coll.status()
+                for g, w_ in zip(coll.download(), want):
+                    compare(g, w_, "f32")
+                if seed != 62:
+                    coll.reset()
+        finally:
+            coll.close()
+
+
 def test_tune_measures_plans_and_the_chosen_one_is_correct():
     H = _harness()
     from paper_2201_11840_amd import binding as B
@@ -804,20 +831,23 @@ def test_config3_with_lds_staging():
 # ---- a run recorded into a HIP graph ---------------------------------------------------------------------------
 
 def test_captured_runs_replay_bit_exactly():
-    """gc3_comm_run has constant kernel arguments (the run counters live in device memory), so a launch can be
-    captured and replayed.  A graph of [restore inputs, run] x 10 is replayed several times, with eager runs of
-    the same communicator and synchronisations in between; every replay must give the eager (oracle-checked)
-    result.  The restore is a copy kernel, not a memset node."""
+    """gc3_comm_run has constant kernel arguments (the run counters and the LL message numbers live in device
+    memory), so a launch can be captured and replayed, under either protocol.  A graph of [restore inputs, run] x 10
+    is replayed several times, with eager runs of the same communicator and synchronisations in between; every
+    replay must give the eager (oracle-checked) result.  The restore is a copy kernel, not a memset node."""
     import torch
     H = _harness()
-    for prog, dtype, elems in ((programs.ring_allreduce(8, instances=2), "f32", 16 * 8192),
-                               (programs.hierarchical_allreduce(2, 3), "bf16", 6 * 40000)):
+    for prog, dtype, elems, cfg in ((programs.ring_allreduce(8, instances=2), "f32", 16 * 8192, dict(protocol=1)),
+                                    (programs.hierarchical_allreduce(2, 3), "bf16", 6 * 40000, dict(protocol=1)),
+                                    # LL: general kernel (several fibers per workgroup) and wavefront-level kernel
+                                    (programs.hierarchical_allreduce(2, 3), "f16", 6 * 8192, dict(protocol=2, team_width=2, target_wgs=16)),
+                                    (programs.multichannel_ring_allreduce(8, 4), "f32", 8 * 2048, dict(protocol=2, wg_size=64))):
         text = prog.to_text()
         p = oracle.parse_program(text)
         ins = inputs.make_inputs(p.ranks, elems, dtype, "normal", 1400)
         want = [a.copy() for a in ins]
         oracle.run_program(p, want, None, dtype, slots=2)
-        coll = H.Collective(text, dtype, elems, H.make_config(protocol=1))
+        coll = H.Collective(text, dtype, elems, H.make_config(**cfg))
         try:
             coll.upload(ins)
             pristine = [t.clone() for t in coll.inputs]
@@ -849,29 +879,6 @@ def test_captured_runs_replay_bit_exactly():
                     compare(g, w_, dtype)
         finally:
             coll.close()
-    # the LL protocol's message numbers are kernel arguments: such a run is refused while its stream is capturing
-    import ctypes
-    from paper_2201_11840_amd import binding as B
-    hip = ctypes.CDLL("libamdhip64.so")
-    coll = H.Collective(programs.ring_allreduce(4).to_text(), "f32", 4 * 64, H.make_config(protocol=2))
-    side = torch.cuda.Stream()
-    try:
-        torch.cuda.synchronize()
-        relaxed = 2                                            # hipStreamCaptureModeRelaxed
-        assert hip.hipStreamBeginCapture(ctypes.c_void_p(side.cuda_stream), relaxed) == 0
-        try:
-            with pytest.raises(B.Gc3Error) as e:
-                B.gc3_comm_run(coll.comm, coll.elems, coll.code, B.GC3_SUM, side.cuda_stream)
-            assert e.value.status == B.GC3_ERR_ARG
-        finally:
-            g = ctypes.c_void_p()
-            assert hip.hipStreamEndCapture(ctypes.c_void_p(side.cuda_stream), ctypes.byref(g)) == 0
-            if g.value:
-                hip.hipGraphDestroy(g)
-        coll.run()                                             # outside capture the same communicator runs
-        coll.status()
-    finally:
-        coll.close()
 
 
 def test_buffers_beyond_4GiB_sampled():
