@@ -551,16 +551,17 @@ def test_config3_ring_allreduce_r8_x8(mib):
     run_case(w.build(), w.dtype, w.elems_per_rank, w.dist, w.seed)
 
 
-def _full_size_case(w):
-    """A benchmark configuration at its stated size, default launch configuration, EVERY element of every rank
-    against the oracle.  Host copies are dropped as soon as they have been compared."""
+def _full_size_case(w, tune=False):
+    """A benchmark configuration at its stated size, default launch configuration (or, with `tune`, the plan
+    gc3_comm_tune picks, as bench.py runs it), EVERY element of every rank against the oracle.  Host copies are
+    dropped as soon as they have been compared."""
     H = _harness()
     prog = w.build()
     text = prog.to_text()
     p = oracle.parse_program(text)
     assert p.inplace
     ins = inputs.make_inputs(p.ranks, w.elems_per_rank, w.dtype, w.dist, w.seed)
-    coll = H.Collective(text, w.dtype, w.elems_per_rank)
+    coll = H.Collective(text, w.dtype, w.elems_per_rank, tune=tune)
     try:
         coll.upload(ins)
         coll.run()
@@ -585,12 +586,23 @@ def test_config4_hierarchical_allreduce_2x8():
     _full_size_case(workloads.hier_ar_2x8(64))
 
 
-def test_config5_alltonext_3x8():
+def test_tuned_plans_at_the_stated_sizes():
+    """The plans the tuner picks for the benchmark's workloads are unlike the default one (die-scope FIFOs, one
+    wavefront per thread-block lane, 128 lanes, LL): the same full compare under them."""
+    table = workloads.by_name()
+    for name in ("ring_allreduce_r8_x8_f32_64MiB", "hier_allreduce_2x8_bf16_64MiB", "allpairs_allreduce_r8_f32_64MiB",
+                 "ring_allreduce_rrs_r8_x8_f32_64MiB", "ring_allreduce_r8_x8_f32_1MiB", "ring_allreduce_r4_f32_64KiB",
+                 "mc_ring_allreduce_r8_c4_f32_256KiB", "allpairs_allreduce_r8_f32_256KiB"):
+        _full_size_case(table[name], tune=True)
+    test_config5_alltonext_3x8(tune=True)
+
+
+def test_config5_alltonext_3x8(tune=False):
     w = workloads.alltonext_3x8()
     H = _harness()
     prog = w.build()
     ins = inputs.make_inputs(24, w.elems_per_rank, w.dtype, w.dist, w.seed)
-    coll = H.Collective(prog.to_text(), w.dtype, w.elems_per_rank)
+    coll = H.Collective(prog.to_text(), w.dtype, w.elems_per_rank, tune=tune)
     try:
         coll.fill_outputs_with_sentinel()
         coll.upload(ins)
@@ -602,6 +614,8 @@ def test_config5_alltonext_3x8():
     assert set(np.unique(got[0].view(np.uint16))) == {inputs.SENTINEL16}       # rank 0 receives nothing
     for r in range(1, 24):
         assert got[r].tobytes() == ins[r - 1].tobytes()                      # out[i+1] == in[i], bytewise
+    if tune:
+        return
     # the oracle on a smaller buffer of the same program, element by element
     run_case(prog, w.dtype, 8 * 65536, w.dist, w.seed, exact_only=True)
 
