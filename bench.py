@@ -187,36 +187,30 @@ def report(w, coll, mean_ms, min_ms, wall_ms, prog, launches_before_timed=0):
     return rec
 
 
-def graph_replay_us(text, elems, w, cfg, tune, runs_per_graph=20, replays=5):
-    """Time per run when 20 runs are recorded once into a HIP graph and the graph is replayed: what is left of a
-    latency-bound collective without the host's enqueue path."""
+def graph_replay_us(c, runs_per_graph=20, replays=5):
+    """Time per run when 20 runs of collective `c` are recorded once into a HIP graph and the graph is replayed:
+    what is left of a latency-bound collective without the host's enqueue path."""
     import torch
-    from paper_2201_11840_amd import harness
-    c = harness.Collective(text, "f32", elems, cfg, tune=tune)
-    try:
-        device_inputs(c, w, w.seed)
-        for _ in range(3):
+    for _ in range(3):
+        c.run()
+    c.status()
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.graph(graph, stream=side):
+        for _ in range(runs_per_graph):
             c.run()
-        c.status()
-        graph = torch.cuda.CUDAGraph()
-        side = torch.cuda.Stream()
-        side.wait_stream(torch.cuda.current_stream())
-        with torch.cuda.graph(graph, stream=side):
-            for _ in range(runs_per_graph):
-                c.run()
+    graph.replay()
+    torch.cuda.synchronize()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(replays):
         graph.replay()
-        torch.cuda.synchronize()
-        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        a.record()
-        for _ in range(replays):
-            graph.replay()
-        b.record()
-        torch.cuda.synchronize()
-        c.status()
-        return round(a.elapsed_time(b) * 1e3 / (replays * runs_per_graph), 2)
-    finally:
-        c.close()
-        torch.cuda.empty_cache()
+    b.record()
+    torch.cuda.synchronize()
+    c.status()
+    del graph
+    return round(a.elapsed_time(b) * 1e3 / (replays * runs_per_graph), 2)
 
 
 def size_sweep(steps, warmup, tune, cfg):
@@ -248,11 +242,11 @@ def size_sweep(steps, warmup, tune, cfg):
                          "algbw_GBps": round(kib * 1024 / (m * 1e-3) / 1e9, 2),
                          "team_width": c.info.team_width, "grid": li.grid, "wg_size": li.wg_size,
                          "kernel": KERNEL_NAMES[li.kernel]}
+            if kib <= 1024:
+                row[name]["us_graph_replay"] = graph_replay_us(c)
             c.close()
             del pr, c
             torch.cuda.empty_cache()
-            if kib <= 1024:
-                row[name]["us_graph_replay"] = graph_replay_us(prog.to_text(), elems, w, cfg, tune)
         log("[bench] size sweep " + json.dumps(row))
         rows.append(row)
     return rows
@@ -360,6 +354,9 @@ def main() -> int:
             m, mn, wl = time_workload(c2, args.steps, args.warmup, pr)
             before2 = (c2.tune_report.count * TUNE_LAUNCHES_PER_PLAN + TUNE_EXTRA_LAUNCHES if c2.tune_report is not None else 0) + args.warmup
             rec = report(w2, c2, m, mn, wl, prog2, before2)
+            if m < 0.1:                                   # latency-bound: also without the host's enqueue path
+                rec["ms_graph_replay"] = round(graph_replay_us(c2) * 1e-3, 5)
+                rec["interpreter_launches_after_timed"] = args.steps + 3 + 20 * 6     # back to back; warm-up, 6 replays of 20
             slots = c2.info.fifo_slots
             c2.close()
             del pr, c2
