@@ -99,10 +99,11 @@ typedef struct gc3_comm_config {
                               blocks x W stays within target_wgs: every lane then has a workgroup of its
                               own).  0 = choose W and the sharing so that the heaviest workgroup is
                               lightest */
-  int32_t wg_size;         /* threads per workgroup: 64, 128, 256 or 512; default 256 (a run whose lanes get
-                              at most 8 KiB of a chunk launches 128 of them).  With 64, runs in which every
-                              workgroup executes a single thread-block lane use the wavefront-level
-                              interpreter: no workgroup barrier and no LDS state on the path of a hop */
+  int32_t wg_size;         /* threads per workgroup: 64, 128, 256 or 512; default 256.  A run whose lanes get
+                              at most 8 KiB of a chunk launches fewer: 64 when every workgroup executes a
+                              single thread-block lane, else at most 128.  Workgroups of 64 threads with a
+                              single thread-block lane each run the wavefront-level interpreter (under either
+                              protocol): no workgroup barrier and no LDS state on the path of a hop */
   int32_t lds_stage;       /* 1 = the receiving instructions (recv, rrc, rcs, rrcs, rrs) bring the FIFO payload into LDS
                               with direct-to-LDS 128-bit loads and read it back from there, so loads in flight
                               hold no registers; 0 (default) = through registers.  Same results; on MI355X the
