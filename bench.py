@@ -350,7 +350,7 @@ def main() -> int:
             c2 = harness.Collective(prog2.to_text(), w2.dtype, w2.elems_per_rank, cfg, tune=tune)
             device_inputs(c2, w2, w2.seed)
             c2.fill_outputs_with_sentinel()
-            pr = [t.clone() for t in c2.inputs] if c2.inplace else None
+            pr = [t.clone() for t in c2.inputs]      # every run finds freshly written inputs, in place or not
             m, mn, wl = time_workload(c2, args.steps, args.warmup, pr)
             before2 = (c2.tune_report.count * TUNE_LAUNCHES_PER_PLAN + TUNE_EXTRA_LAUNCHES if c2.tune_report is not None else 0) + args.warmup
             rec = report(w2, c2, m, mn, wl, prog2, before2)
