@@ -302,7 +302,11 @@ int gc3_comm_launch_info(const gc3_comm* comm, size_t elems_per_rank, gc3_dtype 
  * counters and the LL message numbers live in device memory), the call copies nothing and waits for nothing, so
  * under either protocol it may be recorded into a HIP graph and replayed any number of times, also interleaved
  * with eager runs of the same communicator (never overlapping them).  A communicator serves 2^32 - 1 runs between
- * resets. */
+ * resets.
+ * The call records no event of its own (that costs a latency-bound collective several microseconds): the library
+ * remembers `hip_stream` and records an event on it when the run has to be waited for - in gc3_comm_status,
+ * gc3_comm_bind, gc3_comm_destroy, or when a run of another communicator must not overlap this one.  Keep the
+ * stream alive until then; if it is gone, the whole device is waited for instead. */
 int gc3_comm_run(gc3_comm* comm, size_t elems_per_rank, gc3_dtype dtype, gc3_redop op, void* hip_stream);
 
 /* Bytes the method itself loads and stores through global memory in one run of this size: the sum over all
