@@ -137,7 +137,11 @@ int wait_for_last_run(gc3_comm* c) {
     rc = settle_event(c);
     if (rc != GC3_OK) c->event_pending = false;
   }
-  if (rc != GC3_OK) { HIP_TRY(hipDeviceSynchronize()); return GC3_OK; }
+  if (rc != GC3_OK) {
+    (void)hipGetLastError();
+    HIP_TRY(hipDeviceSynchronize());
+    return GC3_OK;
+  }
   if (c->done_recorded) HIP_TRY(hipEventSynchronize(c->done));
   return GC3_OK;
 }
@@ -159,11 +163,17 @@ int ledger_make_room(const gc3_comm* c, int device, hipStream_t st, int32_t wgs,
   // must not overlap); other owners' runs that have completed no longer occupy the device
   v.erase(std::remove_if(v.begin(), v.end(), [&](const LedgerEntry& e) { return e.owner == c; }), v.end());
   for (LedgerEntry& e : v) {
-    int rc = settle_event(e.owner);
-    if (rc != GC3_OK) return rc;
+    if (settle_event(e.owner) != GC3_OK) {
+      // the other communicator's stream is gone: nothing can be recorded on it any more, so wait for everything
+      // the device still runs (its run included) and count that run as finished
+      e.owner->event_pending = false;
+      (void)hipGetLastError();
+      HIP_TRY(hipDeviceSynchronize());
+      e.wgs = 0;
+    }
   }
   v.erase(std::remove_if(v.begin(), v.end(), [&](const LedgerEntry& e) {
-            return hipEventQuery(e.owner->done) == hipSuccess;
+            return e.wgs == 0 || !e.owner->done_recorded || hipEventQuery(e.owner->done) == hipSuccess;
           }), v.end());
   std::vector<InFlightRun> runs;
   for (const LedgerEntry& e : v) runs.push_back({(uint64_t)(uintptr_t)e.stream, e.wgs, e.capacity});
