@@ -63,6 +63,39 @@ def test_many_runs_give_the_same_verified_result(w, scope):
         coll.close()
 
 
+@pytest.mark.parametrize("name,build,dtype,nbytes,cfg", [
+    ("mc_ring_r8_c4_4KiB", lambda: programs.multichannel_ring_allreduce(8, 4), "f32", 4096, dict(protocol=2, wg_size=64)),
+    ("ring_r8_64KiB_8slots", lambda: programs.ring_allreduce(8), "f32", 65536,
+     dict(protocol=2, wg_size=64, fifo_slots=8, min_lane_bytes=1024)),
+    ("hier_2x3_96KiB_general", lambda: programs.hierarchical_allreduce(2, 3), "bf16", 6 * 16384,
+     dict(protocol=2, team_width=2, target_wgs=16)),
+    ("allpairs_r8_32KiB", lambda: programs.allpairs_allreduce(8), "f16", 32768, dict(protocol=2, wg_size=64)),
+], ids=lambda x: x if isinstance(x, str) else "")
+def test_many_ll_runs_give_the_same_verified_result(name, build, dtype, nbytes, cfg):
+    """The LL protocol under repetition: its flags count on from run to run in device memory, slots are reused
+    with and without head-flag polls, on the wavefront-level and on the general kernel."""
+    w = workloads.Workload(name, build, dtype, nbytes, "normal", 11)
+    prog = w.build()
+    ins = inputs.make_inputs(prog.ranks, w.elems_per_rank, w.dtype, w.dist, w.seed)
+    coll = H.Collective(prog.to_text(), w.dtype, w.elems_per_rank, H.make_config(**cfg))
+    assert coll.launch.kernel in (1, 4)
+    try:
+        _verified_first_run(w, coll, ins)
+        good = [t.clone() for t in coll.outputs]
+        coll.upload(ins)
+        pristine = [t.clone() for t in coll.inputs]
+        for it in range(3000):
+            for d, s in zip(coll.inputs, pristine):
+                d.copy_(s)
+            coll.run()
+            if it % 100 == 99:
+                coll.status()
+                for r in range(coll.ranks):
+                    assert torch.equal(coll.outputs[r], good[r]), f"run {it}, rank {r}"
+    finally:
+        coll.close()
+
+
 def test_two_communicators_and_a_side_stream():
     # two communicators alive at once, launched alternately on a non-default stream
     a = workloads.ring_ar_r8x8(1)
