@@ -89,8 +89,9 @@ typedef struct gc3_comm_config {
   int32_t fifo_slots;      /* s of Section 6.1, 1..8; default 2 */
   int32_t tile_bytes;      /* largest number of bytes of one chunk a workgroup moves per tile (Section 6.2,
                               chunk tiling); multiple of 16, at most 1 MiB; default 65536, halved (not
-                              below 16384) while all FIFOs together exceed 256 MiB.  A FIFO slot holds
-                              max_count x tile_bytes.  A run tiles with about half a lane's share of a
+                              below 16384) while all FIFOs together exceed 256 MiB.  A FIFO slot of a
+                              connection holds tile_bytes x the largest `count` of the instructions that use
+                              that connection.  A run tiles with about half a lane's share of a
                               chunk, at least 16 KiB and at most this. */
   int32_t team_width;      /* W: lanes per IR thread block; lane w owns the w-th 1/W of every chunk and
                               has FIFO slots, flags and a semaphore of its own (the runtime applying
@@ -151,7 +152,8 @@ typedef struct gc3_comm_info {
   int32_t max_resident_wgs;  /* occupancy x compute units */
   int32_t fifo_slots;
   int32_t tile_bytes;
-  int32_t slot_bytes;        /* max_count x tile_bytes */
+  int32_t slot_bytes;        /* the largest slot: max_count x tile_bytes (a connection's slots are sized for the
+                                largest `count` among its own instructions) */
   uint64_t fifo_bytes;       /* device memory held by all FIFOs */
   int32_t compute_units;
   int32_t max_fibers_per_wg; /* most thread-block lanes multiplexed by one workgroup (1 = none shared) */

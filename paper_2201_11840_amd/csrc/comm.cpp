@@ -52,7 +52,7 @@ struct gc3_comm {
   bool die_scope = false;   // FIFO payload is read from the L2 of the die both ends of a connection run on
   uint64_t min_lane_bytes = 8192;
   uint64_t ll_max_lane_bytes = 8192;
-  uint32_t ll_slot_bytes = 0;
+  uint32_t ll_unit_bytes = 0;
   int max_pushes = 0;
   uint64_t algorithmic_chunks = 0;
   std::vector<int32_t> scratch_chunks;
@@ -237,7 +237,7 @@ void shape_run_with(const gc3_comm_info& info, uint64_t cb, uint64_t min_lane_by
   // small chunks are not worth splitting over all lanes: every active lane gets at least min_lane_bytes
   p.W_active = (uint32_t)std::max<uint64_t>(1, std::min<uint64_t>(p.W, cb / min_lane_bytes));
   p.slots = (uint32_t)info.fifo_slots;
-  p.slot_bytes = (uint32_t)info.slot_bytes;
+  p.unit_bytes = (uint32_t)info.tile_bytes;
   // Shares are computed exactly as the kernel does.
   uint64_t lane_share = 0;
   {
@@ -348,7 +348,7 @@ int gc3_comm_create(const gc3_program* prog, const gc3_comm_config* cfg_in, gc3_
   c->die_scope = cfg.fifo_scope == 2;
   c->min_lane_bytes = (uint64_t)cfg.min_lane_bytes;
   c->ll_max_lane_bytes = (uint64_t)cfg.ll_max_lane_bytes;
-  c->ll_slot_bytes = (uint32_t)(2ull * plan.max_count * (uint64_t)cfg.ll_max_lane_bytes);
+  c->ll_unit_bytes = (uint32_t)(2ull * (uint64_t)cfg.ll_max_lane_bytes);
   c->max_pushes = plan.max_pushes;
   for (int r = 0; r < R; ++r) c->scratch_chunks.push_back(prog->rank[r].scratch_chunks);
   c->bufs.assign((size_t)R * 3, nullptr);
@@ -472,7 +472,7 @@ int gc3_comm_run(gc3_comm* comm, size_t elems_per_rank, gc3_dtype dtype, gc3_red
   p.spin_limit_ticks = comm->spin_limit_ticks;
   shape_run(comm->info, cb, comm->min_lane_bytes, comm->ll_max_lane_bytes, comm->lds_stage, comm->die_scope, L);
   p.ll_fifo = comm->d_ll_fifo;
-  p.ll_slot_bytes = comm->ll_slot_bytes;
+  p.ll_unit_bytes = comm->ll_unit_bytes;
   if (L.ll) {
     // an upper bound of the messages one connection carries in this run: the same for every run of one size, so
     // the kernel's arguments stay constant (the fibers keep the running message number in device memory)

@@ -46,12 +46,17 @@ struct DWg {               // 32 bytes, one per (lane, bin) of the plan
   uint32_t pad[3];
 };
 
-struct DFiber {            // 32 bytes: one lane of one IR thread block
+struct DFiber {            // 48 bytes: one lane of one IR thread block
   uint32_t fid;            // global thread-block index * W + lane
   uint32_t instr_begin, ninstr;
   int32_t send_conn, recv_conn;  // connection index or -1
   uint32_t recv_from_tb;   // global index of the thread block at the sending end of recv_conn (die-scope FIFOs:
                            // the receiver checks that it runs on the sender's die), 0xffffffff if none
+  // Where the connections' slots are.  A slot of connection c holds count(c) units (count(c) = the largest `count`
+  // of an instruction that uses c; a unit = the slot tile of the plan); the connections follow one another in FIFO
+  // memory, `before` = the sum of count over the connections in front of this one.
+  uint32_t send_units_before, send_count;
+  uint32_t recv_units_before, recv_count;
   uint32_t pad[2];
 };
 
@@ -61,8 +66,8 @@ struct KParams {
   const DWg* wgs;          // [W * wgs_per_lane], lane-major
   const DFiber* fibers;
   void* const* bufs;       // [rank*3 + buffer] user buffers
-  unsigned char* fifo;     // [(conn*W + lane) * slots + slot] * slot_bytes
-  unsigned char* ll_fifo;  // the same for the LL protocol, slots of ll_slot_bytes (data + flag pairs only)
+  unsigned char* fifo;     // connection c, lane, slot at ((before(c) * W + lane * count(c)) * slots + slot * count(c)) * unit_bytes
+  unsigned char* ll_fifo;  // the same for the LL protocol with ll_unit_bytes (data + flag pairs only)
   uint64_t* flags;         // [((conn*W + lane)*2 + {0 tail, 1 head}) * kFlagStrideWords]
   uint64_t* sems;          // [(tb*W + lane) * kFlagStrideWords]: word 0 the semaphore, word 1 the fiber's epoch
                            // (runs it has completed); flag values of a run lie above (epoch + 1) << 32;
@@ -72,8 +77,9 @@ struct KParams {
   const uint32_t* hold;    // null, or a start word every workgroup waits for (failure-path tests)
   uint64_t chunk_bytes;
   uint64_t spin_limit_ticks;  // of the 100 MHz wall clock
-  uint32_t W, slots, tile_bytes, slot_bytes;
-  uint32_t ll_slot_bytes;  // 2 * max_count * LL tile bytes
+  uint32_t W, slots, tile_bytes;
+  uint32_t unit_bytes;     // what a slot holds per unit of `count`: the slot tile of the plan (>= tile_bytes)
+  uint32_t ll_unit_bytes;  // 2 * LL tile bytes
   uint32_t ll_msgs;        // LL protocol: an upper bound of the messages one connection carries in this run.  Every
                            // fiber keeps the number of LL messages of its past runs next to its epoch (word 3 of its
                            // semaphore line); message k of this run carries flag = low 32 bits of that number + k + 1

@@ -452,6 +452,9 @@ __global__ void __launch_bounds__(512) gc3_interpreter(KParams p) {
   // per fiber: its thread block's record and the three buffer pointers of its rank, fetched once
   __shared__ uint32_t f_ibeg[kMaxFibersPerWg], f_ninstr[kMaxFibersPerWg], f_ilds[kMaxFibersPerWg];
   __shared__ int32_t f_sconn[kMaxFibersPerWg], f_rconn[kMaxFibersPerWg];
+  // slots of the fiber's connections: position of its first slot in units of `count` x slot tile, units per slot
+  __shared__ uint64_t f_sfirst[kMaxFibersPerWg], f_rfirst[kMaxFibersPerWg];
+  __shared__ uint32_t f_scount[kMaxFibersPerWg], f_rcount[kMaxFibersPerWg];
   __shared__ uint64_t s_buf[3];
   // the instruction lists of this workgroup's fibers, when they fit (else they are read from global memory
   // every time): an instruction is fetched once per tile, and a fetch is a dependent global access on the
@@ -499,6 +502,10 @@ __global__ void __launch_bounds__(512) gc3_interpreter(KParams p) {
     f_ilds[tid] = f.instr_begin - hdr.instr_begin;
     f_sconn[tid] = f.send_conn;
     f_rconn[tid] = f.recv_conn;
+    f_sfirst[tid] = ((uint64_t)f.send_units_before * W + (uint64_t)lane * f.send_count) * p.slots;
+    f_rfirst[tid] = ((uint64_t)f.recv_units_before * W + (uint64_t)lane * f.recv_count) * p.slots;
+    f_scount[tid] = f.send_count;
+    f_rcount[tid] = f.recv_count;
   }
   if (tid >= 32 && tid < 35) s_buf[tid - 32] = (uint64_t)p.bufs[hdr.rank * 3 + (tid - 32)];
   const bool instr_in_lds = hdr.ninstr <= (uint32_t)kLdsInstrs;
@@ -535,9 +542,10 @@ __global__ void __launch_bounds__(512) gc3_interpreter(KParams p) {
       uint64_t* const tail_recv = recv_conn >= 0 ? flag_of(p, recv_conn, lane, 0) : nullptr;
       uint64_t* const head_recv = recv_conn >= 0 ? flag_of(p, recv_conn, lane, 1) : nullptr;
       unsigned char* const fifo_base = LL ? p.ll_fifo : p.fifo;            // LL slots have a region of their own
-      const uint32_t slot_bytes = LL ? p.ll_slot_bytes : p.slot_bytes;
-      unsigned char* const fifo_send = send_conn >= 0 ? fifo_base + (uint64_t)((uint32_t)send_conn * W + lane) * p.slots * slot_bytes : nullptr;
-      unsigned char* const fifo_recv = recv_conn >= 0 ? fifo_base + (uint64_t)((uint32_t)recv_conn * W + lane) * p.slots * slot_bytes : nullptr;
+      const uint32_t unit_bytes = LL ? p.ll_unit_bytes : p.unit_bytes;
+      const uint32_t sslot_bytes = uni(f_scount[fi]) * unit_bytes, rslot_bytes = uni(f_rcount[fi]) * unit_bytes;
+      unsigned char* const fifo_send = send_conn >= 0 ? fifo_base + uni64(f_sfirst[fi]) * unit_bytes : nullptr;
+      unsigned char* const fifo_recv = recv_conn >= 0 ? fifo_base + uni64(f_rfirst[fi]) * unit_bytes : nullptr;
       uint64_t* const my_sem = sem_of(p, tbi, lane);
 
       bool progressed = false;
@@ -582,7 +590,7 @@ __global__ void __launch_bounds__(512) gc3_interpreter(KParams p) {
             }
             if (LL && pops && !block && res == 1) {
               // non-blocking readiness probe: has the first element of the message arrived?
-              const uint32_t* first = (const uint32_t*)(fifo_recv + (uint64_t)(recv_seq % p.slots) * slot_bytes);
+              const uint32_t* first = (const uint32_t*)(fifo_recv + (uint64_t)(recv_seq % p.slots) * rslot_bytes);
               if (__hip_atomic_load(first + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != ll_fin) res = 0;
             }
             if (tid == 0) s_res[phase & 1] = res;
@@ -599,8 +607,8 @@ __global__ void __launch_bounds__(512) gc3_interpreter(KParams p) {
         const uint64_t coff = off0 + toff;   // byte offset inside each chunk
         unsigned char* const srcb = ins.srcbuf < 3 ? (unsigned char*)uni64(s_buf[ins.srcbuf]) + (uint64_t)ins.srcidx * p.chunk_bytes + coff : nullptr;
         unsigned char* const dstb = ins.dstbuf < 3 ? (unsigned char*)uni64(s_buf[ins.dstbuf]) + (uint64_t)ins.dstidx * p.chunk_bytes + coff : nullptr;
-        unsigned char* const rslot = pops ? fifo_recv + (uint64_t)(recv_seq % p.slots) * slot_bytes : nullptr;
-        unsigned char* const sslot = pushes ? fifo_send + (uint64_t)(send_seq % p.slots) * slot_bytes : nullptr;
+        unsigned char* const rslot = pops ? fifo_recv + (uint64_t)(recv_seq % p.slots) * rslot_bytes : nullptr;
+        unsigned char* const sslot = pushes ? fifo_send + (uint64_t)(send_seq % p.slots) * sslot_bytes : nullptr;
         bool data_ok = true;
         if (LL && (pops || pushes)) {
           constexpr int UL = COH ? kUserLdCoh : kUserLd, US = COH ? kUserStCoh : kUserSt;
@@ -746,9 +754,13 @@ __global__ void __launch_bounds__(64) gc3_interpreter_wave(KParams p) {
   uint64_t* const tail_recv = recv_conn >= 0 ? flag_of(p, recv_conn, lane, 0) : nullptr;
   uint64_t* const head_recv = recv_conn >= 0 ? flag_of(p, recv_conn, lane, 1) : nullptr;
   unsigned char* const fifo_base = LL ? p.ll_fifo : p.fifo;
-  const uint32_t slot_bytes = LL ? p.ll_slot_bytes : p.slot_bytes;
-  unsigned char* const fifo_send = send_conn >= 0 ? fifo_base + (uint64_t)((uint32_t)send_conn * W + lane) * p.slots * slot_bytes : nullptr;
-  unsigned char* const fifo_recv = recv_conn >= 0 ? fifo_base + (uint64_t)((uint32_t)recv_conn * W + lane) * p.slots * slot_bytes : nullptr;
+  const uint32_t unit_bytes = LL ? p.ll_unit_bytes : p.unit_bytes;
+  const uint32_t send_count = uni(f.send_count), recv_count = uni(f.recv_count);
+  const uint32_t sslot_bytes = send_count * unit_bytes, rslot_bytes = recv_count * unit_bytes;
+  unsigned char* const fifo_send = send_conn >= 0
+      ? fifo_base + ((uint64_t)uni(f.send_units_before) * W + (uint64_t)lane * send_count) * p.slots * unit_bytes : nullptr;
+  unsigned char* const fifo_recv = recv_conn >= 0
+      ? fifo_base + ((uint64_t)uni(f.recv_units_before) * W + (uint64_t)lane * recv_count) * p.slots * unit_bytes : nullptr;
   uint32_t send_seq = 0, recv_seq = 0, head_known = 0;
 
   for (uint32_t t = 0; t < ntiles; ++t) {               // tile loop outside, instruction loop inside
@@ -788,8 +800,8 @@ __global__ void __launch_bounds__(64) gc3_interpreter_wave(KParams p) {
       const uint64_t coff = off0 + toff;
       unsigned char* const srcb = ins.srcbuf < 3 ? bufs[ins.srcbuf] + (uint64_t)ins.srcidx * p.chunk_bytes + coff : nullptr;
       unsigned char* const dstb = ins.dstbuf < 3 ? bufs[ins.dstbuf] + (uint64_t)ins.dstidx * p.chunk_bytes + coff : nullptr;
-      unsigned char* const rslot = pops ? fifo_recv + (uint64_t)(recv_seq % p.slots) * slot_bytes : nullptr;
-      unsigned char* const sslot = pushes ? fifo_send + (uint64_t)(send_seq % p.slots) * slot_bytes : nullptr;
+      unsigned char* const rslot = pops ? fifo_recv + (uint64_t)(recv_seq % p.slots) * rslot_bytes : nullptr;
+      unsigned char* const sslot = pushes ? fifo_send + (uint64_t)(send_seq % p.slots) * sslot_bytes : nullptr;
       if (LL && (pops || pushes)) {
         constexpr int UL = COH ? kUserLdCoh : kUserLd, US = COH ? kUserStCoh : kUserSt;
         const uint32_t ll_fin = ll_base + recv_seq + 1, ll_fout = ll_base + send_seq + 1, nvec = len >> 4;

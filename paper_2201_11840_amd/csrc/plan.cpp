@@ -74,6 +74,7 @@ int make_plan(const gc3_program& prog, const gc3_comm_config& cfg, int cus, long
     return id;
   };
   std::vector<int> conn_sender;   // global thread-block index of the sending end of every connection
+  std::vector<uint32_t> conn_count;   // largest `count` of an instruction that uses the connection
   auto note_end = [&](std::vector<int>& ends, int conn, int tb) {
     if ((int)ends.size() <= conn) ends.resize(conn + 1, -1);
     ends[conn] = tb;
@@ -97,8 +98,12 @@ int make_plan(const gc3_program& prog, const gc3_comm_config& cfg, int cus, long
       d.ninstr = (uint32_t)tb.instrs.size();
       d.send_conn = d.recv_conn = -1;
       for (const Instr& in : tb.instrs) {
-        if (op_pushes(in.op)) { d.send_conn = conn_of(r, tb.send, tb.chan); note_end(conn_sender, d.send_conn, g); }
-        if (op_pops(in.op)) d.recv_conn = conn_of(tb.recv, r, tb.chan);
+        auto note_count = [&](int conn) {
+          if ((int)conn_count.size() <= conn) conn_count.resize(conn + 1, 1);
+          conn_count[conn] = std::max<uint32_t>(conn_count[conn], (uint32_t)in.count);
+        };
+        if (op_pushes(in.op)) { d.send_conn = conn_of(r, tb.send, tb.chan); note_end(conn_sender, d.send_conn, g); note_count(d.send_conn); }
+        if (op_pops(in.op)) { d.recv_conn = conn_of(tb.recv, r, tb.chan); note_count(d.recv_conn); }
         DInstr di{};
         di.op = in.op;
         di.srcbuf = (in.srcbuf == BUF_OUT && prog.inplace) ? (uint32_t)BUF_IN : in.srcbuf;
@@ -122,6 +127,11 @@ int make_plan(const gc3_program& prog, const gc3_comm_config& cfg, int cus, long
     }
   }
   const int nconn = (int)conn_id.size();
+  // FIFO memory is laid out connection by connection, each with slots of its own size
+  conn_count.resize(nconn, 1);
+  std::vector<uint32_t> units_before(nconn + 1, 0);
+  for (int c = 0; c < nconn; ++c) units_before[c + 1] = units_before[c] + conn_count[c];
+  const uint64_t total_units = units_before[nconn];
 
 
   // about four workgroups per compute unit give enough bytes in flight to cover memory latency
@@ -257,6 +267,8 @@ int make_plan(const gc3_program& prog, const gc3_comm_config& cfg, int cus, long
         f.recv_conn = tbs[g].recv_conn;
         f.recv_from_tb = (tbs[g].recv_conn >= 0 && (size_t)tbs[g].recv_conn < conn_sender.size())
                              ? (uint32_t)conn_sender[tbs[g].recv_conn] : 0xffffffffu;
+        if (f.send_conn >= 0) { f.send_units_before = units_before[f.send_conn]; f.send_count = conn_count[f.send_conn]; }
+        if (f.recv_conn >= 0) { f.recv_units_before = units_before[f.recv_conn]; f.recv_count = conn_count[f.recv_conn]; }
         fibers.push_back(f);
         h.ninstr += tbs[g].ninstr;
         h.rank = tbs[g].rank;
@@ -277,12 +289,12 @@ int make_plan(const gc3_program& prog, const gc3_comm_config& cfg, int cus, long
     // shared with the user data that streams through)
     const uint64_t soft = fifo_limit ? fifo_limit : cfg.fifo_scope == 2 ? (16ull << 20) : (256ull << 20);
     const int floor_bytes = fifo_limit ? 1024 : cfg.fifo_scope == 2 ? 4096 : 16384;
-    while (tile_bytes > floor_bytes && (uint64_t)nconn * W * cfg.fifo_slots * max_count * (uint64_t)tile_bytes > soft)
+    while (tile_bytes > floor_bytes && total_units * W * cfg.fifo_slots * (uint64_t)tile_bytes > soft)
       tile_bytes /= 2;
   }
   plan.cfg.tile_bytes = tile_bytes;
   const uint64_t slot_bytes = (uint64_t)max_count * (uint64_t)tile_bytes;
-  const uint64_t fifo_bytes = std::max<uint64_t>(16, (uint64_t)nconn * W * cfg.fifo_slots * slot_bytes);
+  const uint64_t fifo_bytes = std::max<uint64_t>(16, total_units * W * cfg.fifo_slots * (uint64_t)tile_bytes);
   if (slot_bytes > (1ull << 30) || fifo_bytes > (64ull << 30)) { msg = "FIFO memory too large"; return GC3_ERR_SIZE; }
   if (fifo_limit && fifo_bytes > fifo_limit) {
     msg = "the connections' FIFOs need " + std::to_string(fifo_bytes) + " bytes, " + std::to_string(fifo_limit) + " are available";
@@ -292,7 +304,8 @@ int make_plan(const gc3_program& prog, const gc3_comm_config& cfg, int cus, long
   if (cfg.fifo_scope == 2) protocol = 1;
   if (protocol == 0) protocol = prog.protocol == "simple" ? 1 : (prog.protocol == "ll" || prog.protocol == "ll128") ? 2 : 3;
   const uint64_t ll_slot_bytes = 2ull * max_count * (uint64_t)cfg.ll_max_lane_bytes;
-  const uint64_t ll_fifo_bytes = protocol == 1 ? 0 : std::max<uint64_t>(16, (uint64_t)nconn * W * cfg.fifo_slots * ll_slot_bytes);
+  const uint64_t ll_fifo_bytes =
+      protocol == 1 ? 0 : std::max<uint64_t>(16, total_units * W * cfg.fifo_slots * 2ull * (uint64_t)cfg.ll_max_lane_bytes);
   if (protocol != 1 && (ll_slot_bytes > (1ull << 30) || ll_fifo_bytes > (64ull << 30))) {
     msg = "LL FIFO memory too large";
     return GC3_ERR_SIZE;
