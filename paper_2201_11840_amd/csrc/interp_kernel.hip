@@ -200,6 +200,7 @@ __device__ __forceinline__ bool move_tile_ll(rsrc_t in_ll, rsrc_t src, rsrc_t ds
       uint32_t spins = 0;
       for (;;) {
         bool all = true;
+        asm volatile("" ::: "memory");                   // the slot is re-read in every iteration, never hoisted
 #pragma unroll
         for (int u = 0; u < UN; ++u) {
           const uint32_t i = base + u * nthreads;
