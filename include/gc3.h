@@ -86,7 +86,8 @@ typedef struct gc3_program_info {
 
 /* Tunables of a communicator.  Zero in any field selects the default. */
 typedef struct gc3_comm_config {
-  int32_t fifo_slots;      /* s of Section 6.1, 1..8; default 2 */
+  int32_t fifo_slots;      /* s of Section 6.1, 1..8; default 2 (with 4 or more a receiver may announce freed slots
+                              less often than after every message, see gc3_comm_info.head_stride) */
   int32_t tile_bytes;      /* largest number of bytes of one chunk a workgroup moves per tile (Section 6.2,
                               chunk tiling); multiple of 16, at most 1 MiB; default 65536, halved (not
                               below 16384) while all FIFOs together exceed 256 MiB.  A FIFO slot of a
@@ -162,6 +163,11 @@ typedef struct gc3_comm_info {
                                 team_width / active lanes workgroups each (split) */
   int32_t protocol;          /* 1 simple, 2 LL, 3 auto (after applying the configuration's override) */
   uint64_t ll_fifo_bytes;    /* device memory held by the LL slots */
+  int32_t head_stride;       /* a receiver announces freed slots after every head_stride-th message it has taken: 1, or
+                                - with 4 or more slots - 2 (4 with 8 slots) when the program is also free of
+                                deadlock with fifo_slots - head_stride + 1 slots, which is what a sender can then
+                                count on (Section 6.1: a sender may be up to s messages ahead) */
+  int32_t reserved;
 } gc3_comm_info;
 
 /* Message for the most recent error on this thread.  host; owned by the library; never null. */

@@ -68,7 +68,8 @@ class CommInfo(C.Structure):
                 ("active_wgs", C.c_int32), ("max_resident_wgs", C.c_int32), ("fifo_slots", C.c_int32),
                 ("tile_bytes", C.c_int32), ("slot_bytes", C.c_int32), ("fifo_bytes", C.c_uint64),
                 ("compute_units", C.c_int32), ("max_fibers_per_wg", C.c_int32),
-                ("wgs_per_lane", C.c_int32), ("protocol", C.c_int32), ("ll_fifo_bytes", C.c_uint64)]
+                ("wgs_per_lane", C.c_int32), ("protocol", C.c_int32), ("ll_fifo_bytes", C.c_uint64),
+                ("head_stride", C.c_int32), ("reserved", C.c_int32)]
 
 
 GC3_TUNE_MAX_TRIED = 96

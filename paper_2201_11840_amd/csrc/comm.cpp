@@ -237,6 +237,7 @@ void shape_run_with(const gc3_comm_info& info, uint64_t cb, uint64_t min_lane_by
   // small chunks are not worth splitting over all lanes: every active lane gets at least min_lane_bytes
   p.W_active = (uint32_t)std::max<uint64_t>(1, std::min<uint64_t>(p.W, cb / min_lane_bytes));
   p.slots = (uint32_t)info.fifo_slots;
+  p.head_mask = (uint32_t)std::max(1, info.head_stride) - 1;
   p.unit_bytes = (uint32_t)info.tile_bytes;
   // Shares are computed exactly as the kernel does.
   uint64_t lane_share = 0;

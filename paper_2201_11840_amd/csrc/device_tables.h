@@ -78,6 +78,8 @@ struct KParams {
   uint64_t chunk_bytes;
   uint64_t spin_limit_ticks;  // of the 100 MHz wall clock
   uint32_t W, slots, tile_bytes;
+  uint32_t head_mask;      // a receiver stores the head flag when (messages taken & head_mask) == 0: the plan's
+                           // head stride (a power of two) minus one
   uint32_t unit_bytes;     // what a slot holds per unit of `count`: the slot tile of the plan (>= tile_bytes)
   uint32_t ll_unit_bytes;  // 2 * LL tile bytes
   uint32_t ll_msgs;        // LL protocol: an upper bound of the messages one connection carries in this run.  Every

@@ -651,7 +651,7 @@ __global__ void __launch_bounds__(512) gc3_interpreter(KParams p) {
           }
           if (tid == 0) {
             if (pushes && !LL) store_flag(tail_send, run_base + send_seq);
-            if (pops) store_flag(head_recv, run_base + recv_seq);
+            if (pops && (recv_seq & p.head_mask) == 0) store_flag(head_recv, run_base + recv_seq);
             if (hasdep) store_flag(my_sem, run_base + (uint64_t)t * tb_ninstr + s + 1);
           }
         }
@@ -835,7 +835,7 @@ __global__ void __launch_bounds__(64) gc3_interpreter_wave(KParams p) {
         if (!LL || hasdep) __builtin_amdgcn_s_waitcnt(0);
         if (tid == 0) {
           if (pushes && !LL) store_flag(tail_send, run_base + send_seq);
-          if (pops) store_flag(head_recv, run_base + recv_seq);
+          if (pops && (recv_seq & p.head_mask) == 0) store_flag(head_recv, run_base + recv_seq);
           if (hasdep) store_flag(my_sem, run_base + (uint64_t)t * tb_ninstr + s + 1);
         }
       }

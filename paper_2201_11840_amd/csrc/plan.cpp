@@ -58,6 +58,18 @@ int make_plan(const gc3_program& prog, const gc3_comm_config& cfg, int cus, long
   int rc = validate(prog, cfg.fifo_slots, msg);
   if (rc != GC3_OK) return rc;
   plan.cfg = cfg;
+  // A receiver that announces freed slots only after every h-th message saves flag stores on the path of a hop.
+  // A sender can then count on s - h + 1 slots only (it sees the receiver's count rounded down to a multiple
+  // of h), and may find up to s: if the program completes with s - h + 1 slots it completes under this rule too
+  // (take the order of events of a complete execution with s - h + 1 slots: the first of them that has not
+  // happened yet is always enabled - its message has been sent, or at most as many messages are in flight as
+  // then, or its semaphore has been set).
+  int head_stride = 1;
+  if (cfg.fifo_slots >= 4) {
+    const int h = cfg.fifo_slots >= 8 ? 4 : 2;
+    std::string unused;
+    if (validate(prog, cfg.fifo_slots - h + 1, unused) == GC3_OK) head_stride = h;
+  }
 
   // ---- flatten the program -------------------------------------------------------------------
   const int R = prog.ranks;
@@ -337,6 +349,7 @@ int make_plan(const gc3_program& prog, const gc3_comm_config& cfg, int cus, long
   plan.info.max_fibers_per_wg = max_fibers;
   plan.info.protocol = protocol;
   plan.info.ll_fifo_bytes = ll_fifo_bytes;
+  plan.info.head_stride = head_stride;
   return GC3_OK;
 }
 

@@ -290,6 +290,39 @@ def test_largest_tile_and_slot_settings():
     run_case(programs.ring_allreduce(3), "f32", 3 * 100, "uniform", 9, cfg)                 # 25 tiles of one unit
 
 
+@pytest.mark.parametrize("slots", [3, 4, 5, 8])
+def test_sender_far_ahead_of_the_receiver(slots):
+    # One rank streams 24 messages, the other takes them one by one (and reduces half of them): the sender runs
+    # into the slot limit again and again and goes on only when the receiver announces freed slots - after every
+    # message, or after every 2nd / 4th when the plan allows that (4 or more slots).  Both kernels, both protocols,
+    # several tiles.  The last case needs every one of its slots (both ranks send 4 or 8 before they receive).
+    from paper_2201_11840_amd.ir import Program
+    n = 24
+    p = Program(f"stream_{n}", "custom", 2, n, n, inplace=False)
+    src = p.tb(0, send=1, recv=-1, chan=0)
+    dst = p.tb(1, send=-1, recv=0, chan=0)
+    for k in range(n):
+        src.add("send", src=("i", k))
+        if k % 2:
+            dst.add("rrc", src=("i", k), dst=("o", k))
+        else:
+            dst.add("recv", dst=("o", k))
+    H = _harness()
+    for wg in (64, 256):
+        cfg = H.make_config(fifo_slots=slots, tile_bytes=1024, team_width=2, min_lane_bytes=16, wg_size=wg)
+        run_case(p, "f32", n * (3 * 256 + 4), "uniform", 40 + slots, cfg)
+    if slots in (4, 8):
+        q = Program(f"exchange_{slots}", "custom", 2, slots, slots, inplace=False)
+        for r in (0, 1):
+            tb = q.tb(r, send=1 - r, recv=1 - r, chan=0)
+            for k in range(slots):
+                tb.add("send", src=("i", k))
+            for k in range(slots):
+                tb.add("recv", dst=("o", k))
+        cfg = H.make_config(fifo_slots=slots, tile_bytes=1024, team_width=2, min_lane_bytes=16, wg_size=64)
+        run_case(q, "f16", slots * (2 * 512 + 8), "normal", 50 + slots, cfg)
+
+
 def test_repeated_runs_and_changing_sizes_on_one_communicator():
     # flags and semaphores only grow: a second and third run reuse them without clearing
     H = _harness()

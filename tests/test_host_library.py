@@ -240,6 +240,24 @@ def test_plan_respects_configuration_and_limits():
     assert e.value.status == B.GC3_ERR_DEADLOCK
 
 
+def test_head_stride_follows_the_slack_in_the_slots():
+    # a receiver announces freed slots every head_stride-th message only when the program also completes with
+    # fifo_slots - head_stride + 1 slots (what a sender can then count on, Section 6.1)
+    ring = programs.ring_allreduce(4)
+    assert [plan(ring, fifo_slots=s).head_stride for s in (2, 3, 4, 7, 8)] == [1, 1, 2, 2, 4]
+
+    def both_send_first(k):
+        class P:
+            def to_text(self):
+                return two_rank([SEND] * k + [RECV] * k, [SEND] * k + [RECV] * k)
+        return P()
+    # k messages are in flight before anything is received: needs k slots
+    assert plan(both_send_first(5), fifo_slots=8).head_stride == 4      # 5 slots are enough
+    assert plan(both_send_first(6), fifo_slots=8).head_stride == 1      # would deadlock with 5
+    assert plan(both_send_first(3), fifo_slots=4).head_stride == 2
+    assert plan(both_send_first(4), fifo_slots=4).head_stride == 1
+
+
 def test_tune_rejects_bad_sizes_before_touching_a_device():
     prog = B.gc3_program_load(programs.ring_allreduce(4).to_text())
     for elems, dtype, status in [(0, B.GC3_F32, B.GC3_ERR_SIZE), (66, B.GC3_F32, B.GC3_ERR_SIZE),
