@@ -175,11 +175,13 @@ def report(w, coll, mean_ms, min_ms, wall_ms, prog, launches_before_timed=0):
            "fifo_MiB": round(coll.info.fifo_bytes / 2 ** 20, 1),
            "launch": {"grid": li.grid, "wg_size": li.wg_size, "active_lanes": li.active_lanes, "split": li.split,
                       "tile_bytes": li.tile_bytes, "fifo_scope": "die" if li.die_scope else "device",
+                      "user_scope": "die" if coll.info.user_scope == 2 else "device",
                       "kernel": KERNEL_NAMES[li.kernel]}}
     rep = coll.tune_report
     if rep is not None:
         rec["tuned"] = {"team_width": coll.cfg.team_width, "target_wgs": coll.cfg.target_wgs,
                         "tile_bytes": coll.cfg.tile_bytes, "wg_size": coll.cfg.wg_size, "fifo_scope": coll.cfg.fifo_scope,
+                        "user_scope": coll.cfg.user_scope,
                         "plans_timed": rep.count,
                         "untuned_plan_ms_in_tuner": round(rep.tried[0].ms, 5),
                         "chosen_plan_ms_in_tuner": round(rep.tried[rep.best].ms, 5)}
@@ -270,6 +272,7 @@ def main() -> int:
     ap.add_argument("--target-wgs", type=int, default=0)
     ap.add_argument("--lds-stage", type=int, default=0)
     ap.add_argument("--fifo-scope", type=int, default=0, help="1 device scope, 2 die scope (FIFO payload stays in the dies' L2s)")
+    ap.add_argument("--user-scope", type=int, default=0, help="1 device scope, 2 die scope (a rank's workgroups share a die and read its buffers through that die's L2)")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py: this build runs on ONE GPU: the ranks of a GC3-IR program are virtual ranks in one "
@@ -285,7 +288,7 @@ def main() -> int:
         return 2
     cfg = harness.make_config(fifo_slots=args.fifo_slots, tile_bytes=args.tile_bytes, team_width=args.team_width,
                               wg_size=args.wg_size, target_wgs=args.target_wgs, lds_stage=args.lds_stage,
-                              protocol=1 if args.lds_stage else 0, fifo_scope=args.fifo_scope)
+                              protocol=1 if args.lds_stage else 0, fifo_scope=args.fifo_scope, user_scope=args.user_scope)
     traffic = measured_traffic()
 
     # ---- headline workload: seeded host inputs (shared with the CPU baseline) ---------------------

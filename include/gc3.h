@@ -142,7 +142,19 @@ typedef struct gc3_comm_config {
                               that split fiber lists over idle lanes' workgroups (small chunks), use device scope.
                               Every receiver checks at run time that it shares its sender's die and abandons the
                               run with GC3_ERR_PLACEMENT otherwise */
-  int32_t reserved1;       /* must be 0 */
+  int32_t user_scope;      /* how thread blocks of one rank see each other's writes to the rank's buffers (Section 5.2:
+                              the dependencies between thread blocks of a GPU).  0 or 1 = device scope: in programs
+                              with such dependencies every access to a user buffer bypasses the dies' L2s.
+                              2 = die scope: the workgroups of rank r all run on die r mod 8 (the plan orders its
+                              workgroups so that workgroup index mod 8 = rank mod 8, padding with empty workgroups
+                              where ranks have unequal numbers of them or the rank count is no multiple of 8), so
+                              the thread blocks of a rank meet in one L2: reads are served from it (loads that
+                              bypass only the compute unit's L1, write-through stores).  A chain of dependent
+                              instructions gets shorter by a trip to memory per link (All Pairs AllReduce, 8 ranks,
+                              4 - 256 KiB: 21 - 24 -> 18 - 21 us back to back on MI355X).  Not together with
+                              fifo_scope 2 (which places lanes, not ranks, on dies).  Every workgroup checks at
+                              run time that its rank's workgroups share a die; a run where they do not ends with
+                              GC3_ERR_PLACEMENT and its results are not to be used */
 } gc3_comm_config;
 
 typedef struct gc3_comm_info {
@@ -167,7 +179,7 @@ typedef struct gc3_comm_info {
                                 - with 4 or more slots - 2 (4 with 8 slots) when the program is also free of
                                 deadlock with fifo_slots - head_stride + 1 slots, which is what a sender can then
                                 count on (Section 6.1: a sender may be up to s messages ahead) */
-  int32_t reserved;
+  int32_t user_scope;        /* 1 device, 2 die (see gc3_comm_config) */
 } gc3_comm_info;
 
 /* Message for the most recent error on this thread.  host; owned by the library; never null. */
@@ -230,6 +242,8 @@ typedef struct gc3_tune_entry {
   int32_t protocol;        /* 1 simple, 2 LL, 3 chosen per run */
   int32_t min_lane_bytes;  /* as passed to the planner (0 = chosen per run) */
   int32_t fifo_slots;      /* s of the plan */
+  int32_t user_scope;      /* 1 device, 2 die */
+  int32_t reserved;
   double ms;               /* mean duration of one run */
 } gc3_tune_entry;
 typedef struct gc3_tune_report {
@@ -248,7 +262,8 @@ typedef struct gc3_tune_report {
  * again the slot tiles, then die-scope FIFOs with 64, 128 and 256
  * threads x team widths 8..64 and their slot tiles, then - when the fastest run so far takes under 0.1 ms and `base`
  * leaves the protocol to the program - the LL protocol (Section 6.1) with workgroups of one wavefront, team widths
- * 16 and 64, lane shares of at least 4 KiB or 1 KiB and the default number of slots or 8 - only over fields `base` leaves 0 - it creates
+ * 16 and 64, lane shares of at least 4 KiB or 1 KiB and the default number of slots or 8, then - for programs with
+ * dependencies between thread blocks - the plan chosen so far with die-scope user buffers - only over fields `base` leaves 0 - it creates
  * a communicator on the current device, binds stand-in buffers of the real sizes (non-zero filler) that it
  * allocates and frees itself, times 5 runs after 2 warm-up runs (8 for the first plan) on `hip_stream` - back to back
  * when all inputs together are under 32 MiB, else each run on its own after a fill of the input buffers, so that a run

@@ -51,16 +51,16 @@ class CommConfig(C.Structure):
                 ("wg_size", C.c_int32), ("lds_stage", C.c_int32), ("target_wgs", C.c_int32),
                 ("spin_limit_us", C.c_uint64), ("debug_hold", C.c_int32), ("min_lane_bytes", C.c_int32),
                 ("protocol", C.c_int32), ("ll_max_lane_bytes", C.c_int32), ("fifo_scope", C.c_int32),
-                ("reserved1", C.c_int32)]
+                ("user_scope", C.c_int32)]
 
 
 def make_config(fifo_slots: int = 0, tile_bytes: int = 0, team_width: int = 0, wg_size: int = 0,
                 spin_limit_us: int = 0, target_wgs: int = 0, debug_hold: int = 0,
                 min_lane_bytes: int = 0, protocol: int = 0, ll_max_lane_bytes: int = 0, lds_stage: int = 0,
-                fifo_scope: int = 0) -> CommConfig:
+                fifo_scope: int = 0, user_scope: int = 0) -> CommConfig:
     """A gc3_comm_config; zero fields select the library's defaults."""
     return CommConfig(fifo_slots, tile_bytes, team_width, wg_size, lds_stage, target_wgs, spin_limit_us,
-                      debug_hold, min_lane_bytes, protocol, ll_max_lane_bytes, fifo_scope, 0)
+                      debug_hold, min_lane_bytes, protocol, ll_max_lane_bytes, fifo_scope, user_scope)
 
 
 class CommInfo(C.Structure):
@@ -69,7 +69,7 @@ class CommInfo(C.Structure):
                 ("tile_bytes", C.c_int32), ("slot_bytes", C.c_int32), ("fifo_bytes", C.c_uint64),
                 ("compute_units", C.c_int32), ("max_fibers_per_wg", C.c_int32),
                 ("wgs_per_lane", C.c_int32), ("protocol", C.c_int32), ("ll_fifo_bytes", C.c_uint64),
-                ("head_stride", C.c_int32), ("reserved", C.c_int32)]
+                ("head_stride", C.c_int32), ("user_scope", C.c_int32)]
 
 
 GC3_TUNE_MAX_TRIED = 96
@@ -92,7 +92,7 @@ class TuneEntry(C.Structure):
     _fields_ = [("team_width", C.c_int32), ("target_wgs", C.c_int32), ("grid", C.c_int32),
                 ("active_wgs", C.c_int32), ("tile_bytes", C.c_int32), ("wg_size", C.c_int32), ("fifo_scope", C.c_int32),
                 ("protocol", C.c_int32), ("min_lane_bytes", C.c_int32),
-                ("fifo_slots", C.c_int32), ("ms", C.c_double)]
+                ("fifo_slots", C.c_int32), ("user_scope", C.c_int32), ("reserved", C.c_int32), ("ms", C.c_double)]
 
 
 class TuneReport(C.Structure):

@@ -43,7 +43,9 @@ struct DWg {               // 32 bytes, one per (lane, bin) of the plan
   uint32_t fiber_begin, nfibers;     // range in the fiber table
   uint32_t instr_begin, ninstr;      // range of the bin's instructions in the instruction table
   uint32_t rank;                     // all fibers of a workgroup belong to one rank
-  uint32_t pad[3];
+  uint32_t rank_first_tb;            // global index of the rank's first thread block (its semaphore lines hold the
+                                     // words in which the rank's workgroups agree, lane by lane, on their die)
+  uint32_t pad[2];
 };
 
 struct DFiber {            // 48 bytes: one lane of one IR thread block
@@ -72,7 +74,9 @@ struct KParams {
   uint64_t* sems;          // [(tb*W + lane) * kFlagStrideWords]: word 0 the semaphore, word 1 the fiber's epoch
                            // (runs it has completed); flag values of a run lie above (epoch + 1) << 32;
                            // word 2 (die-scope FIFOs) the die the fiber runs on in this run, as run base + die + 1;
-                           // word 3 (LL protocol) LL message numbers the fiber's past runs have used up
+                           // word 3 (LL protocol) LL message numbers the fiber's past runs have used up;
+                           // word 4 (first thread block of a rank; die-scope user buffers) the die the workgroups of
+                           // this lane of the rank run on in this run, as run base + die + 1
   uint32_t* error;         // 0 = fine, else a gc3_status (negated) set by the first failing workgroup
   const uint32_t* hold;    // null, or a start word every workgroup waits for (failure-path tests)
   uint64_t chunk_bytes;
@@ -89,6 +93,8 @@ struct KParams {
   uint32_t wgs_per_lane;   // workgroups per lane of the static plan (the grid is lane-major)
   uint32_t nsplit;         // in this run the fiber list of every (lane, bin) is dealt round-robin to this many
                            // workgroups (1 = as planned); uses the workgroups of lanes that own no bytes
+  uint32_t rank_die;       // 1: the plan placed the workgroups of rank r on die r mod 8 and the run relies on it (user
+                           // buffers of dependent thread blocks meet in that die's L2): every workgroup checks it
   uint32_t bin_major;      // 0: workgroup = (sub * W_active + lane) * wgs_per_lane + bin.  1 (die-scope FIFOs, needs
                            // W_active a multiple of 8 and nsplit 1): workgroup = bin * W_active + lane, so that lane w of
                            // every thread block runs on die w mod 8 (consecutive workgroups go to consecutive dies)

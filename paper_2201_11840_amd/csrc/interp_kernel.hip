@@ -312,6 +312,20 @@ __device__ __forceinline__ uint64_t ll_run_start(uint64_t used, uint32_t msgs) {
 
 // Failure-path test facility: wait (bounded by the spin limit) for a start word that the host never sets.
 // Called by one thread; returns false when the run is abandoned.
+// Die-scope user buffers: the workgroups that run lane w of a rank's thread blocks - they wait on each other and
+// read what the others wrote of the lane's share of the rank's buffers - must share a die.  Each of them raises the
+// word of (rank, lane) to (run base + its die + 1) at its start and looks at what it found when it ends: a different
+// value of this run means two of them ran on different dies (whichever came second sees it), and the run is marked
+// as failed.  (The fibers of one lane have all completed the same runs, so they agree on the run base; other lanes
+// may have sat out runs on small buffers.)
+__device__ __forceinline__ uint64_t rank_die_enter(const KParams& p, uint32_t rank_first_tb, uint32_t lane, uint64_t run_base) {
+  uint64_t* const word = p.sems + ((uint64_t)rank_first_tb * p.W + lane) * kFlagStrideWords + 4;
+  return __hip_atomic_fetch_max(word, run_base + this_die() + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void rank_die_leave(const KParams& p, uint64_t found, uint64_t run_base) {
+  if (found > run_base && found != run_base + this_die() + 1) atomicCAS(p.error, 0u, (uint32_t)(-GC3_ERR_PLACEMENT));
+}
+
 __device__ __forceinline__ bool hold_wait(const KParams& p) {
   const uint64_t start = wall_clock64();
   while (__hip_atomic_load(p.hold, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0) {
@@ -480,6 +494,7 @@ __global__ void __launch_bounds__(512) gc3_interpreter(KParams p) {
   }
   const uint32_t W = p.W;
   const uint32_t tile = p.tile_bytes;
+  uint64_t rank_die_found = 0, rank_die_base = 0;      // (thread 0 only)
   // fiber records, the bin's instructions and the rank's buffer pointers: independent loads, one barrier
   if (tid < nf) {
     const DFiber f = p.fibers[hdr.fiber_begin + sub + tid * nsplit];
@@ -493,6 +508,10 @@ __global__ void __launch_bounds__(512) gc3_interpreter(KParams p) {
     f_head[tid] = 0;
     const uint32_t epoch = (uint32_t)load_flag(p.sems + (uint64_t)f.fid * kFlagStrideWords + 1);
     f_epoch[tid] = epoch;
+    if (p.rank_die && tid == 0) {
+      rank_die_base = (uint64_t)(epoch + 1) << 32;
+      rank_die_found = rank_die_enter(p, hdr.rank_first_tb, lane, rank_die_base);
+    }
     if (LL) f_ll[tid] = ll_run_start(load_flag(p.sems + (uint64_t)f.fid * kFlagStrideWords + 3), p.ll_msgs);
     f_from[tid] = f.recv_from_tb;
     if (DIE) store_flag(p.sems + (uint64_t)f.fid * kFlagStrideWords + 2, ((uint64_t)(epoch + 1) << 32) + this_die() + 1);
@@ -698,6 +717,7 @@ __global__ void __launch_bounds__(512) gc3_interpreter(KParams p) {
       last_progress = wall_clock64();
     }
   }
+  if (p.rank_die && tid == 0) rank_die_leave(p, rank_die_found, rank_die_base);
 }
 
 // The same interpreter for workgroups of ONE wavefront that run ONE fiber (simple protocol): tile, step and
@@ -734,6 +754,8 @@ __global__ void __launch_bounds__(64) gc3_interpreter_wave(KParams p) {
   uint64_t* const my_sem = sem_of(p, tbi, lane);
   const uint32_t epoch = uni((uint32_t)load_flag(my_sem + 1));
   const uint64_t run_base = (uint64_t)(epoch + 1) << 32;
+  uint64_t rank_die_found = 0;
+  if (p.rank_die && tid == 0) rank_die_found = rank_die_enter(p, hdr.rank_first_tb, lane, run_base);
   const uint32_t recv_from_tb = uni(f.recv_from_tb);
   const uint64_t ll_start = LL ? uni64(ll_run_start(load_flag(my_sem + 3), p.ll_msgs)) : 0;
   const uint32_t ll_base = (uint32_t)ll_start;
@@ -842,6 +864,7 @@ __global__ void __launch_bounds__(64) gc3_interpreter_wave(KParams p) {
     }
   }
   if (tid == 0) {
+    if (p.rank_die) rank_die_leave(p, rank_die_found, run_base);
     store_flag(my_sem + 1, (uint64_t)epoch + 1);   // this fiber has completed one more run
     if (LL) store_flag(my_sem + 3, ll_start + p.ll_msgs);
   }

@@ -37,7 +37,9 @@ int resolve_config(const gc3_comm_config* cfg_in, gc3_comm_config& cfg, std::str
   if (cfg.debug_hold < 0 || cfg.debug_hold > 1) { msg = "debug_hold must be 0 or 1"; return GC3_ERR_ARG; }
   if (cfg.protocol < 0 || cfg.protocol > 3) { msg = "protocol must be 0..3"; return GC3_ERR_ARG; }
   if (cfg.fifo_scope < 0 || cfg.fifo_scope > 2) { msg = "fifo_scope must be 0, 1 or 2"; return GC3_ERR_ARG; }
-  if (cfg.reserved1 != 0) { msg = "reserved1 must be 0"; return GC3_ERR_ARG; }
+  if (cfg.user_scope == 0) cfg.user_scope = 1;
+  if (cfg.user_scope != 1 && cfg.user_scope != 2) { msg = "user_scope must be 0, 1 (device) or 2 (die)"; return GC3_ERR_ARG; }
+  if (cfg.user_scope == 2 && cfg.fifo_scope == 2) { msg = "die-scope FIFOs place lanes on dies, die-scope user buffers place ranks: choose one"; return GC3_ERR_ARG; }
   if (cfg.fifo_scope == 2 && (cfg.lds_stage || cfg.protocol > 1)) {
     msg = "die-scope FIFOs run the simple protocol through registers (protocol 0 or 1, lds_stage 0)";
     return GC3_ERR_ARG;
@@ -233,7 +235,25 @@ int make_plan(const gc3_program& prog, const gc3_comm_config& cfg, int cus, long
     long wgs = pack(W, round_up, &bins, nullptr);
     if (wgs < 0) { msg = "a workgroup would have to multiplex too many thread blocks"; return GC3_ERR_RESIDENCY; }
   }
-  const long active = (long)bins.size() * W;
+  if (cfg.user_scope == 2) {
+    // Die-scope user buffers: bin index = row * (rank count rounded up to a multiple of 8) + rank, with empty bins
+    // where a rank has fewer than the others.  The grid is lane-major with this many bins per lane, so workgroup
+    // index mod 8 = rank mod 8 whatever the number of active lanes, and consecutive workgroups go to consecutive
+    // dies: all workgroups of a rank run on one die.
+    const int width = (R + 7) / 8 * 8;
+    std::vector<std::vector<std::vector<int>>> of_rank(R);
+    for (auto& b : bins) of_rank[tbs[b.front()].rank].push_back(b);
+    size_t rows = 0;
+    for (auto& v : of_rank) rows = std::max(rows, v.size());
+    std::vector<std::vector<int>> placed;
+    for (size_t i = 0; i < rows; ++i)
+      for (int r = 0; r < width; ++r)
+        placed.push_back(r < R && i < of_rank[r].size() ? of_rank[r][i] : std::vector<int>());
+    bins.swap(placed);
+  }
+  long nonempty = 0;
+  for (auto& b : bins) nonempty += b.empty() ? 0 : 1;
+  const long active = nonempty * W;   // (empty workgroups leave at once and hold no place)
   if (active > resident) {
     msg = "program needs " + std::to_string(active) + " resident workgroups of " + std::to_string(cfg.wg_size) +
           " threads, the device holds " + std::to_string(resident);
@@ -284,6 +304,7 @@ int make_plan(const gc3_program& prog, const gc3_comm_config& cfg, int cus, long
         fibers.push_back(f);
         h.ninstr += tbs[g].ninstr;
         h.rank = tbs[g].rank;
+        h.rank_first_tb = (uint32_t)tb_base[tbs[g].rank];
       }
       wgs.push_back(h);
       max_fibers = std::max(max_fibers, (int)bins[b].size());
@@ -350,6 +371,7 @@ int make_plan(const gc3_program& prog, const gc3_comm_config& cfg, int cus, long
   plan.info.protocol = protocol;
   plan.info.ll_fifo_bytes = ll_fifo_bytes;
   plan.info.head_stride = head_stride;
+  plan.info.user_scope = cfg.user_scope;
   return GC3_OK;
 }
 

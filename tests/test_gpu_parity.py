@@ -213,6 +213,8 @@ def test_random_launch_configurations(seed):
                         team_width=int(rng.choice([1, 2, 3, 5, 8, 13, 32])), wg_size=int(rng.choice([64, 128, 256, 512])),
                         target_wgs=int(rng.choice([0, 16, 100, 512])), min_lane_bytes=int(rng.choice([16, 256, 4096, 8192])),
                         fifo_scope=int(rng.choice([0, 2])))
+    if cfg.fifo_scope != 2:
+        cfg.user_scope = int(rng.choice([0, 2]))
     unit = 16 // inputs.ITEMSIZE[dtype]
     chunk_elems = int(rng.choice([1, 3, 17, 250, 1031, 4100])) * unit          # 16 B .. 64 KiB per chunk
     exact = prog.collective != "allreduce"
@@ -329,19 +331,23 @@ def test_repeated_runs_and_changing_sizes_on_one_communicator():
     prog = programs.hierarchical_allreduce(2, 3)
     text = prog.to_text()
     p = oracle.parse_program(text)
-    coll = H.Collective(text, "f32", 6 * 12000, small_cfg())
-    for elems in (6 * 4000, 6 * 40, 6 * 12000, 6 * 4):
-        coll.resize(elems)
-        ins = inputs.make_inputs(6, elems, "f32", "uniform", elems)
-        want = [a.copy() for a in ins]
-        oracle.run_program(p, want, None, "f32", slots=2)
-        for _ in range(3):
-            coll.upload(ins)
-            coll.run()
-            coll.status()
-            for g, w in zip(coll.download(), want):
-                assert g.tobytes() == w.tobytes()
-    coll.close()
+    # (the second and third configuration use 3, 1, 8, 1, 8 of their 8 lanes in turn: lanes that sat out runs have
+    # completed fewer of them than the others, under die-scope user buffers and die-scope FIFOs as well)
+    for cfg in (small_cfg(), H.make_config(user_scope=2, team_width=8, min_lane_bytes=4096, tile_bytes=2048),
+                H.make_config(fifo_scope=2, team_width=8, min_lane_bytes=4096, tile_bytes=2048)):
+        coll = H.Collective(text, "f32", 6 * 12000, cfg)
+        for elems in (6 * 4000, 6 * 40, 6 * 12000, 6 * 4, 6 * 12000):
+            coll.resize(elems)
+            ins = inputs.make_inputs(6, elems, "f32", "uniform", elems)
+            want = [a.copy() for a in ins]
+            oracle.run_program(p, want, None, "f32", slots=2)
+            for _ in range(3):
+                coll.upload(ins)
+                coll.run()
+                coll.status()
+                for g, w in zip(coll.download(), want):
+                    assert g.tobytes() == w.tobytes()
+        coll.close()
     run_case(prog, "f32", 6 * 4000, "uniform", 77, small_cfg(), repeats=4)
 
 
@@ -842,6 +848,34 @@ def test_die_scope_fifos(dtype):
     # multiple of 8: such a run uses device-scope FIFOs on the same communicator
     run_case(programs.hierarchical_allreduce(2, 3), dtype, 6 * 1024 * m, "normal", 1603, die(team_width=8), expect_die=False)
     run_case(programs.ring_allreduce(4), dtype, 4 * 40000 * m, "normal", 1604, die(team_width=12, min_lane_bytes=1024), expect_die=False)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
+def test_die_scope_user_buffers(dtype):
+    """The workgroups of a rank on one die, the rank's buffers read through that die's L2 by thread blocks that wait
+    on each other: correct only if the planner's placement holds, which every workgroup verifies (a violation fails
+    status() with GC3_ERR_PLACEMENT).  Programs with chains of dependent thread blocks, rank counts that need
+    padding, thread blocks sharing workgroups, both protocols, single and many tiles, idle lanes' workgroups in use."""
+    H = _harness()
+    m = 4 // inputs.ITEMSIZE[dtype]
+    die = lambda **kw: H.make_config(user_scope=2, **kw)
+    cases = [(programs.allpairs_allreduce(8), 8 * 1024 * m, die(wg_size=64)),
+             (programs.allpairs_allreduce(8), 8 * 40000 * m, die(wg_size=64, team_width=16, tile_bytes=4096, min_lane_bytes=1024)),
+             (programs.allpairs_allreduce(8, via_scratch=True), 8 * 30000 * m, die(team_width=8, tile_bytes=1024, min_lane_bytes=256)),
+             (programs.allpairs_allreduce(5), 5 * 9000 * m, die(wg_size=64, team_width=3, tile_bytes=2048, min_lane_bytes=64)),
+             (programs.hierarchical_allreduce(2, 8), 16 * 65536 * m, die()),
+             (programs.hierarchical_allreduce(2, 3), 6 * 20000 * m, die(team_width=2, target_wgs=16, tile_bytes=4096)),
+             (programs.hierarchical_allreduce(3, 2, fuse=False), 6 * 5000 * m, die(wg_size=64, team_width=8, min_lane_bytes=4096)),
+             (programs.hierarchical_allreduce(3, 8), 24 * 8192 * m, die(wg_size=128))]
+    for prog, elems, cfg in cases:
+        run_case(prog, dtype, elems, "normal", 1700, cfg, repeats=3)
+    run_case(programs.twostep_alltoall(2, 4), dtype, 8 * 20000 * m, "normal", 1701, die(team_width=4, tile_bytes=2048), repeats=2, exact_only=True)
+    run_case(programs.allpairs_allreduce(8), dtype, 8 * 4096 * m, "special", 1702, die(wg_size=64), compare=compare_special)
+    from tests.test_compiler import _random_program
+    from paper_2201_11840_amd.compiler import compile_program
+    for seed in range(4):
+        ir = compile_program(_random_program(300 + seed, 3 + seed, 3, 16, use_channels=False))
+        run_case(ir, dtype, ir.in_chunks * 1000 * m, "normal", 1710 + seed, die(fifo_slots=8, tile_bytes=1024, team_width=2, min_lane_bytes=16), repeats=2)
 
 
 def test_config3_and_config4_with_die_scope_fifos():

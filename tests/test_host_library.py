@@ -258,6 +258,26 @@ def test_head_stride_follows_the_slack_in_the_slots():
     assert plan(both_send_first(4), fifo_slots=4).head_stride == 1
 
 
+def test_die_scope_user_buffers_place_the_ranks_on_dies():
+    # user_scope 2: the bins of a lane are ordered row by row over the ranks (rounded up to a multiple of 8, empty
+    # bins as padding), so that workgroup index mod 8 = rank mod 8 in the lane-major grid
+    for prog, kw in [(programs.allpairs_allreduce(8), dict(wg_size=64, team_width=4)),
+                     (programs.hierarchical_allreduce(2, 3), dict(team_width=2)),
+                     (programs.hierarchical_allreduce(3, 8), dict()),
+                     (programs.twostep_alltoall(2, 3), dict(wg_size=64, team_width=1, target_wgs=4096))]:
+        dev, die = plan(prog, **kw), plan(prog, user_scope=2, **kw)
+        assert (dev.user_scope, die.user_scope) == (1, 2)
+        assert die.wgs_per_lane % 8 == 0 and die.wgs_per_lane >= dev.wgs_per_lane
+        assert die.grid == die.wgs_per_lane * die.team_width
+        assert die.team_width == dev.team_width and die.active_wgs == dev.active_wgs     # the same bins, placed
+    # 8 ranks x 7 thread blocks with workgroups of their own: 7 rows of 8, nothing to pad
+    assert plan(programs.allpairs_allreduce(8), user_scope=2, wg_size=64, team_width=4).wgs_per_lane == 56
+    for kw in (dict(user_scope=3), dict(user_scope=2, fifo_scope=2)):
+        with pytest.raises(B.Gc3Error) as e:
+            plan(programs.ring_allreduce(4), **kw)
+        assert e.value.status == B.GC3_ERR_ARG
+
+
 def test_tune_rejects_bad_sizes_before_touching_a_device():
     prog = B.gc3_program_load(programs.ring_allreduce(4).to_text())
     for elems, dtype, status in [(0, B.GC3_F32, B.GC3_ERR_SIZE), (66, B.GC3_F32, B.GC3_ERR_SIZE),
