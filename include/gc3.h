@@ -149,9 +149,9 @@ typedef struct gc3_comm_config {
                               workgroups so that workgroup index mod 8 = rank mod 8, padding with empty workgroups
                               where ranks have unequal numbers of them or the rank count is no multiple of 8), so
                               the thread blocks of a rank meet in one L2: reads are served from it (loads that
-                              bypass only the compute unit's L1, write-through stores).  A chain of dependent
+                              bypass only the compute unit's L1, plain stores).  A chain of dependent
                               instructions gets shorter by a trip to memory per link (All Pairs AllReduce, 8 ranks,
-                              4 - 256 KiB: 21 - 24 -> 18 - 21 us back to back on MI355X).  Not together with
+                              4 - 256 KiB: 21 - 24 -> 17 - 19 us back to back on MI355X).  Not together with
                               fifo_scope 2 (which places lanes, not ranks, on dies).  Every workgroup checks at
                               run time that its rank's workgroups share a die; a run where they do not ends with
                               GC3_ERR_PLACEMENT and its results are not to be used */
@@ -263,7 +263,8 @@ typedef struct gc3_tune_report {
  * threads x team widths 8..64 and their slot tiles, then - when the fastest run so far takes under 0.1 ms and `base`
  * leaves the protocol to the program - the LL protocol (Section 6.1) with workgroups of one wavefront, team widths
  * 16 and 64, lane shares of at least 4 KiB or 1 KiB and the default number of slots or 8, then - for programs with
- * dependencies between thread blocks - the plan chosen so far with die-scope user buffers - only over fields `base` leaves 0 - it creates
+ * dependencies between thread blocks - die-scope user buffers for the plan chosen so far, for 64 and 128 lanes of
+ * 128-thread workgroups and for 16 and 64 lanes of one-wavefront workgroups - only over fields `base` leaves 0 - it creates
  * a communicator on the current device, binds stand-in buffers of the real sizes (non-zero filler) that it
  * allocates and frees itself, times 5 runs after 2 warm-up runs (8 for the first plan) on `hip_stream` - back to back
  * when all inputs together are under 32 MiB, else each run on its own after a fill of the input buffers, so that a run

@@ -19,7 +19,7 @@
 #include "residency.h"
 
 namespace gc3 {
-int launch_interpreter(int dtype, bool coherent_user, int mode, bool die_scope, unsigned grid, unsigned block, void* stream,
+int launch_interpreter(int dtype, int coherent_user, int mode, bool die_scope, unsigned grid, unsigned block, void* stream,
                        const KParams& p);
 int interpreter_occupancy(unsigned block, int kind, int* out);
 int static_scratch_ptr(void** out);
@@ -493,9 +493,9 @@ int gc3_comm_run(gc3_comm* comm, size_t elems_per_rank, gc3_dtype dtype, gc3_red
     rc = ledger_make_room(comm, comm->device, st, (int32_t)L.grid, comm->info.max_resident_wgs);
     if (rc != GC3_OK) return rc;
   }
-  // die-scope user buffers: the thread blocks of a rank meet in one L2, so the accesses need not bypass it
+  // die-scope user buffers: the thread blocks of a rank meet in one L2, so their accesses need not bypass it
   p.rank_die = comm->rank_die ? 1u : 0u;
-  int e = launch_interpreter((int)dtype, comm->has_deps && !comm->rank_die, L.mode, L.die, L.grid, L.block, hip_stream, p);
+  int e = launch_interpreter((int)dtype, comm->rank_die ? 2 : comm->has_deps ? 1 : 0, L.mode, L.die, L.grid, L.block, hip_stream, p);
   if (e != 0) return hip_fail((hipError_t)e, "interpreter launch");
   if (!capturing) {
     ledger_enter(comm, comm->device, st, (int32_t)L.grid, comm->info.max_resident_wgs);
@@ -827,7 +827,7 @@ int gc3_comm_tune(const gc3_program* prog, const gc3_comm_config* base, size_t e
   }
   // pass 7: die-scope user buffers - the workgroups of a rank on one die, its buffers read through that die's L2 -
   // for programs whose thread blocks wait on each other: the plan chosen so far, placed that way.  It shortens chains
-  // of dependent instructions (All Pairs AllReduce on 8 ranks up to 256 KiB: 21-24 -> 18-21 us back to back on
+  // of dependent instructions (All Pairs AllReduce on 8 ranks up to 256 KiB: 21-24 -> 17-19 us back to back on
   // MI355X) and loses where it leaves dies idle (rank counts that are no multiple of 8).
   bool has_deps = false;
   for (const auto& rk : prog->rank)
@@ -839,6 +839,32 @@ int gc3_comm_tune(const gc3_program* prog, const gc3_comm_config* base, size_t e
     gc3_comm_config cfg = *best;
     cfg.user_scope = 2;
     if ((rc = try_config(cfg)) != GC3_OK) return rc;
+    // and the shapes that suit such programs, whichever of them won above: as many 128-thread workgroups as the
+    // device holds, and workgroups of one wavefront (All Pairs AllReduce at 64 MiB: the 128-thread plan gains 6 %
+    // from this placement, the one-wavefront plan loses 4 %, and without it the two are within noise of each other)
+    if (cfg0.wg_size == 0 && cfg0.target_wgs == 0) {
+      for (int w : {64, 128}) {
+        if (cfg0.team_width && cfg0.team_width != w) continue;
+        gc3_comm_config wide = cfg0;
+        wide.wg_size = 128;
+        wide.team_width = w;
+        wide.target_wgs = 3584;
+        wide.user_scope = 2;
+        if (cfg0.tile_bytes == 0) wide.tile_bytes = 16384;
+        if ((rc = try_config(wide)) != GC3_OK) return rc;
+      }
+      seen.clear();
+      seen.emplace_back(-1, -1, -1);
+      for (int w : {16, 64}) {
+        if (cfg0.team_width && cfg0.team_width != w) continue;
+        gc3_comm_config one = cfg0;
+        one.wg_size = 64;
+        one.team_width = w;
+        one.target_wgs = 4096;
+        one.user_scope = 2;
+        if ((rc = try_config(one)) != GC3_OK) return rc;
+      }
+    }
   }
   if (!have) {
     set_error("no configuration could be timed: " + last_msg);
@@ -1008,7 +1034,7 @@ extern "C" int gc3_run_static(const gc3_program* prog, const gc3_comm_config* cf
             cfg.fifo_scope == 2, L);
   // (epochs were cleared with the flags: every call is the first run)
   p.rank_die = cfg.user_scope == 2 ? 1u : 0u;
-  e = launch_interpreter((int)dtype, !plan.deps.empty() && cfg.user_scope != 2, L.mode, L.die, L.grid, L.block, hip_stream, p);
+  e = launch_interpreter((int)dtype, cfg.user_scope == 2 ? 2 : plan.deps.empty() ? 0 : 1, L.mode, L.die, L.grid, L.block, hip_stream, p);
   if (e != 0) return hip_fail((hipError_t)e, "interpreter launch");
   return GC3_OK;
 }

@@ -94,6 +94,12 @@ constexpr int kPolNt = 2, kPolSc1 = 16;   // (bit 0 would be sc0)
 constexpr int kSlotLd = kPolSc1, kSlotSt = kPolSc1;
 constexpr int kUserLd = kPolNt, kUserSt = kPolSc1;
 constexpr int kUserLdCoh = kPolSc1 | kPolNt, kUserStCoh = kPolSc1 | kPolNt;
+// How a program's thread blocks see each other's writes to their rank's buffers (template parameter COH):
+// kCohNone - they never read them (no cross-thread-block dependencies); kCohDevice - through the memory system;
+// kCohDie - through the L2 of the die that all workgroups of the rank run on (loads that bypass only the compute
+// unit's L1, plain stores: complete, for a reader on the same die, when the store counter retires).
+constexpr int kCohNone = 0, kCohDevice = 1, kCohDie = 2;
+constexpr int kUserStDie = 0;
 constexpr int kUnroll = 4;                // 128-bit loads per stream in flight before the adds and stores
 constexpr uint32_t kStageBytes = 16384;   // LDS staging area per workgroup (staged variant only): one sweep of 256 threads
 
@@ -394,11 +400,11 @@ __device__ __forceinline__ int poll_flags(const KParams& p, uint32_t lane_id, bo
 
 // One tile of one instruction under the simple protocol: `count` pieces of `len` bytes, piece j at
 // srcb / dstb + j * chunk_bytes in the user buffers and packed back to back in the FIFO slots.
-template <int DT, bool COH, bool STAGE, bool DIE>
+template <int DT, int COH, bool STAGE, bool DIE>
 __device__ __forceinline__ void move_simple(uint32_t op, uint32_t count, unsigned char* srcb, unsigned char* dstb,
                                             unsigned char* rslot, unsigned char* sslot, uint32_t len,
                                             uint64_t chunk_bytes, uint32_t tid, uint32_t nthreads, unsigned char* stage) {
-  constexpr int UL = COH ? kUserLdCoh : kUserLd, US = COH ? kUserStCoh : kUserSt;
+  constexpr int UL = COH == kCohDevice ? kUserLdCoh : kUserLd, US = COH == kCohDevice ? kUserStCoh : COH == kCohDie ? kUserStDie : kUserSt;
   constexpr int SL = DIE ? kDieSlotLd : kSlotLd, SS = DIE ? kDieSlotSt : kSlotSt;
   const uint32_t nvec = len >> 4;
   for (uint32_t j = 0; j < count; ++j) {
@@ -449,7 +455,7 @@ __device__ __forceinline__ bool op_pushes(uint32_t op) {
 // unfinished a wait is a single poll (a fiber that is not ready yields to the next one, so thread
 // blocks sharing a workgroup can never block each other), and the last unfinished fiber waits by
 // spinning.  One fiber per workgroup is the paper's one-thread-block-per-block execution.
-template <int DT, bool COH, int MODE>
+template <int DT, int COH, int MODE>
 __global__ void __launch_bounds__(512) gc3_interpreter(KParams p) {
   constexpr bool LL = MODE == kLL;
   constexpr bool STAGE = MODE == kStaged;
@@ -631,7 +637,7 @@ __global__ void __launch_bounds__(512) gc3_interpreter(KParams p) {
         unsigned char* const sslot = pushes ? fifo_send + (uint64_t)(send_seq % p.slots) * sslot_bytes : nullptr;
         bool data_ok = true;
         if (LL && (pops || pushes)) {
-          constexpr int UL = COH ? kUserLdCoh : kUserLd, US = COH ? kUserStCoh : kUserSt;
+          constexpr int UL = COH == kCohDevice ? kUserLdCoh : kUserLd, US = COH == kCohDevice ? kUserStCoh : COH == kCohDie ? kUserStDie : kUserSt;
           for (uint32_t j = 0; j < ins.count; ++j) {
             const rsrc_t src = make_rsrc(srcb + (uint64_t)j * p.chunk_bytes, srcb ? len : 0);
             const rsrc_t dst = make_rsrc(dstb + (uint64_t)j * p.chunk_bytes, dstb ? len : 0);
@@ -731,7 +737,7 @@ __global__ void __launch_bounds__(512) gc3_interpreter(KParams p) {
 // load that finds it (the receiver's loads have completed when it has seen the flags, so the head flag needs no
 // wait either).
 constexpr int kWaveLdsInstrs = 64;
-template <int DT, bool COH, int WM>
+template <int DT, int COH, int WM>
 __global__ void __launch_bounds__(64) gc3_interpreter_wave(KParams p) {
   constexpr bool DIE = WM == kDie, LL = WM == kLL;
   __shared__ uint32_t s_instr[kWaveLdsInstrs * 8];
@@ -826,7 +832,7 @@ __global__ void __launch_bounds__(64) gc3_interpreter_wave(KParams p) {
       unsigned char* const rslot = pops ? fifo_recv + (uint64_t)(recv_seq % p.slots) * rslot_bytes : nullptr;
       unsigned char* const sslot = pushes ? fifo_send + (uint64_t)(send_seq % p.slots) * sslot_bytes : nullptr;
       if (LL && (pops || pushes)) {
-        constexpr int UL = COH ? kUserLdCoh : kUserLd, US = COH ? kUserStCoh : kUserSt;
+        constexpr int UL = COH == kCohDevice ? kUserLdCoh : kUserLd, US = COH == kCohDevice ? kUserStCoh : COH == kCohDie ? kUserStDie : kUserSt;
         const uint32_t ll_fin = ll_base + recv_seq + 1, ll_fout = ll_base + send_seq + 1, nvec = len >> 4;
         bool data_ok = true;
         for (uint32_t j = 0; j < ins.count; ++j) {
@@ -870,41 +876,48 @@ __global__ void __launch_bounds__(64) gc3_interpreter_wave(KParams p) {
   }
 }
 
-// Host-callable launcher; returns the hipError_t of the launch.  `coherent_user` selects the
-// instantiation for programs with cross-thread-block dependencies; `mode`: 0 simple, 1 LL, 2 simple with the
+// Host-callable launcher; returns the hipError_t of the launch.  `coherent_user`: 0 for programs without
+// cross-thread-block dependencies, 1 with (user buffers at device scope), 2 with die-scope user buffers; `mode`: 0 simple, 1 LL, 2 simple with the
 // FIFO payload staged through LDS, 3 the one-wavefront one-fiber interpreter (block must be 64), 4 the same under
 // the LL protocol; `die_scope` (modes 0 and 3): FIFO payload kept in the L2 of the die both ends of a connection
 // run on.
 template <int DT>
-static int launch_dt(bool coh, int mode, bool die, unsigned grid, unsigned block, hipStream_t st, const KParams& p) {
+static int launch_dt(int coh, int mode, bool die, unsigned grid, unsigned block, hipStream_t st, const KParams& p) {
 #define GC3_LAUNCH(K) hipLaunchKernelGGL((K), dim3(grid), dim3(block), 0, st, p)
   if (die && mode != 0 && mode != 3) return (int)hipErrorInvalidValue;
   int variant = mode;                       // 0..3 as above, 4 die-scope general, 5 die-scope wavefront, 6 LL wavefront
   if (die) variant = mode == 3 ? 5 : 4;
   else if (mode == 4) variant = 6;
-  switch (variant * 2 + (coh ? 1 : 0)) {
-    case 0: GC3_LAUNCH((gc3_interpreter<DT, false, kSimple>)); break;
-    case 1: GC3_LAUNCH((gc3_interpreter<DT, true, kSimple>)); break;
-    case 2: GC3_LAUNCH((gc3_interpreter<DT, false, kLL>)); break;
-    case 3: GC3_LAUNCH((gc3_interpreter<DT, true, kLL>)); break;
-    case 4: GC3_LAUNCH((gc3_interpreter<DT, false, kStaged>)); break;
-    case 5: GC3_LAUNCH((gc3_interpreter<DT, true, kStaged>)); break;
-    case 6: GC3_LAUNCH((gc3_interpreter_wave<DT, false, kSimple>)); break;
-    case 7: GC3_LAUNCH((gc3_interpreter_wave<DT, true, kSimple>)); break;
-    case 8: GC3_LAUNCH((gc3_interpreter<DT, false, kDie>)); break;
-    case 9: GC3_LAUNCH((gc3_interpreter<DT, true, kDie>)); break;
-    case 10: GC3_LAUNCH((gc3_interpreter_wave<DT, false, kDie>)); break;
-    case 11: GC3_LAUNCH((gc3_interpreter_wave<DT, true, kDie>)); break;
-    case 12: GC3_LAUNCH((gc3_interpreter_wave<DT, false, kLL>)); break;
-    case 13: GC3_LAUNCH((gc3_interpreter_wave<DT, true, kLL>)); break;
+  if (coh == kCohDie && (variant == 4 || variant == 5)) return (int)hipErrorInvalidValue;   // lanes or ranks on dies, not both
+  switch (variant * 3 + coh) {
+    case 0: GC3_LAUNCH((gc3_interpreter<DT, kCohNone, kSimple>)); break;
+    case 1: GC3_LAUNCH((gc3_interpreter<DT, kCohDevice, kSimple>)); break;
+    case 2: GC3_LAUNCH((gc3_interpreter<DT, kCohDie, kSimple>)); break;
+    case 3: GC3_LAUNCH((gc3_interpreter<DT, kCohNone, kLL>)); break;
+    case 4: GC3_LAUNCH((gc3_interpreter<DT, kCohDevice, kLL>)); break;
+    case 5: GC3_LAUNCH((gc3_interpreter<DT, kCohDie, kLL>)); break;
+    case 6: GC3_LAUNCH((gc3_interpreter<DT, kCohNone, kStaged>)); break;
+    case 7: GC3_LAUNCH((gc3_interpreter<DT, kCohDevice, kStaged>)); break;
+    case 8: GC3_LAUNCH((gc3_interpreter<DT, kCohDie, kStaged>)); break;
+    case 9: GC3_LAUNCH((gc3_interpreter_wave<DT, kCohNone, kSimple>)); break;
+    case 10: GC3_LAUNCH((gc3_interpreter_wave<DT, kCohDevice, kSimple>)); break;
+    case 11: GC3_LAUNCH((gc3_interpreter_wave<DT, kCohDie, kSimple>)); break;
+    case 12: GC3_LAUNCH((gc3_interpreter<DT, kCohNone, kDie>)); break;
+    case 13: GC3_LAUNCH((gc3_interpreter<DT, kCohDevice, kDie>)); break;
+    case 15: GC3_LAUNCH((gc3_interpreter_wave<DT, kCohNone, kDie>)); break;
+    case 16: GC3_LAUNCH((gc3_interpreter_wave<DT, kCohDevice, kDie>)); break;
+    case 18: GC3_LAUNCH((gc3_interpreter_wave<DT, kCohNone, kLL>)); break;
+    case 19: GC3_LAUNCH((gc3_interpreter_wave<DT, kCohDevice, kLL>)); break;
+    case 20: GC3_LAUNCH((gc3_interpreter_wave<DT, kCohDie, kLL>)); break;
     default: return (int)hipErrorInvalidValue;
   }
 #undef GC3_LAUNCH
   return (int)hipGetLastError();
 }
 
-int launch_interpreter(int dtype, bool coherent_user, int mode, bool die_scope, unsigned grid, unsigned block, void* stream,
+int launch_interpreter(int dtype, int coherent_user, int mode, bool die_scope, unsigned grid, unsigned block, void* stream,
                        const KParams& p) {
+  if (coherent_user < kCohNone || coherent_user > kCohDie) return (int)hipErrorInvalidValue;
   hipStream_t st = (hipStream_t)stream;
   if ((mode == 3 || mode == 4) && block != 64) return (int)hipErrorInvalidValue;
   switch (dtype) {
@@ -921,33 +934,19 @@ int launch_interpreter(int dtype, bool coherent_user, int mode, bool die_scope, 
 // (and, for runs that fall back to it, device scope).
 int interpreter_occupancy(unsigned block, int kind, int* out) {
   int best = 1 << 30;
-  const void* plain[] = {
-      (const void*)gc3_interpreter<GC3_F32, false, kSimple>, (const void*)gc3_interpreter<GC3_F32, true, kSimple>,
-      (const void*)gc3_interpreter<GC3_F16, false, kSimple>, (const void*)gc3_interpreter<GC3_F16, true, kSimple>,
-      (const void*)gc3_interpreter<GC3_BF16, false, kSimple>, (const void*)gc3_interpreter<GC3_BF16, true, kSimple>,
-      (const void*)gc3_interpreter<GC3_F32, false, kLL>, (const void*)gc3_interpreter<GC3_F32, true, kLL>,
-      (const void*)gc3_interpreter<GC3_F16, false, kLL>, (const void*)gc3_interpreter<GC3_F16, true, kLL>,
-      (const void*)gc3_interpreter<GC3_BF16, false, kLL>, (const void*)gc3_interpreter<GC3_BF16, true, kLL>};
-  const void* die[] = {
-      (const void*)gc3_interpreter<GC3_F32, false, kDie>, (const void*)gc3_interpreter<GC3_F32, true, kDie>,
-      (const void*)gc3_interpreter<GC3_F16, false, kDie>, (const void*)gc3_interpreter<GC3_F16, true, kDie>,
-      (const void*)gc3_interpreter<GC3_BF16, false, kDie>, (const void*)gc3_interpreter<GC3_BF16, true, kDie>};
-  const void* with_stage[] = {
-      (const void*)gc3_interpreter<GC3_F32, false, kStaged>, (const void*)gc3_interpreter<GC3_F32, true, kStaged>,
-      (const void*)gc3_interpreter<GC3_F16, false, kStaged>, (const void*)gc3_interpreter<GC3_F16, true, kStaged>,
-      (const void*)gc3_interpreter<GC3_BF16, false, kStaged>, (const void*)gc3_interpreter<GC3_BF16, true, kStaged>};
-  const void* wave[] = {
-      (const void*)gc3_interpreter_wave<GC3_F32, false, kSimple>, (const void*)gc3_interpreter_wave<GC3_F32, true, kSimple>,
-      (const void*)gc3_interpreter_wave<GC3_F16, false, kSimple>, (const void*)gc3_interpreter_wave<GC3_F16, true, kSimple>,
-      (const void*)gc3_interpreter_wave<GC3_BF16, false, kSimple>, (const void*)gc3_interpreter_wave<GC3_BF16, true, kSimple>};
-  const void* wave_ll[] = {
-      (const void*)gc3_interpreter_wave<GC3_F32, false, kLL>, (const void*)gc3_interpreter_wave<GC3_F32, true, kLL>,
-      (const void*)gc3_interpreter_wave<GC3_F16, false, kLL>, (const void*)gc3_interpreter_wave<GC3_F16, true, kLL>,
-      (const void*)gc3_interpreter_wave<GC3_BF16, false, kLL>, (const void*)gc3_interpreter_wave<GC3_BF16, true, kLL>};
-  const void* wave_die[] = {
-      (const void*)gc3_interpreter_wave<GC3_F32, false, kDie>, (const void*)gc3_interpreter_wave<GC3_F32, true, kDie>,
-      (const void*)gc3_interpreter_wave<GC3_F16, false, kDie>, (const void*)gc3_interpreter_wave<GC3_F16, true, kDie>,
-      (const void*)gc3_interpreter_wave<GC3_BF16, false, kDie>, (const void*)gc3_interpreter_wave<GC3_BF16, true, kDie>};
+#define GC3_ALL_DT(K, C, M) (const void*)K<GC3_F32, C, M>, (const void*)K<GC3_F16, C, M>, (const void*)K<GC3_BF16, C, M>
+  const void* plain[] = {GC3_ALL_DT(gc3_interpreter, kCohNone, kSimple), GC3_ALL_DT(gc3_interpreter, kCohDevice, kSimple),
+                         GC3_ALL_DT(gc3_interpreter, kCohDie, kSimple), GC3_ALL_DT(gc3_interpreter, kCohNone, kLL),
+                         GC3_ALL_DT(gc3_interpreter, kCohDevice, kLL), GC3_ALL_DT(gc3_interpreter, kCohDie, kLL)};
+  const void* die[] = {GC3_ALL_DT(gc3_interpreter, kCohNone, kDie), GC3_ALL_DT(gc3_interpreter, kCohDevice, kDie)};
+  const void* with_stage[] = {GC3_ALL_DT(gc3_interpreter, kCohNone, kStaged), GC3_ALL_DT(gc3_interpreter, kCohDevice, kStaged),
+                              GC3_ALL_DT(gc3_interpreter, kCohDie, kStaged)};
+  const void* wave[] = {GC3_ALL_DT(gc3_interpreter_wave, kCohNone, kSimple), GC3_ALL_DT(gc3_interpreter_wave, kCohDevice, kSimple),
+                        GC3_ALL_DT(gc3_interpreter_wave, kCohDie, kSimple)};
+  const void* wave_ll[] = {GC3_ALL_DT(gc3_interpreter_wave, kCohNone, kLL), GC3_ALL_DT(gc3_interpreter_wave, kCohDevice, kLL),
+                           GC3_ALL_DT(gc3_interpreter_wave, kCohDie, kLL)};
+  const void* wave_die[] = {GC3_ALL_DT(gc3_interpreter_wave, kCohNone, kDie), GC3_ALL_DT(gc3_interpreter_wave, kCohDevice, kDie)};
+#undef GC3_ALL_DT
   auto take = [&](const void* const* fns, int n) -> int {
     for (int i = 0; i < n; ++i) {
       int occ = 0;
@@ -957,9 +956,9 @@ int interpreter_occupancy(unsigned block, int kind, int* out) {
     }
     return 0;
   };
-  int e = kind == 1 ? take(with_stage, 6) : take(plain, 12);
-  if (e == 0 && kind != 1 && block == 64) e = take(wave, 6);
-  if (e == 0 && kind != 1 && block == 64) e = take(wave_ll, 6);
+  int e = kind == 1 ? take(with_stage, 9) : take(plain, 18);
+  if (e == 0 && kind != 1 && block == 64) e = take(wave, 9);
+  if (e == 0 && kind != 1 && block == 64) e = take(wave_ll, 9);
   if (e == 0 && kind == 2) e = take(die, 6);
   if (e == 0 && kind == 2 && block == 64) e = take(wave_die, 6);
   if (e != 0) return e;

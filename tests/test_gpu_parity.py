@@ -473,7 +473,8 @@ def test_tune_measures_plans_and_the_chosen_one_is_correct():
     from paper_2201_11840_amd import binding as B
     for prog, dtype, elems in [(programs.ring_allreduce(8, instances=2), "f32", 16 * 8192),
                                (programs.hierarchical_allreduce(2, 3), "bf16", 6 * 16384),
-                               (programs.alltonext(2, 3), "f16", 3 * 8192)]:
+                               (programs.alltonext(2, 3), "f16", 3 * 8192),
+                               (programs.allpairs_allreduce(8), "f32", 8 * 8192)]:
         text = prog.to_text()
         p = oracle.parse_program(text)
         ins = inputs.make_inputs(p.ranks, elems, dtype, "normal", 77)
@@ -491,13 +492,13 @@ def test_tune_measures_plans_and_the_chosen_one_is_correct():
             assert fastest >= 0.98 * tried[0].ms
         else:
             assert tried[rep.best].ms == fastest < 0.98 * tried[0].ms
-        assert len({(t.team_width, t.grid, t.tile_bytes, t.wg_size, t.fifo_scope, t.protocol, t.min_lane_bytes, t.fifo_slots)
+        assert len({(t.team_width, t.grid, t.tile_bytes, t.wg_size, t.fifo_scope, t.protocol, t.min_lane_bytes, t.fifo_slots, t.user_scope)
                     for t in tried}) == rep.count   # no plan timed twice
         b = tried[rep.best]
         assert (coll.info.team_width, coll.info.grid, coll.info.tile_bytes, coll.info.wg_size) == \
             (b.team_width, b.grid, b.tile_bytes, b.wg_size)
         assert coll.cfg.fifo_scope == (2 if b.fifo_scope == 2 else 0)
-        assert coll.info.protocol == b.protocol
+        assert coll.info.protocol == b.protocol and coll.info.user_scope == b.user_scope
         coll.upload(ins, outs)
         coll.run()
         coll.status()

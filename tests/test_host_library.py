@@ -342,16 +342,17 @@ def test_kernel_resources_of_the_built_library():
     if not os.path.exists(path):
         pytest.skip("library was built without the resource report")
     kernels = [k for k in json.load(open(path)) if "gc3_interpreter" in k["name"]]
-    # 3 data types x dependencies or not x (simple, LL, LDS staging, die-scope FIFOs; wavefront-level at device and die scope and under LL)
-    assert len(kernels) == 42
+    # 3 data types x (no dependencies, user buffers at device scope, at die scope) x (simple, LL, LDS staging;
+    # wavefront-level simple and LL), and x (no dependencies, device scope) x die-scope FIFOs (general, wavefront-level)
+    assert len(kernels) == 3 * (3 * 5 + 2 * 2)
     for k in kernels:
         assert k["scratch_bytes"] == 0, k
         assert k["occupancy"] >= 6, k
         staged = k["lds_bytes"] > 16384               # the staging area is 16 KiB on top of the interpreter's state
         assert k["vgprs"] <= 80 and k["lds_bytes"] <= (32768 if staged else 16384), k
-    assert sum(k["lds_bytes"] > 16384 for k in kernels) == 6
+    assert sum(k["lds_bytes"] > 16384 for k in kernels) == 9
     wave = [k for k in kernels if "gc3_interpreter_wave" in k["name"]]
-    assert len(wave) == 18 and all(k["lds_bytes"] <= 2048 for k in wave)
+    assert len(wave) == 3 * (3 * 2 + 2) and all(k["lds_bytes"] <= 2048 for k in wave)
 
 
 def test_compiler_command_line_writes_loadable_programs(tmp_path):
