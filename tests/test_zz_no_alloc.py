@@ -81,6 +81,9 @@ def test_static_entry_point_matches_the_communicator_path():
     _check(programs.alltonext(2, 3), "f16", 3 * 4096, 4)
     _check(programs.allpairs_allreduce(4, via_scratch=True), "f32", 4 * 2500, 5, H.make_config(tile_bytes=1024, team_width=3, min_lane_bytes=16))
     _check(ring, "f32", 16 * 4, 6)                  # smallest chunk: one 16-byte unit
+    # die-scope user buffers: the placement word is cleared with the flags before every call
+    _check(programs.allpairs_allreduce(8), "f32", 8 * 3000, 8, H.make_config(user_scope=2, wg_size=64, team_width=2, tile_bytes=2048, min_lane_bytes=256))
+    _check(programs.hierarchical_allreduce(2, 3), "bf16", 6 * 20000, 9, H.make_config(user_scope=2))
     # 8 slots: freed slots are announced after every 4th message only; many small tiles per lane
     _check(ring, "f32", 16 * 20000, 7, H.make_config(fifo_slots=8, tile_bytes=2048, team_width=4, min_lane_bytes=16))
 
