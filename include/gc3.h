@@ -151,8 +151,10 @@ typedef struct gc3_comm_config {
                               the thread blocks of a rank meet in one L2: reads are served from it (loads that
                               bypass only the compute unit's L1, plain stores).  A chain of dependent
                               instructions gets shorter by a trip to memory per link (All Pairs AllReduce, 8 ranks,
-                              4 - 256 KiB: 21 - 24 -> 17 - 19 us back to back on MI355X).  Not together with
-                              fifo_scope 2 (which places lanes, not ranks, on dies).  Every workgroup checks at
+                              4 - 256 KiB: 21 - 24 -> 17 - 19 us back to back on MI355X).  Together with
+                              fifo_scope 2 the lanes are placed on dies instead (lane w of every thread block of
+                              every rank on die w mod 8, which serves both), in the runs that use die-scope FIFOs;
+                              the others use device scope for both.  Every workgroup checks at
                               run time that its rank's workgroups share a die; a run where they do not ends with
                               GC3_ERR_PLACEMENT and its results are not to be used */
 } gc3_comm_config;

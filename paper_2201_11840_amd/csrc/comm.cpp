@@ -494,8 +494,11 @@ int gc3_comm_run(gc3_comm* comm, size_t elems_per_rank, gc3_dtype dtype, gc3_red
     if (rc != GC3_OK) return rc;
   }
   // die-scope user buffers: the thread blocks of a rank meet in one L2, so their accesses need not bypass it
-  p.rank_die = comm->rank_die ? 1u : 0u;
-  int e = launch_interpreter((int)dtype, comm->rank_die ? 2 : comm->has_deps ? 1 : 0, L.mode, L.die, L.grid, L.block, hip_stream, p);
+  // (with die-scope FIFOs the placement is by lanes and holds in the runs that use it; the others fall back to
+  // device scope for both)
+  const bool user_die = comm->rank_die && (!comm->die_scope || L.die);
+  p.rank_die = user_die ? 1u : 0u;
+  int e = launch_interpreter((int)dtype, user_die ? 2 : comm->has_deps ? 1 : 0, L.mode, L.die, L.grid, L.block, hip_stream, p);
   if (e != 0) return hip_fail((hipError_t)e, "interpreter launch");
   if (!capturing) {
     ledger_enter(comm, comm->device, st, (int32_t)L.grid, comm->info.max_resident_wgs);
@@ -1033,8 +1036,9 @@ extern "C" int gc3_run_static(const gc3_program* prog, const gc3_comm_config* cf
   shape_run(plan.info, cb, (uint64_t)cfg.min_lane_bytes, (uint64_t)cfg.ll_max_lane_bytes, cfg.lds_stage != 0,
             cfg.fifo_scope == 2, L);
   // (epochs were cleared with the flags: every call is the first run)
-  p.rank_die = cfg.user_scope == 2 ? 1u : 0u;
-  e = launch_interpreter((int)dtype, cfg.user_scope == 2 ? 2 : plan.deps.empty() ? 0 : 1, L.mode, L.die, L.grid, L.block, hip_stream, p);
+  const bool user_die = cfg.user_scope == 2 && (cfg.fifo_scope != 2 || L.die);
+  p.rank_die = user_die ? 1u : 0u;
+  e = launch_interpreter((int)dtype, user_die ? 2 : plan.deps.empty() ? 0 : 1, L.mode, L.die, L.grid, L.block, hip_stream, p);
   if (e != 0) return hip_fail((hipError_t)e, "interpreter launch");
   return GC3_OK;
 }

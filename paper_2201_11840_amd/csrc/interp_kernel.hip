@@ -888,7 +888,6 @@ static int launch_dt(int coh, int mode, bool die, unsigned grid, unsigned block,
   int variant = mode;                       // 0..3 as above, 4 die-scope general, 5 die-scope wavefront, 6 LL wavefront
   if (die) variant = mode == 3 ? 5 : 4;
   else if (mode == 4) variant = 6;
-  if (coh == kCohDie && (variant == 4 || variant == 5)) return (int)hipErrorInvalidValue;   // lanes or ranks on dies, not both
   switch (variant * 3 + coh) {
     case 0: GC3_LAUNCH((gc3_interpreter<DT, kCohNone, kSimple>)); break;
     case 1: GC3_LAUNCH((gc3_interpreter<DT, kCohDevice, kSimple>)); break;
@@ -904,8 +903,10 @@ static int launch_dt(int coh, int mode, bool die, unsigned grid, unsigned block,
     case 11: GC3_LAUNCH((gc3_interpreter_wave<DT, kCohDie, kSimple>)); break;
     case 12: GC3_LAUNCH((gc3_interpreter<DT, kCohNone, kDie>)); break;
     case 13: GC3_LAUNCH((gc3_interpreter<DT, kCohDevice, kDie>)); break;
+    case 14: GC3_LAUNCH((gc3_interpreter<DT, kCohDie, kDie>)); break;
     case 15: GC3_LAUNCH((gc3_interpreter_wave<DT, kCohNone, kDie>)); break;
     case 16: GC3_LAUNCH((gc3_interpreter_wave<DT, kCohDevice, kDie>)); break;
+    case 17: GC3_LAUNCH((gc3_interpreter_wave<DT, kCohDie, kDie>)); break;
     case 18: GC3_LAUNCH((gc3_interpreter_wave<DT, kCohNone, kLL>)); break;
     case 19: GC3_LAUNCH((gc3_interpreter_wave<DT, kCohDevice, kLL>)); break;
     case 20: GC3_LAUNCH((gc3_interpreter_wave<DT, kCohDie, kLL>)); break;
@@ -938,14 +939,16 @@ int interpreter_occupancy(unsigned block, int kind, int* out) {
   const void* plain[] = {GC3_ALL_DT(gc3_interpreter, kCohNone, kSimple), GC3_ALL_DT(gc3_interpreter, kCohDevice, kSimple),
                          GC3_ALL_DT(gc3_interpreter, kCohDie, kSimple), GC3_ALL_DT(gc3_interpreter, kCohNone, kLL),
                          GC3_ALL_DT(gc3_interpreter, kCohDevice, kLL), GC3_ALL_DT(gc3_interpreter, kCohDie, kLL)};
-  const void* die[] = {GC3_ALL_DT(gc3_interpreter, kCohNone, kDie), GC3_ALL_DT(gc3_interpreter, kCohDevice, kDie)};
+  const void* die[] = {GC3_ALL_DT(gc3_interpreter, kCohNone, kDie), GC3_ALL_DT(gc3_interpreter, kCohDevice, kDie),
+                       GC3_ALL_DT(gc3_interpreter, kCohDie, kDie)};
   const void* with_stage[] = {GC3_ALL_DT(gc3_interpreter, kCohNone, kStaged), GC3_ALL_DT(gc3_interpreter, kCohDevice, kStaged),
                               GC3_ALL_DT(gc3_interpreter, kCohDie, kStaged)};
   const void* wave[] = {GC3_ALL_DT(gc3_interpreter_wave, kCohNone, kSimple), GC3_ALL_DT(gc3_interpreter_wave, kCohDevice, kSimple),
                         GC3_ALL_DT(gc3_interpreter_wave, kCohDie, kSimple)};
   const void* wave_ll[] = {GC3_ALL_DT(gc3_interpreter_wave, kCohNone, kLL), GC3_ALL_DT(gc3_interpreter_wave, kCohDevice, kLL),
                            GC3_ALL_DT(gc3_interpreter_wave, kCohDie, kLL)};
-  const void* wave_die[] = {GC3_ALL_DT(gc3_interpreter_wave, kCohNone, kDie), GC3_ALL_DT(gc3_interpreter_wave, kCohDevice, kDie)};
+  const void* wave_die[] = {GC3_ALL_DT(gc3_interpreter_wave, kCohNone, kDie), GC3_ALL_DT(gc3_interpreter_wave, kCohDevice, kDie),
+                            GC3_ALL_DT(gc3_interpreter_wave, kCohDie, kDie)};
 #undef GC3_ALL_DT
   auto take = [&](const void* const* fns, int n) -> int {
     for (int i = 0; i < n; ++i) {
@@ -959,8 +962,8 @@ int interpreter_occupancy(unsigned block, int kind, int* out) {
   int e = kind == 1 ? take(with_stage, 9) : take(plain, 18);
   if (e == 0 && kind != 1 && block == 64) e = take(wave, 9);
   if (e == 0 && kind != 1 && block == 64) e = take(wave_ll, 9);
-  if (e == 0 && kind == 2) e = take(die, 6);
-  if (e == 0 && kind == 2 && block == 64) e = take(wave_die, 6);
+  if (e == 0 && kind == 2) e = take(die, 9);
+  if (e == 0 && kind == 2 && block == 64) e = take(wave_die, 9);
   if (e != 0) return e;
   *out = best;
   return 0;

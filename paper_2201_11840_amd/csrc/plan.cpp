@@ -39,7 +39,6 @@ int resolve_config(const gc3_comm_config* cfg_in, gc3_comm_config& cfg, std::str
   if (cfg.fifo_scope < 0 || cfg.fifo_scope > 2) { msg = "fifo_scope must be 0, 1 or 2"; return GC3_ERR_ARG; }
   if (cfg.user_scope == 0) cfg.user_scope = 1;
   if (cfg.user_scope != 1 && cfg.user_scope != 2) { msg = "user_scope must be 0, 1 (device) or 2 (die)"; return GC3_ERR_ARG; }
-  if (cfg.user_scope == 2 && cfg.fifo_scope == 2) { msg = "die-scope FIFOs place lanes on dies, die-scope user buffers place ranks: choose one"; return GC3_ERR_ARG; }
   if (cfg.fifo_scope == 2 && (cfg.lds_stage || cfg.protocol > 1)) {
     msg = "die-scope FIFOs run the simple protocol through registers (protocol 0 or 1, lds_stage 0)";
     return GC3_ERR_ARG;
@@ -235,8 +234,8 @@ int make_plan(const gc3_program& prog, const gc3_comm_config& cfg, int cus, long
     long wgs = pack(W, round_up, &bins, nullptr);
     if (wgs < 0) { msg = "a workgroup would have to multiplex too many thread blocks"; return GC3_ERR_RESIDENCY; }
   }
-  if (cfg.user_scope == 2) {
-    // Die-scope user buffers: bin index = row * (rank count rounded up to a multiple of 8) + rank, with empty bins
+  if (cfg.user_scope == 2 && cfg.fifo_scope != 2) {
+    // Die-scope user buffers (with die-scope FIFOs the lanes are placed on dies instead, which serves both): bin index = row * (rank count rounded up to a multiple of 8) + rank, with empty bins
     // where a rank has fewer than the others.  The grid is lane-major with this many bins per lane, so workgroup
     // index mod 8 = rank mod 8 whatever the number of active lanes, and consecutive workgroups go to consecutive
     // dies: all workgroups of a rank run on one die.

@@ -213,8 +213,7 @@ def test_random_launch_configurations(seed):
                         team_width=int(rng.choice([1, 2, 3, 5, 8, 13, 32])), wg_size=int(rng.choice([64, 128, 256, 512])),
                         target_wgs=int(rng.choice([0, 16, 100, 512])), min_lane_bytes=int(rng.choice([16, 256, 4096, 8192])),
                         fifo_scope=int(rng.choice([0, 2])))
-    if cfg.fifo_scope != 2:
-        cfg.user_scope = int(rng.choice([0, 2]))
+    cfg.user_scope = int(rng.choice([0, 2]))
     unit = 16 // inputs.ITEMSIZE[dtype]
     chunk_elems = int(rng.choice([1, 3, 17, 250, 1031, 4100])) * unit          # 16 B .. 64 KiB per chunk
     exact = prog.collective != "allreduce"
@@ -871,6 +870,14 @@ def test_die_scope_user_buffers(dtype):
     for prog, elems, cfg in cases:
         run_case(prog, dtype, elems, "normal", 1700, cfg, repeats=3)
     run_case(programs.twostep_alltoall(2, 4), dtype, 8 * 20000 * m, "normal", 1701, die(team_width=4, tile_bytes=2048), repeats=2, exact_only=True)
+    # together with die-scope FIFOs: lanes on dies, FIFO payload and user buffers both through the die's L2; a run with
+    # a number of active lanes that is no multiple of 8 falls back to device scope for both
+    for prog, elems, cfg, want_die in [(programs.allpairs_allreduce(8), 8 * 65536 * m, die(fifo_scope=2), True),
+                                       (programs.allpairs_allreduce(8, via_scratch=True), 8 * 40000 * m, die(fifo_scope=2, wg_size=64, team_width=16, target_wgs=4096, min_lane_bytes=2048), True),
+                                       (programs.hierarchical_allreduce(2, 8), 16 * 131072 * m, die(fifo_scope=2), True),
+                                       (programs.hierarchical_allreduce(3, 2, fuse=False), 6 * 20000 * m, die(fifo_scope=2, team_width=24, tile_bytes=8192, min_lane_bytes=512), True),
+                                       (programs.hierarchical_allreduce(2, 3), 6 * 1024 * m, die(fifo_scope=2, team_width=8), False)]:
+        run_case(prog, dtype, elems, "normal", 1703, cfg, repeats=3, expect_die=want_die)
     run_case(programs.allpairs_allreduce(8), dtype, 8 * 4096 * m, "special", 1702, die(wg_size=64), compare=compare_special)
     from tests.test_compiler import _random_program
     from paper_2201_11840_amd.compiler import compile_program

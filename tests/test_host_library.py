@@ -272,10 +272,12 @@ def test_die_scope_user_buffers_place_the_ranks_on_dies():
         assert die.team_width == dev.team_width and die.active_wgs == dev.active_wgs     # the same bins, placed
     # 8 ranks x 7 thread blocks with workgroups of their own: 7 rows of 8, nothing to pad
     assert plan(programs.allpairs_allreduce(8), user_scope=2, wg_size=64, team_width=4).wgs_per_lane == 56
-    for kw in (dict(user_scope=3), dict(user_scope=2, fifo_scope=2)):
-        with pytest.raises(B.Gc3Error) as e:
-            plan(programs.ring_allreduce(4), **kw)
-        assert e.value.status == B.GC3_ERR_ARG
+    with pytest.raises(B.Gc3Error) as e:
+        plan(programs.ring_allreduce(4), user_scope=3)
+    assert e.value.status == B.GC3_ERR_ARG
+    # together with die-scope FIFOs the lanes are placed on dies (bin-major launch), which serves both: no reordering
+    both, fifo = plan(programs.allpairs_allreduce(8), user_scope=2, fifo_scope=2), plan(programs.allpairs_allreduce(8), fifo_scope=2)
+    assert both.user_scope == 2 and (both.wgs_per_lane, both.grid, both.team_width) == (fifo.wgs_per_lane, fifo.grid, fifo.team_width)
 
 
 def test_tune_rejects_bad_sizes_before_touching_a_device():
@@ -342,9 +344,9 @@ def test_kernel_resources_of_the_built_library():
     if not os.path.exists(path):
         pytest.skip("library was built without the resource report")
     kernels = [k for k in json.load(open(path)) if "gc3_interpreter" in k["name"]]
-    # 3 data types x (no dependencies, user buffers at device scope, at die scope) x (simple, LL, LDS staging;
-    # wavefront-level simple and LL), and x (no dependencies, device scope) x die-scope FIFOs (general, wavefront-level)
-    assert len(kernels) == 3 * (3 * 5 + 2 * 2)
+    # 3 data types x (no dependencies, user buffers at device scope, at die scope) x (simple, LL, LDS staging, die-scope
+    # FIFOs; wavefront-level simple, LL and die-scope FIFOs)
+    assert len(kernels) == 3 * 3 * 7
     for k in kernels:
         assert k["scratch_bytes"] == 0, k
         assert k["occupancy"] >= 6, k
@@ -352,7 +354,7 @@ def test_kernel_resources_of_the_built_library():
         assert k["vgprs"] <= 80 and k["lds_bytes"] <= (32768 if staged else 16384), k
     assert sum(k["lds_bytes"] > 16384 for k in kernels) == 9
     wave = [k for k in kernels if "gc3_interpreter_wave" in k["name"]]
-    assert len(wave) == 3 * (3 * 2 + 2) and all(k["lds_bytes"] <= 2048 for k in wave)
+    assert len(wave) == 3 * 3 * 3 and all(k["lds_bytes"] <= 2048 for k in wave)
 
 
 def test_compiler_command_line_writes_loadable_programs(tmp_path):
