@@ -518,8 +518,10 @@ int gc3_comm_status(gc3_comm* comm) {
   if (err != 0) {
     comm->poisoned = true;
     if (-(int)err == GC3_ERR_PLACEMENT)
-      set_error(comm->rank_die ? "die-scope user buffers: the workgroups of a rank did not share a die (results not valid); use user_scope 1"
-                               : "die-scope FIFOs: a receiving workgroup did not run on the die of its sender (run abandoned); use fifo_scope 1");
+      set_error(comm->rank_die && comm->die_scope
+                    ? "die-scope FIFOs and user buffers: workgroups that have to share a die did not (results not valid); use fifo_scope 1 and user_scope 1"
+                    : comm->rank_die ? "die-scope user buffers: the workgroups of a rank did not share a die (results not valid); use user_scope 1"
+                                     : "die-scope FIFOs: a receiving workgroup did not run on the die of its sender (run abandoned); use fifo_scope 1");
     else
       set_error("a workgroup waited longer than the spin limit (run abandoned)");
     return -(int)err;
