@@ -57,6 +57,10 @@ def _pin_suite():
         pins.test_allreduce_integer_values_exact(programs.allpairs_allreduce(4, via_scratch=True), dtype)
     pins.test_alltoall_bytewise(5, "f16")
     pins.test_alltonext_bytewise(2, 2)
+    pins.test_postcondition_definitions_by_hand()
+    for prog in (programs.ring_reduce_scatter(4, instances=2), programs.ring_allgather(3, instances=2)):
+        pins.test_symbolic_postcondition(prog, 2, "round_robin")
+    pins.test_reducescatter_and_allgather_against_their_definitions(4, 2, "f32")
     pins.test_allreduce_fp32_error_bound_and_rank_agreement(programs.ring_allreduce(8, instances=2))
     pins.test_result_independent_of_order_slots_and_fusion("f32")
     pins.test_rrs_leaves_same_final_result()
@@ -140,6 +144,32 @@ NUMERIC_MUTANTS = {
 }
 
 
+POSTCOND_MUTANTS = {
+    "allreduce postcondition forgets rank 0":
+        ("row.append(Counter({(q, j): 1 for q in range(ranks)}))", "row.append(Counter({(q, j): 1 for q in range(1, ranks)}))"),
+    "alltoall postcondition is not transposed":
+        ("row.append(Counter({(src, r * per + k): 1}))", "row.append(Counter({(r, src * per + k): 1}))"),
+    "alltonext postcondition shifts the wrong way":
+        ("row.append(None if r == 0 else Counter({(r - 1, j): 1}))", "row.append(None if r == 0 else Counter({((r + 1) % ranks, j): 1}))"),
+    "alltonext postcondition expects rank 0 to receive":
+        ("row.append(None if r == 0 else Counter({(r - 1, j): 1}))", "row.append(Counter({((r - 1) % ranks, j): 1}))"),
+    "reducescatter postcondition takes interleaved chunks":
+        ("row.append(Counter({(q, r * out_chunks + j): 1 for q in range(ranks)}))", "row.append(Counter({(q, j * ranks + r): 1 for q in range(ranks)}))"),
+    "allgather postcondition is rank-minor":
+        ("row.append(Counter({(j // in_chunks, j % in_chunks): 1}))", "row.append(Counter({(j % ranks, j // ranks): 1}))"),
+    "alltoall definition copies instead of transposing":
+        ("o[j * ce:(j + 1) * ce] = inputs[j][i * ce:(i + 1) * ce]", "o[j * ce:(j + 1) * ce] = inputs[i][j * ce:(j + 1) * ce]"),
+    "alltonext definition keeps the rank's own input":
+        ("outs.append(inputs[i - 1].copy())", "outs.append(inputs[i].copy())"),
+    "allreduce definition skips a rank":
+        ("    for a in inputs:\n        acc += numeric.to_float64(a, dtype)", "    for a in inputs[1:]:\n        acc += numeric.to_float64(a, dtype)"),
+    "reducescatter definition hands out the parts in reverse":
+        ("return [total[r * part:(r + 1) * part].copy() for r in range(R)]", "return [total[(R - 1 - r) * part:(R - r) * part].copy() for r in range(R)]"),
+    "allgather definition concatenates in reverse":
+        ("cat = np.concatenate(list(inputs))", "cat = np.concatenate(list(inputs)[::-1])"),
+}
+
+
 def _expect_caught(what):
     try:
         _pin_suite()
@@ -167,4 +197,15 @@ def test_numeric_mistake_is_caught(what, monkeypatch):
     m = _load_mutant("numeric", old, new)
     for fn in ("add", "f32_to_bf16_bits", "bf16_bits_to_f32", "to_float64"):
         monkeypatch.setattr(oracle.numeric, fn, getattr(m, fn))
+    _expect_caught(what)
+
+
+@pytest.mark.parametrize("what", sorted(POSTCOND_MUTANTS))
+def test_postcondition_mistake_is_caught(what, monkeypatch):
+    # a wrong definition of a collective makes correct programs (or the hand-written tiny cases) fail it
+    old, new = POSTCOND_MUTANTS[what]
+    m = _load_mutant("postcond", old, new)
+    for fn in ("symbolic_expected", "check_symbolic", "allreduce_sum_f64", "alltoall_expected", "alltonext_expected",
+               "reducescatter_sum_f64", "allgather_expected"):
+        monkeypatch.setattr(oracle.postcond, fn, getattr(m, fn))
     _expect_caught(what)
