@@ -170,6 +170,25 @@ POSTCOND_MUTANTS = {
 }
 
 
+IRTEXT_MUTANTS = {
+    "parser swaps source and destination index":
+        ("cur_tb.instrs.append(OInstr(a[0], a[1], int(a[2]), a[3], int(a[4]), int(a[5]),",
+         "cur_tb.instrs.append(OInstr(a[0], a[1], int(a[4]), a[3], int(a[2]), int(a[5]),"),
+    "parser swaps send and receive peer":
+        ("cur_tb = OThreadBlock(int(a[2]), int(a[4]), int(a[6]))", "cur_tb = OThreadBlock(int(a[4]), int(a[2]), int(a[6]))"),
+    "parser drops the channel":
+        ("cur_tb = OThreadBlock(int(a[2]), int(a[4]), int(a[6]))", "cur_tb = OThreadBlock(int(a[2]), int(a[4]), 0)"),
+    "parser reads a dependency as (step, thread block)":
+        ("deps = [(int(a[8 + 2 * k]), int(a[9 + 2 * k])) for k in range(nd)]", "deps = [(int(a[9 + 2 * k]), int(a[8 + 2 * k])) for k in range(nd)]"),
+    "parser ignores count":
+        ("a[3], int(a[4]), int(a[5]),", "a[3], int(a[4]), 1,"),
+    "parser swaps input and output chunk counts":
+        ("p.in_chunks, p.out_chunks = int(a[0]), int(a[1])", "p.out_chunks, p.in_chunks = int(a[0]), int(a[1])"),
+    "parser accepts text without end":
+        ("    if not ended:\n        raise IRError(\"missing end\")\n", ""),
+}
+
+
 def _expect_caught(what):
     try:
         _pin_suite()
@@ -208,4 +227,14 @@ def test_postcondition_mistake_is_caught(what, monkeypatch):
     for fn in ("symbolic_expected", "check_symbolic", "allreduce_sum_f64", "alltoall_expected", "alltonext_expected",
                "reducescatter_sum_f64", "allgather_expected"):
         monkeypatch.setattr(oracle.postcond, fn, getattr(m, fn))
+    _expect_caught(what)
+
+
+@pytest.mark.parametrize("what", sorted(IRTEXT_MUTANTS))
+def test_parser_mistake_is_caught(what, monkeypatch):
+    old, new = IRTEXT_MUTANTS[what]
+    m = _load_mutant("irtext", old, new)
+    m.IRError = oracle.IRError
+    monkeypatch.setattr(oracle, "parse_program", m.parse_program)
+    monkeypatch.setattr(oracle.irtext, "parse_program", m.parse_program)
     _expect_caught(what)

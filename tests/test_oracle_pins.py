@@ -417,6 +417,11 @@ def test_bad_programs_are_reported():
         oracle.parse_program("gc3ir 1\nranks 1\n")
     with pytest.raises(oracle.IRError):
         oracle.parse_program(t.replace("op copy", "op fly"))
+    # a text cut off before its last line is not a program
+    good = _two_rank_prog(["op send i 0 - 0 1 0 0"], ["op recv - 0 o 0 1 0 0"])
+    oracle.run_symbolic(oracle.parse_program(good))
+    with pytest.raises(oracle.IRError):
+        oracle.parse_program(good[:good.rindex("end")])
 
 
 def test_wrong_schedule_fails_postcondition():
